@@ -1,0 +1,193 @@
+/*
+ * kdn.h -- C ABI of the KDN KV-cache movement library for AMD MI355X (gfx950).
+ *
+ * The library moves precomputed KV caches between an inference engine's paged
+ * KV memory and a compact stored form, the data-parallel core of the paper's
+ * Knowledge Delivery Network:
+ *   - kdn_store_chunk   : the engine "stores the KV cache" (Sec. 3.2, interface (i));
+ *                         the stored form is the compressed KV of the delivery
+ *                         module (Sec. 3.1).
+ *   - kdn_load_chunk    : the engine "retrieves the KV cache" (Sec. 3.2, interface
+ *                         (ii)); the KV is decompressed on the GPU (Sec. 3.1).
+ *   - kdn_compose[_batch]: the blending module puts several independently
+ *                         precomputed KV caches together in one context (Sec. 3.1),
+ *                         at positions other than the prefix (Sec. 3, limitation
+ *                         "prefix-only reusing"; Sec. 3.2 "KV-cache blending").
+ * The paper defines no data format or arithmetic; the formats and rules below
+ * are this library's definitions.
+ *
+ * General conventions
+ *   - Pointers marked [device] are HIP device memory on the current device and are
+ *     owned by the caller; pointers marked [host] are ordinary host memory, read
+ *     before the call returns.  The library allocates no KV memory.  It owns only a
+ *     small per-device table store (RoPE cos/sin rows, segment tables), created
+ *     lazily and released by kdn_shutdown().
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All
+ *     work is enqueued on it; calls return after enqueueing; results are valid once
+ *     the stream has been synchronised.
+ *   - Every call returns a kdn_status.  Argument errors are detected on the host
+ *     and reported with nothing enqueued.  Nothing throws or aborts across the ABI.
+ *   - Block ids inside a [device] block table are NOT checked on the fast path: an
+ *     id outside [0, num_blocks) or a destination block listed twice is undefined
+ *     behaviour.  kdn_validate_block_table() is the opt-in check.
+ *   - KV values must be finite.
+ *
+ * Paged cache layout (kdn_cache_desc).  For layer l, side K or V, physical block b,
+ * slot s (token within the block), kv-head h and dimension j the bf16 element is
+ *     base[l*layer_stride + b*block_stride + s*token_stride + h*head_stride + j]
+ * with strides in elements and j contiguous.  Token t of a request whose block
+ * table is bt lives in block bt[t / block_size], slot t % block_size.
+ *
+ * Stored forms (kdn_format).  A chunk stored with Tp tokens is one byte buffer:
+ *   KDN_FMT_RAW_BF16       bf16 [L][2][Tp][H][D]             (side 0 = K, 1 = V)
+ *   KDN_FMT_INT8_ROWSCALE  int8 [L][2][Tp][H][D]  codes, followed at byte
+ *                          L*2*Tp*H*D by fp32 [L][2][Tp][H]  scales,
+ *                          one scale per (token, kv-head) row.
+ * int8 rule per row x[0..D): amax = max|x_j|.  If amax < 2^-121 (this includes the
+ * all-zero row) the scale is 0 and all codes are 0.  Otherwise scale = amax/127,
+ * inv = 127/amax (IEEE fp32 divisions) and code_j = clamp(rint(x_j*inv), -127, 127),
+ * rint rounding halves to even; -128 is never produced.  Dequantisation is the
+ * single fp32 product (float)code_j * scale, rounded to bf16 (nearest even).
+ *
+ * RoPE shift.  Keys carry rotary position embedding with half-split pairing:
+ * element j pairs with j + D/2, j in [0, D/2), at frequency
+ * theta_j = rope_base^(-2j/D).  Shifting a chunk by d positions maps
+ *     lo' = fma(-hi, s_j, lo*c_j),   hi' = fma(lo, s_j, hi*c_j)
+ * in fp32, where c_j = (float)cos(d*theta_j), s_j = (float)sin(d*theta_j) are
+ * evaluated on the host in double as pow(rope_base, -(double)(2*j)/(double)D),
+ * multiplied by (double)d, passed to cos/sin and rounded once to fp32.  A shift of
+ * 0 skips the rotation (bit-identical to a load).  Values are never rotated.
+ */
+#ifndef KDN_H
+#define KDN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    KDN_OK = 0,
+    KDN_EINVAL = -1,       /* NULL pointer, non-positive size, unknown format, shape mismatch */
+    KDN_EALIGN = -2,       /* a base pointer or stride is not 16-byte aligned */
+    KDN_ERANGE = -3,       /* token range outside the block table / chunk, bad block id (validator) */
+    KDN_ESIZE = -4,        /* chunk buffer too small, too many chunks, grid limit exceeded */
+    KDN_EDEVICE = -5,      /* a HIP call failed, or no usable device */
+    KDN_EUNSUPPORTED = -6  /* head_dim not a multiple of 16 or above 512 */
+} kdn_status;
+
+typedef enum {
+    KDN_FMT_RAW_BF16 = 0,
+    KDN_FMT_INT8_ROWSCALE = 1
+} kdn_format;
+
+/* The engine's paged KV memory.  k_base, v_base: [device] bf16, 16-byte aligned;
+ * all strides in elements and multiples of 8. */
+typedef struct {
+    void *k_base;
+    void *v_base;
+    int32_t num_layers, num_kv_heads, head_dim, block_size, num_blocks;
+    int64_t layer_stride, block_stride, token_stride, head_stride;
+} kdn_cache_desc;
+
+/* A stored chunk, or a token view of one.  data: [device], 16-byte aligned, at
+ * least kdn_chunk_bytes(..., parent_tokens, fmt) bytes.  A view covers tokens
+ * [token_start, token_start + num_tokens) of the parent_tokens the buffer holds. */
+typedef struct {
+    void *data;
+    uint64_t bytes;
+    int32_t fmt; /* kdn_format */
+    int32_t num_layers, num_kv_heads, head_dim;
+    int32_t parent_tokens;
+    int32_t token_start;
+    int32_t num_tokens;
+} kdn_chunk;
+
+/* One request of a batched compose: chunks [host array of n_chunks], offsets [host
+ * array of n_chunks RoPE position deltas], the request's block table [device], and
+ * the first request token to write. */
+typedef struct {
+    const kdn_chunk *chunks;
+    const int32_t *offsets;
+    int32_t n_chunks;
+    const int32_t *block_table_dev;
+    int32_t table_len;
+    int32_t dest_token_start;
+} kdn_request;
+
+/* Bytes of a stored chunk of num_tokens tokens: L*2*T*H*D*2 (raw) or L*2*T*H*(D+4)
+ * (int8).  Returns 0 on invalid arguments. */
+uint64_t kdn_chunk_bytes(int32_t num_layers, int32_t num_kv_heads, int32_t head_dim,
+                         int32_t num_tokens, int32_t fmt);
+
+/* Describe a whole stored chunk over a caller-owned buffer (no device work). */
+kdn_status kdn_chunk_init(kdn_chunk *out, void *data_dev, uint64_t bytes, int32_t fmt,
+                          int32_t num_layers, int32_t num_kv_heads, int32_t head_dim,
+                          int32_t num_tokens);
+
+/* View of tokens [token_start, token_start+num_tokens) of `chunk`, relative to the
+ * chunk's own view (no device work).  KDN_ERANGE if the range leaves the chunk. */
+kdn_status kdn_chunk_slice(const kdn_chunk *chunk, int32_t token_start, int32_t num_tokens,
+                           kdn_chunk *out);
+
+/* Store (Sec. 3.2, interface (i)).  Gathers request tokens [token_start,
+ * token_start+num_tokens) through block_table_dev [device, table_len int32 entries]
+ * from the paged cache into out->data in the format out->fmt.  In: out->data,
+ * out->bytes, out->fmt.  Out: the remaining fields of *out (a whole chunk of
+ * num_tokens tokens).  KDN_ESIZE if out->bytes is too small. */
+kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                           int32_t table_len, int32_t token_start, int32_t num_tokens,
+                           kdn_chunk *out, void *stream);
+
+/* Load (Sec. 3.2, interface (ii); decompression on the GPU, Sec. 3.1).  Writes the
+ * chunk view's tokens to request tokens [dest_token_start, dest_token_start +
+ * chunk->num_tokens) of the paged cache.  No rotation.  Slots and blocks outside
+ * that token range are not written. */
+kdn_status kdn_load_chunk(const kdn_chunk *chunk, const kdn_cache_desc *cache,
+                          const int32_t *block_table_dev, int32_t table_len,
+                          int32_t dest_token_start, void *stream);
+
+/* Compose (blending module, Sec. 3.1).  Chunk i is written to request tokens
+ * [dest_token_start + S_i, dest_token_start + S_i + T_i), S_i = sum of T_j, j < i, in
+ * the order given; its K rows are shifted by offsets[i] positions (signed; only the
+ * RoPE delta, independent of placement).  chunks, offsets: [host] arrays of
+ * n_chunks.  Chunks may differ in format.  The first use of a new (rope_base,
+ * head_dim, offset) uploads its cos/sin row synchronously; see kdn_rope_prepare. */
+kdn_status kdn_compose(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                       const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                       int32_t table_len, int32_t dest_token_start, double rope_base,
+                       void *stream);
+
+/* Many independent composes in one launch.  requests: [host] array of n_requests.
+ * Block tables of different requests must not share destination blocks.  The
+ * segment table is copied to the device on `stream` before the kernel. */
+kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
+                             const kdn_cache_desc *cache, double rope_base, void *stream);
+
+/* Make the cos/sin rows of the given offsets resident so that later composes with
+ * them enqueue no copy (needed before capturing composes into a HIP graph).
+ * offsets: [host] array of n. */
+kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *offsets,
+                            int32_t n);
+
+/* Debug check, synchronous: KDN_ERANGE if any of the table_len entries of
+ * block_table_dev [device] is outside [0, num_blocks) or occurs twice. */
+kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t table_len,
+                                    int32_t num_blocks, void *stream);
+
+/* fp32 -> bf16, round to nearest even, n elements, in_dev/out_dev [device], the
+ * conversion every load and compose ends with. */
+kdn_status kdn_f32_to_bf16(const float *in_dev, uint16_t *out_dev, uint64_t n, void *stream);
+
+/* Release the library's device tables on every device (synchronises them). */
+kdn_status kdn_shutdown(void);
+
+const char *kdn_status_str(kdn_status status);
+const char *kdn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KDN_H */

@@ -1,0 +1,904 @@
+// KDN KV-cache movement for MI355X (gfx950): kernels, host planner and the C ABI
+// declared in include/kdn.h.
+//
+// Three data-parallel operations of the paper's Knowledge Delivery Network:
+// store (Sec. 3.2, interface (i)), load (interface (ii), decompression on the GPU,
+// Sec. 3.1) and compose (blending module, Sec. 3.1).  All of them stream rows of
+// head_dim elements between two layouts; none is a contraction, so the kernels are
+// organised around 64-wide wavefronts issuing full-width global loads and stores,
+// and the per-row reductions use cross-lane operations.
+//
+// Work decomposition (both directions): a workgroup owns one (layer, K|V, token
+// group) tile.  A token group is a run of at most G consecutive request tokens that
+// lies inside one paged block, so a tile is contiguous in the paged cache (for the
+// dense layout) and contiguous in the stored chunk.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <mutex>
+#include <new>
+#include <unordered_map>
+#include <vector>
+
+#include "kdn.h"
+
+namespace {
+
+constexpr int kThreads = 256;      // 4 wavefronts per workgroup
+constexpr int kMaxInlineSegs = 64; // segments that travel in the kernel arguments
+constexpr int kMaxHeadDim = 512;
+constexpr int kRopeRowsCap = 4096; // cos/sin rows kept per (base, head_dim)
+constexpr int kSegSlots = 8;       // ring of device segment tables for batched composes
+constexpr size_t kSegSlotBytes = 1u << 20;
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// One placed chunk view: rows of tokens [tok0, tok0+T) of a stored buffer that
+// holds Tp tokens go to request tokens [S, S+T) of the request whose table is bt.
+struct Seg {
+    const uint8_t *data;
+    const int32_t *bt;
+    int32_t Tp, tok0, T, S;
+    int32_t rope_row; // row of the cos/sin table, -1: no rotation
+    int32_t pad;
+};
+static_assert(sizeof(Seg) == 40, "Seg layout");
+
+struct SegsInline {
+    Seg s[kMaxInlineSegs];
+    __device__ const Seg &at(int i) const { return s[i]; }
+};
+struct SegsDevice {
+    const Seg *s;
+    __device__ const Seg &at(int i) const { return s[i]; }
+};
+
+struct CacheP {
+    uint16_t *k, *v;
+    int64_t layer_stride, block_stride, token_stride, head_stride;
+    int32_t L, H, D, bs;
+    int32_t G;     // tokens per group; divides bs
+    int32_t dense; // head_stride == D and token_stride == H*D
+};
+
+struct StoreP {
+    CacheP c;
+    const int32_t *bt;
+    uint8_t *out;
+    int32_t t0, T;
+};
+
+struct PlaceP {
+    CacheP c;
+    const f32x2 *rope; // [rows][D/2] (cos, sin)
+};
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__device__ __forceinline__ float code_f32(uint32_t w, int byte)
+{
+    return (float)(int8_t)(w >> (8 * byte));
+}
+
+constexpr __host__ __device__ int log2_ceil(int x)
+{
+    int l = 0;
+    while ((1 << l) < x)
+        ++l;
+    return l;
+}
+
+// ---------------------------------------------------------------------------------
+// store: gather paged rows, per-row amax, quantise.
+// Lane group: D/8 lanes own one row, 8 consecutive elements (one 16-byte load) each;
+// the group is padded to a power of two so the row reduction is a butterfly.
+template <int DT, int FMT>
+__global__ __launch_bounds__(kThreads) void k_store(StoreP p)
+{
+    const int D = DT ? DT : p.c.D;
+    const int R = D >> 3;
+    const int LOGP = DT ? log2_ceil(DT >> 3) : log2_ceil(R);
+    const int P = 1 << LOGP;
+    const int H = p.c.H, G = p.c.G, bs = p.c.bs;
+
+    const int ls = blockIdx.y;
+    const int gi = p.t0 / G + blockIdx.x;
+    const int tok_lo = max(p.t0, gi * G);
+    const int tok_hi = min(p.t0 + p.T, (gi + 1) * G);
+    if (tok_lo >= tok_hi)
+        return;
+    const int blk = p.bt[tok_lo / bs];
+    const int slot0 = tok_lo % bs;
+    const uint16_t *tile = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(ls >> 1) * p.c.layer_stride
+                           + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
+    const int64_t row_base = ((int64_t)ls * p.T + (tok_lo - p.t0)) * H;
+    const int n_rows = (tok_hi - tok_lo) * H;
+    const int n_items = n_rows << LOGP;
+    const int64_t total_rows = (int64_t)p.c.L * 2 * p.T * H;
+
+    const int sub = threadIdx.x & (P - 1);
+    for (int base = 0; base < n_items; base += kThreads) {
+        const int it = base + threadIdx.x;
+        const int r = it >> LOGP;
+        const bool live = it < n_items && sub < R;
+        uint4 w = {0, 0, 0, 0};
+        if (live) {
+            const uint16_t *src;
+            if (p.c.dense) {
+                src = tile + (int64_t)r * D;
+            } else {
+                const int tok = r / H, h = r - tok * H;
+                src = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
+            }
+            w = *reinterpret_cast<const uint4 *>(src + sub * 8);
+        }
+        const int64_t srow = row_base + r;
+        if (FMT == KDN_FMT_RAW_BF16) {
+            if (live)
+                *reinterpret_cast<uint4 *>(p.out + (srow * D + sub * 8) * 2) = w;
+            continue;
+        }
+        // |x| of a bf16 orders like its low 15 bits
+        const uint32_t a0 = w.x & 0x7fff7fffu, a1 = w.y & 0x7fff7fffu;
+        const uint32_t a2 = w.z & 0x7fff7fffu, a3 = w.w & 0x7fff7fffu;
+        uint32_t m = max(max(a0 & 0xffffu, a0 >> 16), max(a1 & 0xffffu, a1 >> 16));
+        m = max(m, max(max(a2 & 0xffffu, a2 >> 16), max(a3 & 0xffffu, a3 >> 16)));
+        for (int o = 1; o < P; o <<= 1)
+            m = max(m, (uint32_t)__shfl_xor((int)m, o));
+        const float amax = __uint_as_float(m << 16);
+        const bool keep = amax >= 0x1p-121f;
+        const float scale = keep ? amax / 127.0f : 0.0f;
+        const float inv = keep ? 127.0f / amax : 0.0f;
+        if (!live)
+            continue;
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+        uint32_t q[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            uint32_t acc = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t word = ww[2 * i + (e >> 1)];
+                const float x = (e & 1) ? bf16_hi(word) : bf16_lo(word);
+                float rr = __builtin_rintf(x * inv);
+                rr = fminf(fmaxf(rr, -127.0f), 127.0f);
+                acc |= ((uint32_t)(int)rr & 0xffu) << (8 * e);
+            }
+            q[i] = acc;
+        }
+        uint2 qq = {q[0], q[1]};
+        *reinterpret_cast<uint2 *>(p.out + srow * D + sub * 8) = qq;
+        if (sub == 0)
+            *reinterpret_cast<float *>(p.out + total_rows * D + srow * 4) = scale;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// place: dequantise (or copy), rotate K pairs, round to bf16, scatter.
+// Lane group: D/16 lanes own one row; a lane takes 8 elements of the lower half and
+// the 8 elements of the upper half that pair with them, so the rotation needs no
+// exchange between lanes and each lane writes two full 16-byte bf16 vectors.
+template <int DT, int FMT, typename Segs>
+__global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
+{
+    const int D = DT ? DT : p.c.D;
+    const int half = D >> 1;
+    const int R = D >> 4;
+    const int LOGP = DT ? log2_ceil(DT >> 4) : log2_ceil(R);
+    const int P = 1 << LOGP;
+    const int H = p.c.H, G = p.c.G, bs = p.c.bs;
+
+    const Seg &sg = segs.at(blockIdx.z);
+    const int S = sg.S, T = sg.T;
+    const int ls = blockIdx.y;
+    const int gi = S / G + blockIdx.x;
+    const int tok_lo = max(S, gi * G);
+    const int tok_hi = min(S + T, (gi + 1) * G);
+    if (tok_lo >= tok_hi)
+        return;
+    const int blk = sg.bt[tok_lo / bs];
+    const int slot0 = tok_lo % bs;
+    uint16_t *tile = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(ls >> 1) * p.c.layer_stride
+                     + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
+    const int Tp = sg.Tp;
+    const int64_t row_base = ((int64_t)ls * Tp + sg.tok0 + (tok_lo - S)) * H;
+    const int64_t total_rows = (int64_t)p.c.L * 2 * Tp * H;
+    const int n_items = ((tok_hi - tok_lo) * H) << LOGP;
+    const uint8_t *data = sg.data;
+    const bool rotate = (ls & 1) == 0 && sg.rope_row >= 0;
+
+    const int sub = threadIdx.x & (P - 1);
+    __shared__ f32x2 s_cs[kMaxHeadDim / 2];
+    f32x2 cs[8];
+    if (rotate) {
+        const f32x2 *row = p.rope + (int64_t)sg.rope_row * half;
+        for (int i = threadIdx.x; i < half; i += kThreads)
+            s_cs[i] = row[i];
+        __syncthreads();
+        if (sub < R) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                cs[e] = s_cs[sub * 8 + e];
+        }
+    }
+
+    for (int it = threadIdx.x; it < n_items; it += kThreads) {
+        if (sub >= R)
+            continue;
+        const int r = it >> LOGP;
+        const int64_t srow = row_base + r;
+        uint16_t *dst;
+        if (p.c.dense) {
+            dst = tile + (int64_t)r * D + sub * 8;
+        } else {
+            const int tok = r / H, h = r - tok * H;
+            dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride + sub * 8;
+        }
+        float a[8], b[8];
+        if (FMT == KDN_FMT_RAW_BF16) {
+            const uint16_t *src = reinterpret_cast<const uint16_t *>(data) + srow * D + sub * 8;
+            const uint4 lo = *reinterpret_cast<const uint4 *>(src);
+            const uint4 hi = *reinterpret_cast<const uint4 *>(src + half);
+            if (!rotate) { // bit copy
+                *reinterpret_cast<uint4 *>(dst) = lo;
+                *reinterpret_cast<uint4 *>(dst + half) = hi;
+                continue;
+            }
+            const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                a[2 * e] = bf16_lo(lw[e]);
+                a[2 * e + 1] = bf16_hi(lw[e]);
+                b[2 * e] = bf16_lo(hw[e]);
+                b[2 * e + 1] = bf16_hi(hw[e]);
+            }
+        } else {
+            const uint8_t *src = data + srow * D + sub * 8;
+            const uint2 lo = *reinterpret_cast<const uint2 *>(src);
+            const uint2 hi = *reinterpret_cast<const uint2 *>(src + half);
+            const float sc = *reinterpret_cast<const float *>(data + total_rows * D + srow * 4);
+            const uint32_t lw[2] = {lo.x, lo.y}, hw[2] = {hi.x, hi.y};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                a[e] = code_f32(lw[e >> 2], e & 3) * sc;
+                b[e] = code_f32(hw[e >> 2], e & 3) * sc;
+            }
+        }
+        if (rotate) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float c = cs[e].x, s = cs[e].y;
+                const float ac = a[e] * c, bc = b[e] * c;
+                const float lo = __builtin_fmaf(-b[e], s, ac);
+                const float hi = __builtin_fmaf(a[e], s, bc);
+                a[e] = lo;
+                b[e] = hi;
+            }
+        }
+        uint4 olo = {pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(a[4], a[5]),
+                     pack_bf16(a[6], a[7])};
+        uint4 ohi = {pack_bf16(b[0], b[1]), pack_bf16(b[2], b[3]), pack_bf16(b[4], b[5]),
+                     pack_bf16(b[6], b[7])};
+        *reinterpret_cast<uint4 *>(dst) = olo;
+        *reinterpret_cast<uint4 *>(dst + half) = ohi;
+    }
+}
+
+__global__ void k_f32_to_bf16(const float *__restrict__ in, uint16_t *__restrict__ out, uint64_t n)
+{
+    const uint64_t pairs = n >> 1;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < pairs; i += stride) {
+        const f32x2 v = reinterpret_cast<const f32x2 *>(in)[i];
+        reinterpret_cast<uint32_t *>(out)[i] = pack_bf16(v.x, v.y);
+    }
+    if ((n & 1) && blockIdx.x == 0 && threadIdx.x == 0)
+        out[n - 1] = (uint16_t)pack_bf16(in[n - 1], 0.0f);
+}
+
+// flags: bit 0 = id out of range, bit 1 = id seen twice
+__global__ void k_validate(const int32_t *bt, int32_t n, int32_t num_blocks, uint32_t *seen,
+                           uint32_t *flags)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n)
+        return;
+    const int32_t id = bt[i];
+    if (id < 0 || id >= num_blocks) {
+        atomicOr(flags, 1u);
+        return;
+    }
+    if (atomicAdd(&seen[id], 1u) != 0)
+        atomicOr(flags, 2u);
+}
+
+// ---------------------------------------------------------------------------------
+// host planner
+
+struct RopeTable {
+    f32x2 *dev = nullptr;
+    int32_t D = 0;
+    std::unordered_map<int32_t, int32_t> row_of;
+};
+
+struct DeviceState {
+    std::unordered_map<uint64_t, RopeTable> rope; // key: bits of base xor D<<52 ... see rope_key
+    uint8_t *seg_dev = nullptr;                   // kSegSlots * kSegSlotBytes
+    uint8_t *seg_host = nullptr;                  // pinned mirror
+    hipEvent_t seg_done[kSegSlots] = {};
+    bool seg_used[kSegSlots] = {};
+    int next_slot = 0;
+};
+
+std::mutex g_mu;
+std::unordered_map<int, DeviceState> g_dev;
+
+uint64_t rope_key(double base, int32_t D)
+{
+    uint64_t b;
+    std::memcpy(&b, &base, sizeof b);
+    return b * 1000003ull + (uint64_t)D;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+kdn_status check_shape(int32_t L, int32_t H, int32_t D)
+{
+    if (L <= 0 || H <= 0 || D <= 0 || L > 32767)
+        return KDN_EINVAL;
+    if (D % 16 != 0 || D > kMaxHeadDim)
+        return KDN_EUNSUPPORTED;
+    return KDN_OK;
+}
+
+kdn_status check_cache(const kdn_cache_desc *c)
+{
+    if (!c || !c->k_base || !c->v_base)
+        return KDN_EINVAL;
+    kdn_status st = check_shape(c->num_layers, c->num_kv_heads, c->head_dim);
+    if (st != KDN_OK)
+        return st;
+    if (c->block_size <= 0 || c->num_blocks <= 0)
+        return KDN_EINVAL;
+    if (c->head_stride < c->head_dim || c->token_stride < 0 || c->block_stride < 0
+        || c->layer_stride < 0)
+        return KDN_EINVAL;
+    if (!aligned16(c->k_base) || !aligned16(c->v_base) || c->head_stride % 8 || c->token_stride % 8
+        || c->block_stride % 8 || c->layer_stride % 8)
+        return KDN_EALIGN;
+    return KDN_OK;
+}
+
+kdn_status check_chunk(const kdn_chunk *ch, const kdn_cache_desc *c)
+{
+    if (!ch || !ch->data)
+        return KDN_EINVAL;
+    if (ch->fmt != KDN_FMT_RAW_BF16 && ch->fmt != KDN_FMT_INT8_ROWSCALE)
+        return KDN_EINVAL;
+    if (ch->num_layers != c->num_layers || ch->num_kv_heads != c->num_kv_heads
+        || ch->head_dim != c->head_dim)
+        return KDN_EINVAL;
+    if (!aligned16(ch->data))
+        return KDN_EALIGN;
+    if (ch->parent_tokens <= 0 || ch->num_tokens <= 0 || ch->token_start < 0)
+        return KDN_EINVAL;
+    if ((int64_t)ch->token_start + ch->num_tokens > ch->parent_tokens)
+        return KDN_ERANGE;
+    if (ch->bytes < kdn_chunk_bytes(ch->num_layers, ch->num_kv_heads, ch->head_dim,
+                                    ch->parent_tokens, ch->fmt))
+        return KDN_ESIZE;
+    return KDN_OK;
+}
+
+CacheP make_cache_p(const kdn_cache_desc *c)
+{
+    CacheP p;
+    p.k = static_cast<uint16_t *>(c->k_base);
+    p.v = static_cast<uint16_t *>(c->v_base);
+    p.layer_stride = c->layer_stride;
+    p.block_stride = c->block_stride;
+    p.token_stride = c->token_stride;
+    p.head_stride = c->head_stride;
+    p.L = c->num_layers;
+    p.H = c->num_kv_heads;
+    p.D = c->head_dim;
+    p.bs = c->block_size;
+    // token group: a whole block when it is small, else 16-token pieces of it
+    p.G = (c->block_size > 16 && c->block_size % 16 == 0) ? 16 : c->block_size;
+    p.dense = (c->head_stride == c->head_dim
+               && c->token_stride == (int64_t)c->num_kv_heads * c->head_dim);
+    return p;
+}
+
+// number of token groups touched by tokens [s, s+t)
+int64_t groups_spanned(int64_t s, int64_t t, int32_t G) { return (s + t - 1) / G - s / G + 1; }
+
+kdn_status hip_status(hipError_t e) { return e == hipSuccess ? KDN_OK : KDN_EDEVICE; }
+
+DeviceState *device_state(int *dev_out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess)
+        return nullptr;
+    if (dev_out)
+        *dev_out = dev;
+    return &g_dev[dev];
+}
+
+// Returns the cos/sin table of (base, D) and fills rows[i] for offsets[i] (-1 for a
+// zero offset).  New rows are computed in double and uploaded before returning.
+kdn_status rope_rows(DeviceState *ds, double base, int32_t D, const int32_t *offsets, int32_t n,
+                     int32_t *rows, const f32x2 **table)
+{
+    *table = nullptr;
+    bool any = false;
+    for (int32_t i = 0; i < n; ++i)
+        any = any || offsets[i] != 0;
+    if (!any) {
+        for (int32_t i = 0; i < n; ++i)
+            rows[i] = -1;
+        return KDN_OK;
+    }
+    if (!(base > 0.0) || !std::isfinite(base))
+        return KDN_EINVAL;
+    {
+        std::unordered_map<int32_t, int32_t> distinct;
+        for (int32_t i = 0; i < n; ++i)
+            if (offsets[i] != 0)
+                distinct.emplace(offsets[i], 0);
+        if ((int32_t)distinct.size() > kRopeRowsCap)
+            return KDN_ESIZE;
+    }
+    RopeTable &rt = ds->rope[rope_key(base, D)];
+    const int32_t half = D / 2;
+    if (!rt.dev) {
+        if (hipMalloc(reinterpret_cast<void **>(&rt.dev), (size_t)kRopeRowsCap * half * sizeof(f32x2))
+            != hipSuccess)
+            return KDN_EDEVICE;
+        rt.D = D;
+    }
+    std::vector<float> row((size_t)half * 2);
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t d = offsets[i];
+        if (d == 0) {
+            rows[i] = -1;
+            continue;
+        }
+        auto it = rt.row_of.find(d);
+        if (it != rt.row_of.end()) {
+            rows[i] = it->second;
+            continue;
+        }
+        if ((int32_t)rt.row_of.size() >= kRopeRowsCap) {
+            // table full: wait until nothing can still read it, then start over
+            if (hipDeviceSynchronize() != hipSuccess)
+                return KDN_EDEVICE;
+            rt.row_of.clear();
+            for (int32_t k = 0; k < i; ++k) // rows handed out earlier in this call are gone
+                if (offsets[k] != 0)
+                    rows[k] = -2;
+        }
+        for (int32_t j = 0; j < half; ++j) {
+            const double theta = std::pow(base, -(double)(2 * j) / (double)D);
+            const double phi = (double)d * theta;
+            row[2 * j] = (float)std::cos(phi);
+            row[2 * j + 1] = (float)std::sin(phi);
+        }
+        const int32_t r = (int32_t)rt.row_of.size();
+        if (hipMemcpy(rt.dev + (size_t)r * half, row.data(), row.size() * sizeof(float),
+                      hipMemcpyHostToDevice)
+            != hipSuccess)
+            return KDN_EDEVICE;
+        rt.row_of.emplace(d, r);
+        rows[i] = r;
+    }
+    for (int32_t i = 0; i < n; ++i)
+        if (rows[i] == -2) // only after a table reset inside this call
+            return rope_rows(ds, base, D, offsets, n, rows, table);
+    *table = rt.dev;
+    return KDN_OK;
+}
+
+template <int DT, int FMT>
+void launch_store(const StoreP &p, dim3 grid, hipStream_t st)
+{
+    hipLaunchKernelGGL((k_store<DT, FMT>), grid, dim3(kThreads), 0, st, p);
+}
+
+template <int FMT>
+void launch_store_d(const StoreP &p, dim3 grid, hipStream_t st)
+{
+    switch (p.c.D) {
+    case 64: launch_store<64, FMT>(p, grid, st); break;
+    case 128: launch_store<128, FMT>(p, grid, st); break;
+    default: launch_store<0, FMT>(p, grid, st); break;
+    }
+}
+
+template <int DT, int FMT>
+void launch_place(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
+                  hipStream_t st)
+{
+    if (segs_dev) {
+        SegsDevice sd{segs_dev};
+        hipLaunchKernelGGL((k_place<DT, FMT, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+    } else {
+        SegsInline si;
+        std::memset(&si, 0, sizeof si);
+        std::memcpy(si.s, segs, (size_t)n * sizeof(Seg));
+        hipLaunchKernelGGL((k_place<DT, FMT, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+    }
+}
+
+template <int FMT>
+void launch_place_d(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
+                    hipStream_t st)
+{
+    switch (p.c.D) {
+    case 64: launch_place<64, FMT>(p, segs, n, segs_dev, grid, st); break;
+    case 128: launch_place<128, FMT>(p, segs, n, segs_dev, grid, st); break;
+    default: launch_place<0, FMT>(p, segs, n, segs_dev, grid, st); break;
+    }
+}
+
+// Enqueue the placement of `segs` (all of one format).  Up to kMaxInlineSegs travel
+// in the kernel arguments; more go through a ring of device tables.
+kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const std::vector<Seg> &segs,
+                          hipStream_t st)
+{
+    if (segs.empty())
+        return KDN_OK;
+    if (segs.size() > 65535 || segs.size() * sizeof(Seg) > kSegSlotBytes)
+        return KDN_ESIZE;
+    int64_t max_groups = 0;
+    for (const Seg &s : segs)
+        max_groups = std::max(max_groups, groups_spanned(s.S, s.T, p.c.G));
+    if (max_groups > 0x7fffffff / kThreads)
+        return KDN_ESIZE;
+    dim3 grid((unsigned)max_groups, (unsigned)(2 * p.c.L), (unsigned)segs.size());
+
+    const Seg *segs_dev = nullptr;
+    int slot = -1;
+    if ((int)segs.size() > kMaxInlineSegs) {
+        if (!ds->seg_dev) {
+            if (hipMalloc(reinterpret_cast<void **>(&ds->seg_dev), kSegSlots * kSegSlotBytes) != hipSuccess)
+                return KDN_EDEVICE;
+            if (hipHostMalloc(reinterpret_cast<void **>(&ds->seg_host), kSegSlots * kSegSlotBytes,
+                              hipHostMallocDefault)
+                != hipSuccess)
+                return KDN_EDEVICE;
+            for (int i = 0; i < kSegSlots; ++i)
+                if (hipEventCreateWithFlags(&ds->seg_done[i], hipEventDisableTiming) != hipSuccess)
+                    return KDN_EDEVICE;
+        }
+        slot = ds->next_slot;
+        ds->next_slot = (slot + 1) % kSegSlots;
+        if (ds->seg_used[slot] && hipEventSynchronize(ds->seg_done[slot]) != hipSuccess)
+            return KDN_EDEVICE;
+        uint8_t *h = ds->seg_host + (size_t)slot * kSegSlotBytes;
+        uint8_t *d = ds->seg_dev + (size_t)slot * kSegSlotBytes;
+        std::memcpy(h, segs.data(), segs.size() * sizeof(Seg));
+        if (hipMemcpyAsync(d, h, segs.size() * sizeof(Seg), hipMemcpyHostToDevice, st) != hipSuccess)
+            return KDN_EDEVICE;
+        segs_dev = reinterpret_cast<const Seg *>(d);
+    }
+    if (fmt == KDN_FMT_RAW_BF16)
+        launch_place_d<KDN_FMT_RAW_BF16>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
+    else
+        launch_place_d<KDN_FMT_INT8_ROWSCALE>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
+    kdn_status rc = hip_status(hipGetLastError());
+    if (slot >= 0) {
+        if (hipEventRecord(ds->seg_done[slot], st) != hipSuccess)
+            return KDN_EDEVICE;
+        ds->seg_used[slot] = true;
+    }
+    return rc;
+}
+
+kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
+                        double rope_base, void *stream)
+{
+    if (!reqs || n_reqs <= 0)
+        return KDN_EINVAL;
+    kdn_status st = check_cache(cache);
+    if (st != KDN_OK)
+        return st;
+    std::vector<int32_t> offs;
+    for (int32_t r = 0; r < n_reqs; ++r) {
+        const kdn_request &q = reqs[r];
+        if (!q.chunks || !q.offsets || q.n_chunks <= 0 || !q.block_table_dev || q.table_len <= 0
+            || q.dest_token_start < 0)
+            return KDN_EINVAL;
+        int64_t total = q.dest_token_start;
+        for (int32_t i = 0; i < q.n_chunks; ++i) {
+            st = check_chunk(&q.chunks[i], cache);
+            if (st != KDN_OK)
+                return st;
+            total += q.chunks[i].num_tokens;
+            offs.push_back(q.offsets[i]);
+        }
+        if (total > (int64_t)q.table_len * cache->block_size)
+            return KDN_ERANGE;
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *ds = device_state(nullptr);
+    if (!ds)
+        return KDN_EDEVICE;
+    PlaceP p;
+    p.c = make_cache_p(cache);
+    std::vector<int32_t> rows(offs.size());
+    st = rope_rows(ds, rope_base, cache->head_dim, offs.data(), (int32_t)offs.size(), rows.data(), &p.rope);
+    if (st != KDN_OK)
+        return st;
+    std::vector<Seg> segs[2];
+    size_t k = 0;
+    for (int32_t r = 0; r < n_reqs; ++r) {
+        const kdn_request &q = reqs[r];
+        int32_t S = q.dest_token_start;
+        for (int32_t i = 0; i < q.n_chunks; ++i, ++k) {
+            const kdn_chunk &ch = q.chunks[i];
+            Seg s;
+            s.data = static_cast<const uint8_t *>(ch.data);
+            s.bt = q.block_table_dev;
+            s.Tp = ch.parent_tokens;
+            s.tok0 = ch.token_start;
+            s.T = ch.num_tokens;
+            s.S = S;
+            s.rope_row = rows[k];
+            s.pad = 0;
+            segs[ch.fmt].push_back(s);
+            S += ch.num_tokens;
+        }
+    }
+    for (int f = 0; f < 2; ++f) {
+        st = place_segments(ds, p, f, segs[f], static_cast<hipStream_t>(stream));
+        if (st != KDN_OK)
+            return st;
+    }
+    return KDN_OK;
+}
+
+} // namespace
+
+// ---------------------------------------------------------------------------------
+// C ABI
+
+extern "C" {
+
+uint64_t kdn_chunk_bytes(int32_t L, int32_t H, int32_t D, int32_t T, int32_t fmt)
+{
+    if (L <= 0 || H <= 0 || D <= 0 || T <= 0)
+        return 0;
+    const uint64_t rows = (uint64_t)L * 2 * (uint64_t)T * (uint64_t)H;
+    if (fmt == KDN_FMT_RAW_BF16)
+        return rows * (uint64_t)D * 2;
+    if (fmt == KDN_FMT_INT8_ROWSCALE)
+        return rows * ((uint64_t)D + 4);
+    return 0;
+}
+
+kdn_status kdn_chunk_init(kdn_chunk *out, void *data_dev, uint64_t bytes, int32_t fmt, int32_t L,
+                          int32_t H, int32_t D, int32_t T)
+{
+    if (!out || !data_dev || T <= 0)
+        return KDN_EINVAL;
+    if (fmt != KDN_FMT_RAW_BF16 && fmt != KDN_FMT_INT8_ROWSCALE)
+        return KDN_EINVAL;
+    kdn_status st = check_shape(L, H, D);
+    if (st != KDN_OK)
+        return st;
+    if (!aligned16(data_dev))
+        return KDN_EALIGN;
+    if (bytes < kdn_chunk_bytes(L, H, D, T, fmt))
+        return KDN_ESIZE;
+    out->data = data_dev;
+    out->bytes = bytes;
+    out->fmt = fmt;
+    out->num_layers = L;
+    out->num_kv_heads = H;
+    out->head_dim = D;
+    out->parent_tokens = T;
+    out->token_start = 0;
+    out->num_tokens = T;
+    return KDN_OK;
+}
+
+kdn_status kdn_chunk_slice(const kdn_chunk *chunk, int32_t token_start, int32_t num_tokens,
+                           kdn_chunk *out)
+{
+    if (!chunk || !out || num_tokens <= 0 || token_start < 0)
+        return KDN_EINVAL;
+    if ((int64_t)token_start + num_tokens > chunk->num_tokens)
+        return KDN_ERANGE;
+    kdn_chunk v = *chunk;
+    v.token_start = chunk->token_start + token_start;
+    v.num_tokens = num_tokens;
+    *out = v;
+    return KDN_OK;
+}
+
+kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                           int32_t table_len, int32_t token_start, int32_t num_tokens,
+                           kdn_chunk *out, void *stream)
+{
+    kdn_status st = check_cache(cache);
+    if (st != KDN_OK)
+        return st;
+    if (!block_table_dev || !out || !out->data || table_len <= 0 || num_tokens <= 0 || token_start < 0)
+        return KDN_EINVAL;
+    if (out->fmt != KDN_FMT_RAW_BF16 && out->fmt != KDN_FMT_INT8_ROWSCALE)
+        return KDN_EINVAL;
+    if (!aligned16(out->data))
+        return KDN_EALIGN;
+    if ((int64_t)token_start + num_tokens > (int64_t)table_len * cache->block_size)
+        return KDN_ERANGE;
+    const uint64_t need = kdn_chunk_bytes(cache->num_layers, cache->num_kv_heads, cache->head_dim,
+                                          num_tokens, out->fmt);
+    if (out->bytes < need)
+        return KDN_ESIZE;
+    StoreP p;
+    p.c = make_cache_p(cache);
+    p.bt = block_table_dev;
+    p.out = static_cast<uint8_t *>(out->data);
+    p.t0 = token_start;
+    p.T = num_tokens;
+    const int64_t groups = groups_spanned(token_start, num_tokens, p.c.G);
+    if (groups > 0x7fffffff / kThreads)
+        return KDN_ESIZE;
+    dim3 grid((unsigned)groups, (unsigned)(2 * p.c.L), 1);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (out->fmt == KDN_FMT_RAW_BF16)
+        launch_store_d<KDN_FMT_RAW_BF16>(p, grid, hs);
+    else
+        launch_store_d<KDN_FMT_INT8_ROWSCALE>(p, grid, hs);
+    st = hip_status(hipGetLastError());
+    if (st != KDN_OK)
+        return st;
+    out->num_layers = cache->num_layers;
+    out->num_kv_heads = cache->num_kv_heads;
+    out->head_dim = cache->head_dim;
+    out->parent_tokens = num_tokens;
+    out->token_start = 0;
+    out->num_tokens = num_tokens;
+    return KDN_OK;
+}
+
+kdn_status kdn_load_chunk(const kdn_chunk *chunk, const kdn_cache_desc *cache,
+                          const int32_t *block_table_dev, int32_t table_len,
+                          int32_t dest_token_start, void *stream)
+{
+    const int32_t zero = 0;
+    kdn_request q = {chunk, &zero, 1, block_table_dev, table_len, dest_token_start};
+    if (!chunk)
+        return KDN_EINVAL;
+    return compose_impl(&q, 1, cache, 1.0, stream);
+}
+
+kdn_status kdn_compose(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                       const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                       int32_t table_len, int32_t dest_token_start, double rope_base, void *stream)
+{
+    kdn_request q = {chunks, offsets, n_chunks, block_table_dev, table_len, dest_token_start};
+    return compose_impl(&q, 1, cache, rope_base, stream);
+}
+
+kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
+                             const kdn_cache_desc *cache, double rope_base, void *stream)
+{
+    return compose_impl(requests, n_requests, cache, rope_base, stream);
+}
+
+kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *offsets, int32_t n)
+{
+    if (!offsets || n <= 0)
+        return KDN_EINVAL;
+    kdn_status st = check_shape(1, 1, head_dim);
+    if (st != KDN_OK)
+        return st;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *ds = device_state(nullptr);
+    if (!ds)
+        return KDN_EDEVICE;
+    std::vector<int32_t> rows((size_t)n);
+    const f32x2 *table;
+    return rope_rows(ds, rope_base, head_dim, offsets, n, rows.data(), &table);
+}
+
+kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t table_len,
+                                    int32_t num_blocks, void *stream)
+{
+    if (!block_table_dev || table_len <= 0 || num_blocks <= 0)
+        return KDN_EINVAL;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    uint32_t *scratch = nullptr;
+    const size_t bytes = ((size_t)num_blocks + 1) * sizeof(uint32_t);
+    if (hipMalloc(reinterpret_cast<void **>(&scratch), bytes) != hipSuccess)
+        return KDN_EDEVICE;
+    kdn_status rc = KDN_OK;
+    uint32_t flags = 0;
+    if (hipMemsetAsync(scratch, 0, bytes, hs) != hipSuccess)
+        rc = KDN_EDEVICE;
+    if (rc == KDN_OK) {
+        hipLaunchKernelGGL(k_validate, dim3((table_len + 255) / 256), dim3(256), 0, hs, block_table_dev,
+                           table_len, num_blocks, scratch + 1, scratch);
+        if (hipGetLastError() != hipSuccess
+            || hipMemcpyAsync(&flags, scratch, sizeof flags, hipMemcpyDeviceToHost, hs) != hipSuccess
+            || hipStreamSynchronize(hs) != hipSuccess)
+            rc = KDN_EDEVICE;
+    }
+    (void)hipFree(scratch);
+    if (rc != KDN_OK)
+        return rc;
+    return flags ? KDN_ERANGE : KDN_OK;
+}
+
+kdn_status kdn_f32_to_bf16(const float *in_dev, uint16_t *out_dev, uint64_t n, void *stream)
+{
+    if (!in_dev || !out_dev)
+        return KDN_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(in_dev) & 7u) || (reinterpret_cast<uintptr_t>(out_dev) & 3u))
+        return KDN_EALIGN;
+    if (n == 0)
+        return KDN_OK;
+    const uint64_t pairs = (n + 1) / 2;
+    const unsigned blocks = (unsigned)std::min<uint64_t>((pairs + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(k_f32_to_bf16, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       in_dev, out_dev, n);
+    return hip_status(hipGetLastError());
+}
+
+kdn_status kdn_shutdown(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    int cur = 0;
+    (void)hipGetDevice(&cur);
+    kdn_status rc = KDN_OK;
+    for (auto &kv : g_dev) {
+        if (hipSetDevice(kv.first) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+            rc = KDN_EDEVICE;
+            continue;
+        }
+        DeviceState &ds = kv.second;
+        for (auto &rt : ds.rope)
+            if (rt.second.dev)
+                (void)hipFree(rt.second.dev);
+        if (ds.seg_dev)
+            (void)hipFree(ds.seg_dev);
+        if (ds.seg_host)
+            (void)hipHostFree(ds.seg_host);
+        for (int i = 0; i < kSegSlots; ++i)
+            if (ds.seg_done[i])
+                (void)hipEventDestroy(ds.seg_done[i]);
+    }
+    g_dev.clear();
+    (void)hipSetDevice(cur);
+    return rc;
+}
+
+const char *kdn_status_str(kdn_status s)
+{
+    switch (s) {
+    case KDN_OK: return "ok";
+    case KDN_EINVAL: return "invalid argument";
+    case KDN_EALIGN: return "pointer or stride not 16-byte aligned";
+    case KDN_ERANGE: return "token range or block id out of range";
+    case KDN_ESIZE: return "buffer too small or too many segments";
+    case KDN_EDEVICE: return "HIP call failed";
+    case KDN_EUNSUPPORTED: return "head_dim must be a multiple of 16, at most 512";
+    }
+    return "unknown status";
+}
+
+const char *kdn_version(void) { return "kdn-gfx950 0.1"; }
+
+} // extern "C"

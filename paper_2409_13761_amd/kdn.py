@@ -1,0 +1,301 @@
+"""Thin Python binding of the C ABI in include/kdn.h.
+
+Argument marshalling only: every step of store / load / compose runs in the HIP
+kernels of libkdn.so.  PyTorch supplies device memory (tensors) and streams.
+There is no CPU fallback: if the library is missing or was not built, importing
+this module's entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libkdn.so")
+
+FMT_RAW_BF16 = 0
+FMT_INT8_ROWSCALE = 1
+
+OK, EINVAL, EALIGN, ERANGE, ESIZE, EDEVICE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+
+
+class KdnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (%d)" % (where, status_str(status), status))
+
+
+class CacheDesc(C.Structure):
+    _fields_ = [("k_base", C.c_void_p), ("v_base", C.c_void_p),
+                ("num_layers", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("block_size", C.c_int32), ("num_blocks", C.c_int32),
+                ("layer_stride", C.c_int64), ("block_stride", C.c_int64),
+                ("token_stride", C.c_int64), ("head_stride", C.c_int64)]
+
+
+class ChunkDesc(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("bytes", C.c_uint64), ("fmt", C.c_int32),
+                ("num_layers", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("parent_tokens", C.c_int32), ("token_start", C.c_int32), ("num_tokens", C.c_int32)]
+
+
+class RequestDesc(C.Structure):
+    _fields_ = [("chunks", C.POINTER(ChunkDesc)), ("offsets", C.POINTER(C.c_int32)),
+                ("n_chunks", C.c_int32), ("block_table_dev", C.c_void_p),
+                ("table_len", C.c_int32), ("dest_token_start", C.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libkdn.so (built beforehand by build.build_library / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libkdn.so is not built: run `python -m paper_2409_13761_amd.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+        L.kdn_chunk_bytes.restype = u64
+        L.kdn_chunk_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.kdn_chunk_init.restype = C.c_int
+        L.kdn_chunk_init.argtypes = [C.POINTER(ChunkDesc), vp, u64, i32, i32, i32, i32, i32]
+        L.kdn_chunk_slice.restype = C.c_int
+        L.kdn_chunk_slice.argtypes = [C.POINTER(ChunkDesc), i32, i32, C.POINTER(ChunkDesc)]
+        L.kdn_store_chunk.restype = C.c_int
+        L.kdn_store_chunk.argtypes = [C.POINTER(CacheDesc), vp, i32, i32, i32, C.POINTER(ChunkDesc), vp]
+        L.kdn_load_chunk.restype = C.c_int
+        L.kdn_load_chunk.argtypes = [C.POINTER(ChunkDesc), C.POINTER(CacheDesc), vp, i32, i32, vp]
+        L.kdn_compose.restype = C.c_int
+        L.kdn_compose.argtypes = [C.POINTER(ChunkDesc), C.POINTER(i32), i32, C.POINTER(CacheDesc),
+                                  vp, i32, i32, C.c_double, vp]
+        L.kdn_compose_batch.restype = C.c_int
+        L.kdn_compose_batch.argtypes = [C.POINTER(RequestDesc), i32, C.POINTER(CacheDesc),
+                                        C.c_double, vp]
+        L.kdn_rope_prepare.restype = C.c_int
+        L.kdn_rope_prepare.argtypes = [C.c_double, i32, C.POINTER(i32), i32]
+        L.kdn_validate_block_table.restype = C.c_int
+        L.kdn_validate_block_table.argtypes = [vp, i32, i32, vp]
+        L.kdn_f32_to_bf16.restype = C.c_int
+        L.kdn_f32_to_bf16.argtypes = [vp, vp, u64, vp]
+        L.kdn_shutdown.restype = C.c_int
+        L.kdn_shutdown.argtypes = []
+        L.kdn_status_str.restype = C.c_char_p
+        L.kdn_status_str.argtypes = [C.c_int]
+        L.kdn_version.restype = C.c_char_p
+        L.kdn_version.argtypes = []
+        _ = i64
+        _lib = L
+    return _lib
+
+
+EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk",
+           "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_rope_prepare",
+           "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
+           "kdn_version"]
+
+
+def status_str(status: int) -> str:
+    return lib().kdn_status_str(status).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != OK:
+        raise KdnError(status, where)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+# ------------------------------------------------------------------ descriptors
+@dataclass
+class PagedCache:
+    """An engine's paged KV memory held in two bf16 tensors shaped
+    [L][num_blocks][block_size][H][D] (last dimension contiguous)."""
+    k: torch.Tensor
+    v: torch.Tensor
+
+    def __post_init__(self):
+        for t in (self.k, self.v):
+            assert t.dtype == torch.bfloat16 and t.dim() == 5 and t.stride(4) == 1
+        assert self.k.shape == self.v.shape and self.k.stride() == self.v.stride()
+
+    @property
+    def shape(self):
+        L, nb, bs, H, D = self.k.shape
+        return L, nb, bs, H, D
+
+    def desc(self) -> CacheDesc:
+        L, nb, bs, H, D = self.k.shape
+        s = self.k.stride()
+        return CacheDesc(self.k.data_ptr(), self.v.data_ptr(), L, H, D, bs, nb,
+                         s[0], s[1], s[2], s[3])
+
+
+class Chunk:
+    """A stored chunk (or token view) over a uint8 device tensor."""
+
+    def __init__(self, data: torch.Tensor, desc: ChunkDesc):
+        self.data, self.desc = data, desc
+
+    @property
+    def fmt(self) -> int:
+        return self.desc.fmt
+
+    @property
+    def num_tokens(self) -> int:
+        return self.desc.num_tokens
+
+    def slice(self, token_start: int, num_tokens: int) -> "Chunk":
+        return chunk_slice(self, token_start, num_tokens)
+
+    def _split(self):
+        d = self.desc
+        n = d.num_layers * 2 * d.parent_tokens * d.num_kv_heads * d.head_dim
+        return d, n
+
+    def codes(self) -> torch.Tensor:
+        d, n = self._split()
+        assert d.fmt == FMT_INT8_ROWSCALE
+        return self.data[:n].view(torch.int8).view(d.num_layers, 2, d.parent_tokens,
+                                                   d.num_kv_heads, d.head_dim)
+
+    def scales(self) -> torch.Tensor:
+        d, n = self._split()
+        assert d.fmt == FMT_INT8_ROWSCALE
+        return self.data[n:n + n // d.head_dim * 4].view(torch.float32).view(
+            d.num_layers, 2, d.parent_tokens, d.num_kv_heads)
+
+    def raw(self) -> torch.Tensor:
+        d, n = self._split()
+        assert d.fmt == FMT_RAW_BF16
+        return self.data[:2 * n].view(torch.bfloat16).view(d.num_layers, 2, d.parent_tokens,
+                                                           d.num_kv_heads, d.head_dim)
+
+
+# ------------------------------------------------------------------ calls
+def kdn_chunk_bytes(L: int, H: int, D: int, num_tokens: int, fmt: int) -> int:
+    return int(lib().kdn_chunk_bytes(L, H, D, num_tokens, fmt))
+
+
+def alloc_chunk(cache: PagedCache, num_tokens: int, fmt: int) -> Chunk:
+    """Allocate the device buffer of a chunk with torch and describe it."""
+    L, _, _, H, D = cache.shape
+    n = kdn_chunk_bytes(L, H, D, num_tokens, fmt)
+    if n == 0:
+        raise KdnError(EINVAL, "kdn_chunk_bytes")
+    data = torch.empty(n, dtype=torch.uint8, device=cache.k.device)
+    d = ChunkDesc()
+    _check(lib().kdn_chunk_init(C.byref(d), data.data_ptr(), n, fmt, L, H, D, num_tokens),
+           "kdn_chunk_init")
+    return Chunk(data, d)
+
+
+def chunk_from_buffer(data: torch.Tensor, fmt: int, L: int, H: int, D: int, num_tokens: int) -> Chunk:
+    d = ChunkDesc()
+    _check(lib().kdn_chunk_init(C.byref(d), data.data_ptr(), data.numel() * data.element_size(),
+                                fmt, L, H, D, num_tokens), "kdn_chunk_init")
+    return Chunk(data, d)
+
+
+def chunk_slice(chunk: Chunk, token_start: int, num_tokens: int) -> Chunk:
+    d = ChunkDesc()
+    _check(lib().kdn_chunk_slice(C.byref(chunk.desc), token_start, num_tokens, C.byref(d)),
+           "kdn_chunk_slice")
+    return Chunk(chunk.data, d)
+
+
+def kdn_store_chunk(cache: PagedCache, block_table: torch.Tensor, token_start: int,
+                    num_tokens: int, out: Chunk, stream=None) -> Chunk:
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous()
+    cd = cache.desc()
+    _check(lib().kdn_store_chunk(C.byref(cd), block_table.data_ptr(), block_table.numel(),
+                                 token_start, num_tokens, C.byref(out.desc), _stream(stream)),
+           "kdn_store_chunk")
+    return out
+
+
+def kdn_load_chunk(chunk: Chunk, cache: PagedCache, block_table: torch.Tensor,
+                   dest_token_start: int = 0, stream=None) -> None:
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous()
+    cd = cache.desc()
+    _check(lib().kdn_load_chunk(C.byref(chunk.desc), C.byref(cd), block_table.data_ptr(),
+                                block_table.numel(), dest_token_start, _stream(stream)),
+           "kdn_load_chunk")
+
+
+def _chunk_array(chunks):
+    arr = (ChunkDesc * len(chunks))()
+    for i, c in enumerate(chunks):
+        arr[i] = c.desc
+    return arr
+
+
+def kdn_compose(chunks, offsets, cache: PagedCache, block_table: torch.Tensor, rope_base: float,
+                dest_token_start: int = 0, stream=None) -> None:
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous()
+    assert len(chunks) == len(offsets)
+    cd = cache.desc()
+    arr = _chunk_array(chunks)
+    off = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
+    _check(lib().kdn_compose(arr, off, len(chunks), C.byref(cd), block_table.data_ptr(),
+                             block_table.numel(), dest_token_start, float(rope_base),
+                             _stream(stream)), "kdn_compose")
+
+
+class BatchPlan:
+    """Marshalled arguments of a batched compose, reusable across calls."""
+
+    def __init__(self, requests):
+        """requests: list of (chunks, offsets, block_table, dest_token_start)."""
+        self._keep = []
+        self.arr = (RequestDesc * len(requests))()
+        for i, (chunks, offsets, bt, dest) in enumerate(requests):
+            assert bt.dtype == torch.int32 and bt.is_contiguous() and len(chunks) == len(offsets)
+            ca = _chunk_array(chunks)
+            oa = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
+            self._keep += [ca, oa, bt, chunks]
+            self.arr[i] = RequestDesc(ca, oa, len(chunks), bt.data_ptr(), bt.numel(), int(dest))
+        self.n = len(requests)
+
+
+def kdn_compose_batch(plan_or_requests, cache: PagedCache, rope_base: float, stream=None) -> None:
+    plan = plan_or_requests if isinstance(plan_or_requests, BatchPlan) else BatchPlan(plan_or_requests)
+    cd = cache.desc()
+    _check(lib().kdn_compose_batch(plan.arr, plan.n, C.byref(cd), float(rope_base), _stream(stream)),
+           "kdn_compose_batch")
+
+
+def kdn_rope_prepare(rope_base: float, head_dim: int, offsets) -> None:
+    off = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
+    _check(lib().kdn_rope_prepare(float(rope_base), head_dim, off, len(offsets)), "kdn_rope_prepare")
+
+
+def kdn_validate_block_table(block_table: torch.Tensor, num_blocks: int, stream=None) -> int:
+    """Returns the status (OK or ERANGE) instead of raising."""
+    return int(lib().kdn_validate_block_table(block_table.data_ptr(), block_table.numel(),
+                                              num_blocks, _stream(stream)))
+
+
+def kdn_f32_to_bf16(x: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+    assert x.dtype == torch.float32 and x.is_contiguous()
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.bfloat16, device=x.device)
+    _check(lib().kdn_f32_to_bf16(x.data_ptr(), out.data_ptr(), x.numel(), _stream(stream)),
+           "kdn_f32_to_bf16")
+    return out
+
+
+def kdn_shutdown() -> None:
+    _check(lib().kdn_shutdown(), "kdn_shutdown")
+
+
+def kdn_version() -> str:
+    return lib().kdn_version().decode()

@@ -1,0 +1,284 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element, on the same seeded inputs.  Sizes span several tiles and ragged tails.
+
+Bars: stored codes, scales, raw copies, placement and all V outputs bit-exact;
+RoPE-shifted K within 1e-2 absolute for N(0,1) inputs (and, as the design
+target, without a differing bit)."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import (INT8, RAW, assert_cache_equal, assert_chunk_equal, bits_of, chunk_to_dev,
+                     dev_cache, dev_table, host_cache, to_dev_bf16)
+from oracle import kdn_oracle as O
+from paper_2409_13761_amd import kdn, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+# ------------------------------------------------------------------ store
+@pytest.mark.parametrize("fmt", [RAW, INT8])
+@pytest.mark.parametrize("shape", [
+    # L, nb, bs, H, D, t0, T
+    (2, 24, 16, 4, 64, 0, 128),        # block aligned, several tiles
+    (2, 24, 16, 4, 64, 5, 150),        # starts and ends inside a block
+    (3, 40, 16, 8, 128, 17, 301),      # 8B-like rows, ragged
+    (1, 64, 1, 2, 128, 3, 50),         # block of one token
+    (2, 12, 32, 2, 64, 9, 300),        # block larger than the token group
+    (2, 12, 24, 3, 32, 7, 200),        # block size not a multiple of 16
+    (1, 20, 16, 1, 16, 0, 97),         # smallest head_dim
+    (1, 20, 8, 2, 96, 3, 100),         # head_dim whose lane group is padded
+    (1, 10, 16, 2, 256, 1, 77),
+    (1, 6, 16, 1, 512, 0, 40),         # largest head_dim
+])
+def test_store_matches_oracle(fmt, shape):
+    L, nb, bs, H, D, t0, T = shape
+    _say("store fmt=%d shape=%s" % (fmt, shape))
+    hc = host_cache(100 + D + bs, L, nb, bs, H, D)
+    n_tab = (t0 + T + bs - 1) // bs
+    bt = synth.disjoint_block_tables(3, nb, [n_tab])[0]
+    want = O.store(hc, bt, t0, T, fmt)
+    dc = dev_cache(hc)
+    out = kdn.alloc_chunk(dc, T, fmt)
+    out.data.fill_(0xAB)
+    kdn.kdn_store_chunk(dc, dev_table(bt), t0, T, out)
+    assert_chunk_equal(out, want)
+    assert (out.desc.parent_tokens, out.desc.token_start, out.desc.num_tokens) == (T, 0, T)
+
+
+def test_store_special_rows():
+    """Zero rows, -0, rows under the 2^-121 threshold, fp32-denormal scales, huge rows,
+    exact ties; and every positive finite bf16 as a row's amax."""
+    L, nb, bs, H, D = 1, 2100, 16, 1, 16
+    k = np.zeros((L, nb, bs, H, D), dtype=np.uint16)
+    rows = k.reshape(-1, D)
+    # every positive finite bf16 once as amax, with companions at fixed ratios
+    amax_bits = np.arange(1, 0x7F80, dtype=np.uint16)
+    n = amax_bits.size
+    rows[:n, 0] = amax_bits
+    f = (amax_bits.astype(np.uint32) << 16).view(np.float32)
+    for j, ratio in enumerate((0.5, -0.25, 0.75, -0.999, 0.0039, 0.3333, -0.0117), start=1):
+        rows[:n, j] = bits_of(torch.from_numpy((f * np.float32(ratio)).astype(np.float32)).to(torch.bfloat16))
+    rows[n, 3] = 0x8000                                   # row of zeros with one -0
+    rows[n + 1, :] = 0x02FF                               # under the threshold everywhere
+    rows[n + 2, :4] = [0x0300, 0x8300, 0x0280, 0x0001]    # exactly 2^-121
+    ties = torch.tensor([127.0, 63.5, -63.5, 0.5, -0.5, 1.5, 2.5, -2.5, 126.5, -126.5, 3.5, 0, 0, 0, 0, 0])
+    rows[n + 3] = bits_of(ties.to(torch.bfloat16))
+    v = synth.normal_bf16(5, k.shape)
+    hc = O.PagedCache(k, v)
+    T = nb * bs
+    bt = np.arange(nb, dtype=np.int32)
+    want = O.store(hc, bt, 0, T, INT8)
+    dc = dev_cache(hc)
+    out = kdn.alloc_chunk(dc, T, INT8)
+    kdn.kdn_store_chunk(dc, dev_table(bt), 0, T, out)
+    assert_chunk_equal(out, want)
+    sc = out.scales().cpu().numpy()[0, 0, :, 0]
+    assert sc[n] == 0 and sc[n + 1] == 0 and sc[n + 2] > 0
+    # and the special rows load back bit-exactly as the oracle says
+    hd = O.PagedCache(np.zeros_like(k), np.zeros_like(v))
+    O.load(want, hd, bt, 0)
+    dd = dev_cache(O.PagedCache(np.zeros_like(k), np.zeros_like(v)))
+    kdn.kdn_load_chunk(out, dd, dev_table(bt), 0)
+    assert_cache_equal(dd, hd)
+
+
+def test_store_strided_cache():
+    """Paged memory with padded token and head strides (a view of a larger tensor)."""
+    L, nb, bs, H, D = 2, 10, 16, 3, 64
+    hc = host_cache(7, L, nb, bs, H, D)
+    bt = synth.disjoint_block_tables(7, nb, [6])[0]
+    want = O.store(hc, bt, 3, 80, INT8)
+    big_k = torch.zeros((L, nb, bs, H + 2, D + 16), dtype=torch.bfloat16, device="cuda")
+    big_v = torch.zeros_like(big_k)
+    big_k[:, :, :, :H, :D] = to_dev_bf16(hc.k)
+    big_v[:, :, :, :H, :D] = to_dev_bf16(hc.v)
+    dc = kdn.PagedCache(big_k[:, :, :, :H, :D], big_v[:, :, :, :H, :D])
+    out = kdn.alloc_chunk(dc, 80, INT8)
+    kdn.kdn_store_chunk(dc, dev_table(bt), 3, 80, out)
+    assert_chunk_equal(out, want)
+    # and the way back into the padded layout touches no padding
+    dst_bt = synth.disjoint_block_tables(8, nb, [6])[0]
+    hd = host_cache(9, L, nb, bs, H, D)
+    O.compose([want], [40], hd, dst_bt, 10000.0, dest=5)
+    big_k.fill_(0), big_v.fill_(0)
+    hd0 = host_cache(9, L, nb, bs, H, D)
+    big_k[:, :, :, :H, :D] = to_dev_bf16(hd0.k)
+    big_v[:, :, :, :H, :D] = to_dev_bf16(hd0.v)
+    kdn.kdn_compose([out], [40], dc, dev_table(dst_bt), 10000.0, dest_token_start=5)
+    assert_cache_equal(kdn.PagedCache(big_k[:, :, :, :H, :D].contiguous(), big_v[:, :, :, :H, :D].contiguous()), hd)
+    assert float(big_k[:, :, :, H:, :].abs().max()) == 0 and float(big_k[..., D:].abs().max()) == 0
+
+
+# ------------------------------------------------------------------ load / compose
+@pytest.mark.parametrize("fmt", [RAW, INT8])
+@pytest.mark.parametrize("shape", [
+    # L, nb, bs, H, D, dest, T
+    (2, 24, 16, 4, 64, 0, 128),
+    (2, 24, 16, 4, 64, 7, 150),
+    (3, 40, 16, 8, 128, 21, 301),
+    (1, 64, 1, 2, 128, 3, 50),
+    (2, 12, 32, 2, 64, 9, 300),
+    (2, 12, 24, 3, 32, 7, 200),
+    (1, 20, 16, 1, 16, 0, 97),
+    (1, 20, 8, 2, 96, 3, 100),
+    (1, 10, 16, 2, 256, 1, 77),
+    (1, 6, 16, 1, 512, 0, 40),
+])
+def test_load_matches_oracle_and_touches_nothing_else(fmt, shape):
+    L, nb, bs, H, D, dest, T = shape
+    _say("load fmt=%d shape=%s" % (fmt, shape))
+    src = host_cache(200 + D, L, nb, bs, H, D)
+    n_src = (T + bs - 1) // bs
+    n_dst = (dest + T + bs - 1) // bs
+    if n_src + n_dst > nb:
+        src_bt = synth.disjoint_block_tables(4, nb, [n_src])[0]
+        dst_bt = synth.disjoint_block_tables(5, nb, [n_dst])[0]
+    else:
+        src_bt, dst_bt = synth.disjoint_block_tables(4, nb, [n_src, n_dst])
+    ch = O.store(src, src_bt, 0, T, fmt)
+    hd = host_cache(300 + D, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.load(ch, hd, dst_bt, dest)
+    kdn.kdn_load_chunk(chunk_to_dev(ch), dd, dev_table(dst_bt), dest)
+    assert_cache_equal(dd, hd)
+
+
+@pytest.mark.parametrize("fmt", [RAW, INT8])
+@pytest.mark.parametrize("D,base", [(64, 10000.0), (128, 500000.0), (96, 10000.0), (16, 10000.0), (256, 1e6)])
+def test_compose_ragged_chunks_with_offsets(fmt, D, base):
+    L, nb, bs, H = 2, 64, 16, 2
+    _say("compose fmt=%d D=%d" % (fmt, D))
+    src = host_cache(400 + D, L, nb, bs, H, D)
+    t1, t2, t3, t4, dst_bt = synth.disjoint_block_tables(11, nb, [4, 3, 5, 2, 16])
+    chunks = [O.store(src, t1, 0, 61, fmt), O.store(src, t2, 2, 40, fmt),
+              O.store(src, t3, 5, 70, fmt), O.store(src, t4, 0, 17, fmt)]
+    offsets = [0, 61, -33, 100000]
+    hd = host_cache(500 + D, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose(chunks, offsets, hd, dst_bt, base, dest=9)
+    kdn.kdn_compose([chunk_to_dev(c) for c in chunks], offsets, dd, dev_table(dst_bt), base,
+                    dest_token_start=9)
+    assert_cache_equal(dd, hd)
+
+
+def test_compose_mixed_formats_and_slices():
+    L, nb, bs, H, D = 2, 48, 16, 4, 64
+    src = host_cache(21, L, nb, bs, H, D)
+    a, b, dst_bt = synth.disjoint_block_tables(21, nb, [10, 6, 14])
+    whole = O.store(src, a, 0, 160, INT8)
+    rawc = O.store(src, b, 3, 90, RAW)
+    chunks = [whole.slice(100, 50), rawc.slice(10, 33), whole.slice(0, 64), rawc.slice(0, 10)]
+    offsets = [7, 0, 50, -90]
+    hd = host_cache(22, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose(chunks, offsets, hd, dst_bt, 10000.0, dest=1)
+    dw, dr = chunk_to_dev(whole), chunk_to_dev(rawc)
+    dchunks = [dw.slice(100, 50), dr.slice(10, 33), dw.slice(0, 64), dr.slice(0, 10)]
+    kdn.kdn_compose(dchunks, offsets, dd, dev_table(dst_bt), 10000.0, dest_token_start=1)
+    assert_cache_equal(dd, hd)
+
+
+def test_zero_offset_compose_is_bitwise_the_loads():
+    """Raw chunks holding -0.0 and NaN-free extreme patterns survive store -> compose(0)."""
+    L, nb, bs, H, D = 1, 16, 16, 2, 64
+    k = synth.normal_bf16(31, (L, nb, bs, H, D))
+    k[0, :, :, 0, ::7] = 0x8000
+    k[0, :, :, 1, ::5] = 0x0001
+    k[0, :, :, 1, 1::5] = 0x7F7F
+    hc = O.PagedCache(k, synth.normal_bf16(32, (L, nb, bs, H, D)))
+    a, b = synth.disjoint_block_tables(31, nb, [6, 6])
+    dc = dev_cache(hc)
+    out = kdn.alloc_chunk(dc, 96, RAW)
+    kdn.kdn_store_chunk(dc, dev_table(a), 0, 96, out)
+    kdn.kdn_compose([out.slice(0, 40), out.slice(40, 56)], [0, 0], dc, dev_table(b), 10000.0)
+    torch.cuda.synchronize()
+    gk, gv = bits_of(dc.k), bits_of(dc.v)
+    assert np.array_equal(gk[:, b], hc.k[:, a]) and np.array_equal(gv[:, b], hc.v[:, a])
+
+
+def test_many_chunks_go_through_the_device_segment_table():
+    """More chunks than fit in the kernel arguments."""
+    L, nb, bs, H, D = 1, 128, 16, 2, 64
+    src = host_cache(41, L, nb, bs, H, D)
+    a, dst_bt = synth.disjoint_block_tables(41, nb, [60, 60])
+    whole = O.store(src, a, 0, 960, INT8)
+    n = 100
+    cuts = np.sort(synth._rng(41, 9).choice(np.arange(1, 900), size=n - 1, replace=False))
+    cuts = np.concatenate([[0], cuts, [900]])
+    order = synth.permutation(41, n)
+    chunks = [whole.slice(int(cuts[i]), int(cuts[i + 1] - cuts[i])) for i in order]
+    offsets = [int((i * 37) % 11 - 5) for i in range(n)]
+    hd = host_cache(42, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose(chunks, offsets, hd, dst_bt, 10000.0, dest=3)
+    dw = chunk_to_dev(whole)
+    dchunks = [dw.slice(int(cuts[i]), int(cuts[i + 1] - cuts[i])) for i in order]
+    for _ in range(3):       # the ring of device tables is reused
+        kdn.kdn_compose(dchunks, offsets, dd, dev_table(dst_bt), 10000.0, dest_token_start=3)
+    assert_cache_equal(dd, hd)
+
+
+def test_batched_compose_matches_independent_oracle_composes():
+    L, nb, bs, H, D = 2, 200, 16, 2, 128
+    src = host_cache(51, L, nb, bs, H, D)
+    tabs = synth.disjoint_block_tables(51, nb, [8] * 6 + [18] * 8)
+    pool = [O.store(src, tabs[i], 0, 128 - 3 * i, INT8) for i in range(6)]
+    dpool = [chunk_to_dev(c) for c in pool]
+    draws = synth.zipf_distinct_draws(51, 8, 2, 6)
+    hd = host_cache(52, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    reqs = []
+    for r in range(8):
+        ids = [int(x) for x in draws[r]]
+        offs = [0, pool[ids[0]].T]
+        O.compose([pool[i] for i in ids], offs, hd, tabs[6 + r], 500000.0, dest=r % 3)
+        reqs.append(([dpool[i] for i in ids], offs, dev_table(tabs[6 + r]), r % 3))
+    kdn.kdn_compose_batch(reqs, dd, 500000.0)
+    assert_cache_equal(dd, hd)
+
+
+# ------------------------------------------------------------------ utilities
+@pytest.mark.timeout(600)
+def test_f32_to_bf16_every_input_pattern():
+    """All 2^32 fp32 inputs, in 64 slabs, against the oracle's conversion."""
+    lo = torch.arange(0, 1 << 26, dtype=torch.int64, device="cuda")
+    for slab in range(64):
+        u = (lo + (slab << 26)).to(torch.int32) if slab < 32 else (lo + (slab << 26) - (1 << 32)).to(torch.int32)
+        x = u.view(torch.float32)
+        got = bits_of(kdn.kdn_f32_to_bf16(x))
+        xh = x.cpu().numpy()
+        want = O.f32_to_bf16(xh)
+        nan = np.isnan(xh)
+        if slab % 8 == 0:
+            print("[bf16] slab %d" % slab, flush=True)
+        assert np.array_equal(got[~nan], want[~nan]), "slab %d" % slab
+        assert np.all((got[nan] & 0x7F80) == 0x7F80) and np.all((got[nan] & 0x7F) != 0)
+
+
+def test_validate_block_table():
+    ok = dev_table(np.array([5, 1, 7, 0], dtype=np.int32))
+    assert kdn.kdn_validate_block_table(ok, 8) == kdn.OK
+    assert kdn.kdn_validate_block_table(ok, 7) == kdn.ERANGE
+    assert kdn.kdn_validate_block_table(dev_table(np.array([5, 1, 5], dtype=np.int32)), 8) == kdn.ERANGE
+    assert kdn.kdn_validate_block_table(dev_table(np.array([-1, 2], dtype=np.int32)), 8) == kdn.ERANGE
+
+
+def test_rope_prepare_then_compose_and_shutdown_are_repeatable():
+    L, nb, bs, H, D = 1, 16, 16, 1, 64
+    src = host_cache(61, L, nb, bs, H, D)
+    a, b = synth.disjoint_block_tables(61, nb, [4, 4])
+    ch = O.store(src, a, 0, 64, INT8)
+    kdn.kdn_rope_prepare(10000.0, D, [5, 6, 7])
+    for _ in range(2):
+        hd = host_cache(62, L, nb, bs, H, D)
+        dd = dev_cache(hd)
+        O.compose([ch], [6], hd, b, 10000.0)
+        kdn.kdn_compose([chunk_to_dev(ch)], [6], dd, dev_table(b), 10000.0)
+        assert_cache_equal(dd, hd)
+        torch.cuda.synchronize()
+        kdn.kdn_shutdown()

@@ -1,0 +1,115 @@
+"""CPU-side checks: the C-ABI library loads, exports every declared symbol, and its
+host-side argument checks answer without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2409_13761_amd import build, kdn
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(build.LIB_PATH):
+        build.build_library()
+    return kdn.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "kdn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kdn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(kdn.EXPORTS) == names
+
+
+def test_chunk_bytes(lib):
+    assert kdn.kdn_chunk_bytes(32, 8, 128, 1, 1) == 67584
+    assert kdn.kdn_chunk_bytes(32, 8, 128, 1, 0) == 131072
+    assert kdn.kdn_chunk_bytes(80, 8, 128, 1, 1) == 168960
+    assert kdn.kdn_chunk_bytes(2, 4, 64, 256, 1) == 256 * 1088
+    assert kdn.kdn_chunk_bytes(2, 4, 64, 0, 1) == 0
+    assert kdn.kdn_chunk_bytes(2, 4, 64, 4, 7) == 0
+    # 32768 tokens of the 80-layer shape need more than 32 bits
+    assert kdn.kdn_chunk_bytes(80, 8, 128, 32768, 1) == 32768 * 168960
+
+
+def _cache(**kw):
+    d = dict(k=0x1000, v=0x2000, L=2, H=4, D=64, bs=16, nb=8)
+    d.update(kw)
+    H, D, bs, nb = d["H"], d["D"], d["bs"], d["nb"]
+    return kdn.CacheDesc(d["k"], d["v"], d["L"], H, D, bs, nb,
+                         d.get("ls", nb * bs * H * D), d.get("bst", bs * H * D),
+                         d.get("ts", H * D), d.get("hs", D))
+
+
+def _chunk(fmt=1, data=0x4000, T=16, L=2, H=4, D=64, nbytes=None):
+    if nbytes is None:
+        nbytes = kdn.kdn_chunk_bytes(L, H, D, T, fmt)
+    return kdn.ChunkDesc(data, nbytes, fmt, L, H, D, T, 0, T)
+
+
+def test_argument_errors_are_reported_on_the_host(lib):
+    bt = 0x8000
+    good = _cache()
+    ch = _chunk()
+    f = lib.kdn_store_chunk
+    assert f(None, bt, 4, 0, 16, C.byref(ch), None) == kdn.EINVAL
+    assert f(C.byref(good), None, 4, 0, 16, C.byref(ch), None) == kdn.EINVAL
+    assert f(C.byref(good), bt, 4, 0, 0, C.byref(ch), None) == kdn.EINVAL          # empty range
+    assert f(C.byref(good), bt, 4, -1, 16, C.byref(ch), None) == kdn.EINVAL
+    assert f(C.byref(good), bt, 4, 60, 16, C.byref(ch), None) == kdn.ERANGE        # past the table
+    assert f(C.byref(_cache(k=0x1008)), bt, 4, 0, 16, C.byref(ch), None) == kdn.EALIGN
+    assert f(C.byref(_cache(hs=68)), bt, 4, 0, 16, C.byref(ch), None) == kdn.EALIGN
+    assert f(C.byref(_cache(D=24)), bt, 4, 0, 16, C.byref(ch), None) == kdn.EUNSUPPORTED
+    assert f(C.byref(_cache(D=1024)), bt, 4, 0, 16, C.byref(ch), None) == kdn.EUNSUPPORTED
+    assert f(C.byref(good), bt, 4, 0, 16, C.byref(_chunk(nbytes=100)), None) == kdn.ESIZE
+    assert f(C.byref(good), bt, 4, 0, 16, C.byref(_chunk(fmt=5, nbytes=1 << 20)), None) == kdn.EINVAL
+    assert f(C.byref(good), bt, 4, 0, 16, C.byref(_chunk(data=0x4004)), None) == kdn.EALIGN
+
+    g = lib.kdn_load_chunk
+    assert g(None, C.byref(good), bt, 4, 0, None) == kdn.EINVAL
+    assert g(C.byref(ch), C.byref(good), bt, 4, 49, None) == kdn.ERANGE
+    assert g(C.byref(_chunk(H=8)), C.byref(good), bt, 4, 0, None) == kdn.EINVAL   # shape mismatch
+    short = _chunk()
+    short.bytes -= 1
+    assert g(C.byref(short), C.byref(good), bt, 4, 0, None) == kdn.ESIZE
+    view = _chunk()
+    view.token_start, view.num_tokens = 10, 10
+    assert g(C.byref(view), C.byref(good), bt, 4, 0, None) == kdn.ERANGE
+
+    off = (C.c_int32 * 2)(0, 16)
+    arr = (kdn.ChunkDesc * 2)(_chunk(T=40), _chunk(T=40))
+    h = lib.kdn_compose
+    assert h(arr, off, 2, C.byref(good), bt, 4, 0, 10000.0, None) == kdn.ERANGE   # 80 tokens > 64 slots
+    assert h(arr, off, 0, C.byref(good), bt, 4, 0, 10000.0, None) == kdn.EINVAL
+    assert h(arr, None, 2, C.byref(good), bt, 4, 0, 10000.0, None) == kdn.EINVAL
+
+
+def test_chunk_init_and_slice(lib):
+    d = kdn.ChunkDesc()
+    assert lib.kdn_chunk_init(C.byref(d), 0x4000, 1 << 20, 1, 2, 4, 64, 100) == kdn.OK
+    assert (d.parent_tokens, d.token_start, d.num_tokens) == (100, 0, 100)
+    s = kdn.ChunkDesc()
+    assert lib.kdn_chunk_slice(C.byref(d), 10, 50, C.byref(s)) == kdn.OK
+    s2 = kdn.ChunkDesc()
+    assert lib.kdn_chunk_slice(C.byref(s), 5, 45, C.byref(s2)) == kdn.OK
+    assert (s2.parent_tokens, s2.token_start, s2.num_tokens) == (100, 15, 45)
+    assert lib.kdn_chunk_slice(C.byref(s), 5, 46, C.byref(s2)) == kdn.ERANGE
+    assert lib.kdn_chunk_init(C.byref(d), 0x4000, 10, 1, 2, 4, 64, 100) == kdn.ESIZE
+    assert lib.kdn_chunk_init(C.byref(d), 0x4001, 1 << 20, 1, 2, 4, 64, 100) == kdn.EALIGN
+
+
+def test_status_strings(lib):
+    for s in (0, -1, -2, -3, -4, -5, -6):
+        assert kdn.status_str(s)
+    assert "kdn" in kdn.kdn_version()

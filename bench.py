@@ -8,7 +8,8 @@ heads, head_dim 128, bf16, paged in blocks of 16 tokens) through the whole path:
   compose  the chunk as 8 slices of 512 tokens, in a seeded order, each shifted by
            its cumulative RoPE offset, into another fresh table   (kdn_compose)
 Inputs are resident in HBM before the timed region.  Four disjoint buffer sets are
-cycled so that the 256 MB last-level cache cannot serve a repeat.
+cycled, and a step reads chunks that were stored two or three steps earlier, so that
+the 256 MB last-level cache cannot serve a repeat or a just-written chunk.
 
 Prints ONE JSON line: tokens/s over the whole step, the roofline of the dominant
 kernel (the place kernel behind load and compose) from HIP-event timings, and the
@@ -84,21 +85,27 @@ def main() -> int:
            for _ in names] for _ in range(args.steps)]
 
     def step(i, events=None):
-        src, dst_a, dst_b, chunk, slices = sets[i % n_sets]
+        # The chunk a step loads or composes was stored two or three steps earlier, with
+        # gigabytes of traffic in between, so it comes from HBM, not from the cache.
+        src, dst_a, dst_b, chunk, _ = sets[i % n_sets]
+        load_chunk = sets[(i + 2) % n_sets][3]
+        compose_slices = sets[(i + 1) % n_sets][4]
         if events:
             events[0][0].record()
         kdn.kdn_store_chunk(cache, src, 0, T, chunk)
         if events:
             events[0][1].record()
             events[1][0].record()
-        kdn.kdn_load_chunk(chunk, cache, dst_a, 0)
+        kdn.kdn_load_chunk(load_chunk, cache, dst_a, 0)
         if events:
             events[1][1].record()
             events[2][0].record()
-        kdn.kdn_compose(slices, offsets, cache, dst_b, base)
+        kdn.kdn_compose(compose_slices, offsets, cache, dst_b, base)
         if events:
             events[2][1].record()
 
+    for s in range(n_sets):                     # every chunk exists before any is read
+        kdn.kdn_store_chunk(cache, sets[s][0], 0, T, sets[s][3])
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()

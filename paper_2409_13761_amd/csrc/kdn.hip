@@ -29,12 +29,15 @@ namespace {
 constexpr int kThreads = 256;      // 4 wavefronts per workgroup
 constexpr int kMaxInlineSegs = 64; // segments that travel in the kernel arguments
 constexpr int kMaxHeadDim = 512;
+constexpr int kStoreU = 4;         // 16-byte loads a store thread keeps in flight
 constexpr int kRopeRowsCap = 4096; // cos/sin rows kept per (base, head_dim)
 constexpr int kSegSlots = 8;       // ring of device segment tables for batched composes
 constexpr size_t kSegSlotBytes = 1u << 20;
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // One placed chunk view: rows of tokens [tok0, tok0+T) of a stored buffer that
 // holds Tp tokens go to request tokens [S, S+T) of the request whose table is bt.
@@ -101,18 +104,42 @@ constexpr __host__ __device__ int log2_ceil(int x)
 // ---------------------------------------------------------------------------------
 // store: gather paged rows, per-row amax, quantise.
 // Lane group: D/8 lanes own one row, 8 consecutive elements (one 16-byte load) each;
-// the group is padded to a power of two so the row reduction is a butterfly.
-template <int DT, int FMT>
+// the group is padded to a power of two so the row reduction is a butterfly of
+// cross-lane moves (DPP within 16 lanes, wavefront shuffles beyond).
+// Grid: x = group * 2L + (layer, side).
+
+// max over the P lanes of a row's lane group; every lane of the group gets the result
+template <int P>
+__device__ __forceinline__ uint32_t group_max(uint32_t m)
+{
+    if (P >= 2) // lane ^ 1
+        m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0xB1, 0xf, 0xf, true));
+    if (P >= 4) // lane ^ 2
+        m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x4E, 0xf, 0xf, true));
+    if (P >= 8) // mirror within 8 lanes: the other quad
+        m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x141, 0xf, 0xf, true));
+    if (P >= 16) // mirror within 16 lanes: the other half
+        m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x140, 0xf, 0xf, true));
+    if (P >= 32)
+        m = max(m, (uint32_t)__shfl_xor((int)m, 16));
+    if (P >= 64)
+        m = max(m, (uint32_t)__shfl_xor((int)m, 32));
+    return m;
+}
+
+template <int DT, int FMT, int P>
 __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 {
+    constexpr int U = kStoreU;
+    constexpr int LOGP = log2_ceil(P);
     const int D = DT ? DT : p.c.D;
     const int R = D >> 3;
-    const int LOGP = DT ? log2_ceil(DT >> 3) : log2_ceil(R);
-    const int P = 1 << LOGP;
     const int H = p.c.H, G = p.c.G, bs = p.c.bs;
+    const int L2 = 2 * p.c.L;
 
-    const int ls = blockIdx.y;
-    const int gi = p.t0 / G + blockIdx.x;
+    const int piece = blockIdx.x / L2;
+    const int ls = blockIdx.x - piece * L2;
+    const int gi = p.t0 / G + piece;
     const int tok_lo = max(p.t0, gi * G);
     const int tok_hi = min(p.t0 + p.T, (gi + 1) * G);
     if (tok_lo >= tok_hi)
@@ -122,64 +149,73 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     const uint16_t *tile = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(ls >> 1) * p.c.layer_stride
                            + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
     const int64_t row_base = ((int64_t)ls * p.T + (tok_lo - p.t0)) * H;
-    const int n_rows = (tok_hi - tok_lo) * H;
-    const int n_items = n_rows << LOGP;
+    const int n_items = ((tok_hi - tok_lo) * H) << LOGP;
     const int64_t total_rows = (int64_t)p.c.L * 2 * p.T * H;
+    uint8_t *codes = p.out + row_base * D;
+    float *scales = reinterpret_cast<float *>(p.out + total_rows * D) + row_base;
 
     const int sub = threadIdx.x & (P - 1);
-    for (int base = 0; base < n_items; base += kThreads) {
-        const int it = base + threadIdx.x;
-        const int r = it >> LOGP;
-        const bool live = it < n_items && sub < R;
-        uint4 w = {0, 0, 0, 0};
-        if (live) {
-            const uint16_t *src;
-            if (p.c.dense) {
-                src = tile + (int64_t)r * D;
-            } else {
-                const int tok = r / H, h = r - tok * H;
-                src = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
-            }
-            w = *reinterpret_cast<const uint4 *>(src + sub * 8);
-        }
-        const int64_t srow = row_base + r;
-        if (FMT == KDN_FMT_RAW_BF16) {
-            if (live)
-                *reinterpret_cast<uint4 *>(p.out + (srow * D + sub * 8) * 2) = w;
-            continue;
-        }
-        // |x| of a bf16 orders like its low 15 bits
-        const uint32_t a0 = w.x & 0x7fff7fffu, a1 = w.y & 0x7fff7fffu;
-        const uint32_t a2 = w.z & 0x7fff7fffu, a3 = w.w & 0x7fff7fffu;
-        uint32_t m = max(max(a0 & 0xffffu, a0 >> 16), max(a1 & 0xffffu, a1 >> 16));
-        m = max(m, max(max(a2 & 0xffffu, a2 >> 16), max(a3 & 0xffffu, a3 >> 16)));
-        for (int o = 1; o < P; o <<= 1)
-            m = max(m, (uint32_t)__shfl_xor((int)m, o));
-        const float amax = __uint_as_float(m << 16);
-        const bool keep = amax >= 0x1p-121f;
-        const float scale = keep ? amax / 127.0f : 0.0f;
-        const float inv = keep ? 127.0f / amax : 0.0f;
-        if (!live)
-            continue;
-        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-        uint32_t q[2];
+    for (int base = 0; base < n_items; base += kThreads * U) {
+        u32x4 w[U];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            uint32_t acc = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t word = ww[2 * i + (e >> 1)];
-                const float x = (e & 1) ? bf16_hi(word) : bf16_lo(word);
-                float rr = __builtin_rintf(x * inv);
-                rr = fminf(fmaxf(rr, -127.0f), 127.0f);
-                acc |= ((uint32_t)(int)rr & 0xffu) << (8 * e);
+        for (int u = 0; u < U; ++u) {
+            const int it = base + u * kThreads + threadIdx.x;
+            const int r = it >> LOGP;
+            w[u] = u32x4{0, 0, 0, 0};
+            if (it < n_items && sub < R) {
+                const uint16_t *src;
+                if (p.c.dense) {
+                    src = tile + (int64_t)r * D;
+                } else {
+                    const int tok = r / H, h = r - tok * H;
+                    src = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
+                }
+                w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + sub * 8));
             }
-            q[i] = acc;
         }
-        uint2 qq = {q[0], q[1]};
-        *reinterpret_cast<uint2 *>(p.out + srow * D + sub * 8) = qq;
-        if (sub == 0)
-            *reinterpret_cast<float *>(p.out + total_rows * D + srow * 4) = scale;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int it = base + u * kThreads + threadIdx.x;
+            const int r = it >> LOGP;
+            const bool live = it < n_items && sub < R;
+            if (FMT == KDN_FMT_RAW_BF16) {
+                if (live)
+                    __builtin_nontemporal_store(
+                        w[u], reinterpret_cast<u32x4 *>(p.out + ((row_base + r) * D + sub * 8) * 2));
+                continue;
+            }
+            // |x| of a bf16 orders like its low 15 bits
+            uint32_t m = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t a = w[u][i] & 0x7fff7fffu;
+                m = max(m, max(a & 0xffffu, a >> 16));
+            }
+            m = group_max<P>(m);
+            const float amax = __uint_as_float(m << 16);
+            const bool keep = amax >= 0x1p-121f;
+            const float scale = keep ? amax / 127.0f : 0.0f;
+            const float inv = keep ? 127.0f / amax : 0.0f;
+            if (!live)
+                continue;
+            u32x2 q;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                uint32_t acc = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t word = w[u][2 * i + (e >> 1)];
+                    const float x = (e & 1) ? bf16_hi(word) : bf16_lo(word);
+                    float rr = __builtin_rintf(x * inv);
+                    rr = fminf(fmaxf(rr, -127.0f), 127.0f);
+                    acc |= ((uint32_t)(int)rr & 0xffu) << (8 * e);
+                }
+                q[i] = acc;
+            }
+            __builtin_nontemporal_store(q, reinterpret_cast<u32x2 *>(codes + (int64_t)r * D + sub * 8));
+            if (sub == 0)
+                scales[r] = scale;
+        }
     }
 }
 
@@ -188,20 +224,29 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 // Lane group: D/16 lanes own one row; a lane takes 8 elements of the lower half and
 // the 8 elements of the upper half that pair with them, so the rotation needs no
 // exchange between lanes and each lane writes two full 16-byte bf16 vectors.
+// Each thread issues the loads of U items before it touches the first, and both the
+// stored chunk and the paged destination are streamed (non-temporal): nothing here is
+// read twice.
+// Grid: x = group * 2L + (layer, side), so that neighbouring workgroups write to
+// different (layer, side) planes; y = segment.
 template <int DT, int FMT, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 {
+    constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 2 : 4;
+    constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : 2; // 32-bit words per 8 stored elements
     const int D = DT ? DT : p.c.D;
     const int half = D >> 1;
     const int R = D >> 4;
     const int LOGP = DT ? log2_ceil(DT >> 4) : log2_ceil(R);
     const int P = 1 << LOGP;
     const int H = p.c.H, G = p.c.G, bs = p.c.bs;
+    const int L2 = 2 * p.c.L;
 
-    const Seg &sg = segs.at(blockIdx.z);
+    const Seg &sg = segs.at(blockIdx.y);
     const int S = sg.S, T = sg.T;
-    const int ls = blockIdx.y;
-    const int gi = S / G + blockIdx.x;
+    const int piece = blockIdx.x / L2;
+    const int ls = blockIdx.x - piece * L2;
+    const int gi = S / G + piece;
     const int tok_lo = max(S, gi * G);
     const int tok_hi = min(S + T, (gi + 1) * G);
     if (tok_lo >= tok_hi)
@@ -215,6 +260,7 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
     const int64_t total_rows = (int64_t)p.c.L * 2 * Tp * H;
     const int n_items = ((tok_hi - tok_lo) * H) << LOGP;
     const uint8_t *data = sg.data;
+    const float *scales = reinterpret_cast<const float *>(data + total_rows * D) + row_base;
     const bool rotate = (ls & 1) == 0 && sg.rope_row >= 0;
 
     const int sub = threadIdx.x & (P - 1);
@@ -231,66 +277,95 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                 cs[e] = s_cs[sub * 8 + e];
         }
     }
+    if (sub >= R)
+        return;
 
-    for (int it = threadIdx.x; it < n_items; it += kThreads) {
-        if (sub >= R)
-            continue;
-        const int r = it >> LOGP;
-        const int64_t srow = row_base + r;
-        uint16_t *dst;
-        if (p.c.dense) {
-            dst = tile + (int64_t)r * D + sub * 8;
-        } else {
-            const int tok = r / H, h = r - tok * H;
-            dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride + sub * 8;
+    for (int it0 = threadIdx.x; it0 < n_items; it0 += kThreads * U) {
+        uint32_t lo[U][W], hi[U][W];
+        float sc[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int it = it0 + u * kThreads;
+            if (it < n_items) {
+                const int r = it >> LOGP;
+                const uint8_t *src = data + ((row_base + r) * D + sub * 8) * (W / 2);
+                if (FMT == KDN_FMT_RAW_BF16) {
+                    const u32x4 l4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+                    const u32x4 h4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + D));
+#pragma unroll
+                    for (int w = 0; w < W; ++w) {
+                        lo[u][w] = l4[w];
+                        hi[u][w] = h4[w];
+                    }
+                } else {
+                    const u32x2 l2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src));
+                    const u32x2 h2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src + half));
+#pragma unroll
+                    for (int w = 0; w < W; ++w) {
+                        lo[u][w] = l2[w & 1];
+                        hi[u][w] = h2[w & 1];
+                    }
+                    sc[u] = scales[r];
+                }
+            }
         }
-        float a[8], b[8];
-        if (FMT == KDN_FMT_RAW_BF16) {
-            const uint16_t *src = reinterpret_cast<const uint16_t *>(data) + srow * D + sub * 8;
-            const uint4 lo = *reinterpret_cast<const uint4 *>(src);
-            const uint4 hi = *reinterpret_cast<const uint4 *>(src + half);
-            if (!rotate) { // bit copy
-                *reinterpret_cast<uint4 *>(dst) = lo;
-                *reinterpret_cast<uint4 *>(dst + half) = hi;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int it = it0 + u * kThreads;
+            if (it >= n_items)
                 continue;
+            const int r = it >> LOGP;
+            uint16_t *dst;
+            if (p.c.dense) {
+                dst = tile + (int64_t)r * D + sub * 8;
+            } else {
+                const int tok = r / H, h = r - tok * H;
+                dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride + sub * 8;
             }
-            const uint32_t lw[4] = {lo.x, lo.y, lo.z, lo.w}, hw[4] = {hi.x, hi.y, hi.z, hi.w};
+            u32x4 olo, ohi;
+            if (FMT == KDN_FMT_RAW_BF16 && !rotate) { // bit copy
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                a[2 * e] = bf16_lo(lw[e]);
-                a[2 * e + 1] = bf16_hi(lw[e]);
-                b[2 * e] = bf16_lo(hw[e]);
-                b[2 * e + 1] = bf16_hi(hw[e]);
-            }
-        } else {
-            const uint8_t *src = data + srow * D + sub * 8;
-            const uint2 lo = *reinterpret_cast<const uint2 *>(src);
-            const uint2 hi = *reinterpret_cast<const uint2 *>(src + half);
-            const float sc = *reinterpret_cast<const float *>(data + total_rows * D + srow * 4);
-            const uint32_t lw[2] = {lo.x, lo.y}, hw[2] = {hi.x, hi.y};
+                for (int w = 0; w < 4; ++w) {
+                    olo[w] = lo[u][w % W];
+                    ohi[w] = hi[u][w % W];
+                }
+            } else {
+                float a[8], b[8];
+                if (FMT == KDN_FMT_RAW_BF16) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                a[e] = code_f32(lw[e >> 2], e & 3) * sc;
-                b[e] = code_f32(hw[e >> 2], e & 3) * sc;
+                    for (int e = 0; e < 4; ++e) {
+                        a[2 * e] = bf16_lo(lo[u][e % W]);
+                        a[2 * e + 1] = bf16_hi(lo[u][e % W]);
+                        b[2 * e] = bf16_lo(hi[u][e % W]);
+                        b[2 * e + 1] = bf16_hi(hi[u][e % W]);
+                    }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        a[e] = code_f32(lo[u][(e >> 2) % W], e & 3) * sc[u];
+                        b[e] = code_f32(hi[u][(e >> 2) % W], e & 3) * sc[u];
+                    }
+                }
+                if (rotate) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float c = cs[e].x, s = cs[e].y;
+                        const float ac = a[e] * c, bc = b[e] * c;
+                        const float l = __builtin_fmaf(-b[e], s, ac);
+                        const float h = __builtin_fmaf(a[e], s, bc);
+                        a[e] = l;
+                        b[e] = h;
+                    }
+                }
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    olo[w] = pack_bf16(a[2 * w], a[2 * w + 1]);
+                    ohi[w] = pack_bf16(b[2 * w], b[2 * w + 1]);
+                }
             }
+            __builtin_nontemporal_store(olo, reinterpret_cast<u32x4 *>(dst));
+            __builtin_nontemporal_store(ohi, reinterpret_cast<u32x4 *>(dst + half));
         }
-        if (rotate) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float c = cs[e].x, s = cs[e].y;
-                const float ac = a[e] * c, bc = b[e] * c;
-                const float lo = __builtin_fmaf(-b[e], s, ac);
-                const float hi = __builtin_fmaf(a[e], s, bc);
-                a[e] = lo;
-                b[e] = hi;
-            }
-        }
-        uint4 olo = {pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(a[4], a[5]),
-                     pack_bf16(a[6], a[7])};
-        uint4 ohi = {pack_bf16(b[0], b[1]), pack_bf16(b[2], b[3]), pack_bf16(b[4], b[5]),
-                     pack_bf16(b[6], b[7])};
-        *reinterpret_cast<uint4 *>(dst) = olo;
-        *reinterpret_cast<uint4 *>(dst + half) = ohi;
     }
 }
 
@@ -509,19 +584,27 @@ kdn_status rope_rows(DeviceState *ds, double base, int32_t D, const int32_t *off
     return KDN_OK;
 }
 
-template <int DT, int FMT>
+template <int DT, int FMT, int P>
 void launch_store(const StoreP &p, dim3 grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((k_store<DT, FMT>), grid, dim3(kThreads), 0, st, p);
+    hipLaunchKernelGGL((k_store<DT, FMT, P>), grid, dim3(kThreads), 0, st, p);
 }
 
 template <int FMT>
 void launch_store_d(const StoreP &p, dim3 grid, hipStream_t st)
 {
     switch (p.c.D) {
-    case 64: launch_store<64, FMT>(p, grid, st); break;
-    case 128: launch_store<128, FMT>(p, grid, st); break;
-    default: launch_store<0, FMT>(p, grid, st); break;
+    case 64: launch_store<64, FMT, 8>(p, grid, st); return;
+    case 128: launch_store<128, FMT, 16>(p, grid, st); return;
+    default: break;
+    }
+    switch (log2_ceil(p.c.D >> 3)) { // lane group: D/8 lanes rounded up to a power of two
+    case 1: launch_store<0, FMT, 2>(p, grid, st); break;
+    case 2: launch_store<0, FMT, 4>(p, grid, st); break;
+    case 3: launch_store<0, FMT, 8>(p, grid, st); break;
+    case 4: launch_store<0, FMT, 16>(p, grid, st); break;
+    case 5: launch_store<0, FMT, 32>(p, grid, st); break;
+    default: launch_store<0, FMT, 64>(p, grid, st); break;
     }
 }
 
@@ -563,9 +646,9 @@ kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const s
     int64_t max_groups = 0;
     for (const Seg &s : segs)
         max_groups = std::max(max_groups, groups_spanned(s.S, s.T, p.c.G));
-    if (max_groups > 0x7fffffff / kThreads)
+    if (max_groups * 2 * p.c.L > 0x7fffffff / kThreads)
         return KDN_ESIZE;
-    dim3 grid((unsigned)max_groups, (unsigned)(2 * p.c.L), (unsigned)segs.size());
+    dim3 grid((unsigned)(max_groups * 2 * p.c.L), (unsigned)segs.size(), 1);
 
     const Seg *segs_dev = nullptr;
     int slot = -1;
@@ -753,9 +836,9 @@ kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_tab
     p.t0 = token_start;
     p.T = num_tokens;
     const int64_t groups = groups_spanned(token_start, num_tokens, p.c.G);
-    if (groups > 0x7fffffff / kThreads)
+    if (groups * 2 * p.c.L > 0x7fffffff / kThreads)
         return KDN_ESIZE;
-    dim3 grid((unsigned)groups, (unsigned)(2 * p.c.L), 1);
+    dim3 grid((unsigned)(groups * 2 * p.c.L), 1, 1);
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (out->fmt == KDN_FMT_RAW_BF16)
         launch_store_d<KDN_FMT_RAW_BF16>(p, grid, hs);

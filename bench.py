@@ -28,6 +28,17 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 
+# HBM bytes per k_place launch of this workload from the FETCH_SIZE / WRITE_SIZE counter runs
+# summarised under profiles/, valid only for the kernel source they were taken with.
+COUNTER_TRAFFIC = {"source_sha256_16": "787f6808c77731d9", "k_place_bytes_per_launch": 815509774}
+
+
+def counter_traffic():
+    import hashlib
+    src = os.path.join(ROOT, "paper_2409_13761_amd", "csrc", "kdn.hip")
+    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    return COUNTER_TRAFFIC["k_place_bytes_per_launch"] if sha == COUNTER_TRAFFIC["source_sha256_16"] else None
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -35,7 +46,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=3)
+    ap.add_argument("--cpu-steps", type=int, default=8)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, a dispatch of known size for "
+                         "scaling hardware byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; the path shards without any exchange "
@@ -115,6 +129,14 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    if args.calibration_copy:
+        a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                              # 1 GiB read, 1 GiB written
+        torch.cuda.synchronize()
+        del a, b
+
     ms = {n: float(np.mean([ev[i][j][0].elapsed_time(ev[i][j][1]) for i in range(args.steps)]))
           for j, n in enumerate(names)}
     bytes_call = T * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)    # B_p + B_q per token
@@ -153,7 +175,7 @@ def main() -> int:
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": None,
+            "traffic": counter_traffic(),
         },
     }
     if not args.no_cpu_baseline:

@@ -127,11 +127,45 @@ __device__ __forceinline__ uint32_t group_max(uint32_t m)
     return m;
 }
 
-template <int DT, int FMT, int P>
+// Row maximum of |x| over the 8 bf16 values a lane holds, as the 15-bit pattern.
+__device__ __forceinline__ uint32_t lane_absmax_bits(u32x4 w)
+{
+    typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+    u16x2 a = __builtin_bit_cast(u16x2, w[0] & 0x7fff7fffu);
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+        a = __builtin_elementwise_max(a, __builtin_bit_cast(u16x2, w[i] & 0x7fff7fffu));
+    const uint32_t m = __builtin_bit_cast(uint32_t, a);
+    return max(m & 0xffffu, m >> 16);
+}
+
+// Codes of 4 values: rint(x * inv) by the add-a-large-constant rule, which rounds the
+// (already rounded) product to the nearest integer, ties to even, exactly as rintf
+// does for |value| < 2^22; the code is then the low byte of the sum's bit pattern.
+// The clamp to [-127, 127] of the format's definition can never bind for finite
+// input: |x| <= amax and inv = RN(127/amax) <= (127/amax)(1 + 2^-24) give
+// |x*inv| <= 127(1 + 2^-24), whose fp32 rounding is at most the float just above
+// 127, and that still rounds to the integer 127.
+__device__ __forceinline__ uint32_t quantise4(uint32_t w0, uint32_t w1, float inv)
+{
+    const float magic = 12582912.0f; // 1.5 * 2^23
+    const uint32_t t0 = __float_as_uint(bf16_lo(w0) * inv + magic);
+    const uint32_t t1 = __float_as_uint(bf16_hi(w0) * inv + magic);
+    const uint32_t t2 = __float_as_uint(bf16_lo(w1) * inv + magic);
+    const uint32_t t3 = __float_as_uint(bf16_hi(w1) * inv + magic);
+    const uint32_t p01 = __builtin_amdgcn_perm(t1, t0, 0x0c0c0400u); // bytes: t0.b0, t1.b0, 0, 0
+    const uint32_t p23 = __builtin_amdgcn_perm(t3, t2, 0x04000c0cu); // bytes: 0, 0, t2.b0, t3.b0
+    return p01 | p23;
+}
+
+template <int DT, int FMT, int P, bool DENSE>
 __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 {
     constexpr int U = kStoreU;
     constexpr int LOGP = log2_ceil(P);
+    // with at least 8 lanes per row the 2*U divisions of a batch are spread over the
+    // lanes of the row's group (one division sequence per batch instead of 2*U)
+    constexpr bool SPREAD = P >= 8 && U == 4;
     const int D = DT ? DT : p.c.D;
     const int R = D >> 3;
     const int H = p.c.H, G = p.c.G, bs = p.c.bs;
@@ -151,10 +185,13 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     const int64_t row_base = ((int64_t)ls * p.T + (tok_lo - p.t0)) * H;
     const int n_items = ((tok_hi - tok_lo) * H) << LOGP;
     const int64_t total_rows = (int64_t)p.c.L * 2 * p.T * H;
-    uint8_t *codes = p.out + row_base * D;
+    uint8_t *codes = p.out + row_base * D * (FMT == KDN_FMT_RAW_BF16 ? 2 : 1);
     float *scales = reinterpret_cast<float *>(p.out + total_rows * D) + row_base;
 
     const int sub = threadIdx.x & (P - 1);
+    const int lane = __lane_id();
+    const int grp_addr = (lane & ~(P - 1)) << 2; // byte address of the group's first lane for bpermute
+
     for (int base = 0; base < n_items; base += kThreads * U) {
         u32x4 w[U];
 #pragma unroll
@@ -164,57 +201,66 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
             w[u] = u32x4{0, 0, 0, 0};
             if (it < n_items && sub < R) {
                 const uint16_t *src;
-                if (p.c.dense) {
-                    src = tile + (int64_t)r * D;
+                if (DENSE) {
+                    src = tile + (uint32_t)(r * D + sub * 8);
                 } else {
                     const int tok = r / H, h = r - tok * H;
-                    src = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
+                    src = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride + sub * 8;
                 }
-                w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + sub * 8));
+                w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+            }
+        }
+        if (FMT == KDN_FMT_RAW_BF16) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int it = base + u * kThreads + threadIdx.x;
+                const int r = it >> LOGP;
+                if (it < n_items && sub < R)
+                    __builtin_nontemporal_store(
+                        w[u], reinterpret_cast<u32x4 *>(codes + (uint32_t)(r * D + sub * 8) * 2));
+            }
+            continue;
+        }
+        // |x| of a bf16 orders like its low 15 bits
+        uint32_t m[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            m[u] = group_max<P>(lane_absmax_bits(w[u]));
+        float inv[U];
+        if (SPREAD) {
+            // lane sub of the group: item (sub & 3); lanes 0..3 form inv = 127/amax,
+            // lanes 4..7 form scale = amax/127 (lanes 8.. repeat, unused)
+            const int us = sub & 3;
+            const uint32_t msel = us == 0 ? m[0] : us == 1 ? m[1] : us == 2 ? m[2] : m[U - 1];
+            const float amax = __uint_as_float(msel << 16);
+            const bool is_scale = (sub & 4) != 0;
+            const float q = (is_scale ? amax : 127.0f) / (is_scale ? 127.0f : amax);
+            const float quot = amax >= 0x1p-121f ? q : 0.0f;
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                inv[u] = __int_as_float(__builtin_amdgcn_ds_bpermute(grp_addr + 4 * u, __float_as_int(quot)));
+            const int it_s = base + us * kThreads + threadIdx.x; // same row as every lane of the group
+            if (is_scale && sub < 8 && it_s < n_items)
+                scales[it_s >> LOGP] = quot;
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const float amax = __uint_as_float(m[u] << 16);
+                const bool keep = amax >= 0x1p-121f;
+                inv[u] = keep ? 127.0f / amax : 0.0f;
+                const int it = base + u * kThreads + threadIdx.x;
+                if (sub == 0 && it < n_items)
+                    scales[it >> LOGP] = keep ? amax / 127.0f : 0.0f;
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int it = base + u * kThreads + threadIdx.x;
             const int r = it >> LOGP;
-            const bool live = it < n_items && sub < R;
-            if (FMT == KDN_FMT_RAW_BF16) {
-                if (live)
-                    __builtin_nontemporal_store(
-                        w[u], reinterpret_cast<u32x4 *>(p.out + ((row_base + r) * D + sub * 8) * 2));
-                continue;
+            if (it < n_items && sub < R) {
+                const u32x2 q = {quantise4(w[u][0], w[u][1], inv[u]), quantise4(w[u][2], w[u][3], inv[u])};
+                __builtin_nontemporal_store(q, reinterpret_cast<u32x2 *>(codes + (uint32_t)(r * D + sub * 8)));
             }
-            // |x| of a bf16 orders like its low 15 bits
-            uint32_t m = 0;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t a = w[u][i] & 0x7fff7fffu;
-                m = max(m, max(a & 0xffffu, a >> 16));
-            }
-            m = group_max<P>(m);
-            const float amax = __uint_as_float(m << 16);
-            const bool keep = amax >= 0x1p-121f;
-            const float scale = keep ? amax / 127.0f : 0.0f;
-            const float inv = keep ? 127.0f / amax : 0.0f;
-            if (!live)
-                continue;
-            u32x2 q;
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                uint32_t acc = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t word = w[u][2 * i + (e >> 1)];
-                    const float x = (e & 1) ? bf16_hi(word) : bf16_lo(word);
-                    float rr = __builtin_rintf(x * inv);
-                    rr = fminf(fmaxf(rr, -127.0f), 127.0f);
-                    acc |= ((uint32_t)(int)rr & 0xffu) << (8 * e);
-                }
-                q[i] = acc;
-            }
-            __builtin_nontemporal_store(q, reinterpret_cast<u32x2 *>(codes + (int64_t)r * D + sub * 8));
-            if (sub == 0)
-                scales[r] = scale;
         }
     }
 }
@@ -229,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 // read twice.
 // Grid: x = group * 2L + (layer, side), so that neighbouring workgroups write to
 // different (layer, side) planes; y = segment.
-template <int DT, int FMT, typename Segs>
+template <int DT, int FMT, bool DENSE, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 {
     constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 2 : 4;
@@ -259,8 +305,8 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
     const int64_t row_base = ((int64_t)ls * Tp + sg.tok0 + (tok_lo - S)) * H;
     const int64_t total_rows = (int64_t)p.c.L * 2 * Tp * H;
     const int n_items = ((tok_hi - tok_lo) * H) << LOGP;
-    const uint8_t *data = sg.data;
-    const float *scales = reinterpret_cast<const float *>(data + total_rows * D) + row_base;
+    const uint8_t *data = sg.data + row_base * D * (W / 2); // first stored row of this tile
+    const float *scales = reinterpret_cast<const float *>(sg.data + total_rows * D) + row_base;
     const bool rotate = (ls & 1) == 0 && sg.rope_row >= 0;
 
     const int sub = threadIdx.x & (P - 1);
@@ -288,7 +334,7 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
             const int it = it0 + u * kThreads;
             if (it < n_items) {
                 const int r = it >> LOGP;
-                const uint8_t *src = data + ((row_base + r) * D + sub * 8) * (W / 2);
+                const uint8_t *src = data + (uint32_t)(r * D + sub * 8) * (W / 2);
                 if (FMT == KDN_FMT_RAW_BF16) {
                     const u32x4 l4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
                     const u32x4 h4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + D));
@@ -316,8 +362,8 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                 continue;
             const int r = it >> LOGP;
             uint16_t *dst;
-            if (p.c.dense) {
-                dst = tile + (int64_t)r * D + sub * 8;
+            if (DENSE) {
+                dst = tile + (uint32_t)(r * D + sub * 8);
             } else {
                 const int tok = r / H, h = r - tok * H;
                 dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride + sub * 8;
@@ -587,7 +633,10 @@ kdn_status rope_rows(DeviceState *ds, double base, int32_t D, const int32_t *off
 template <int DT, int FMT, int P>
 void launch_store(const StoreP &p, dim3 grid, hipStream_t st)
 {
-    hipLaunchKernelGGL((k_store<DT, FMT, P>), grid, dim3(kThreads), 0, st, p);
+    if (p.c.dense)
+        hipLaunchKernelGGL((k_store<DT, FMT, P, true>), grid, dim3(kThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL((k_store<DT, FMT, P, false>), grid, dim3(kThreads), 0, st, p);
 }
 
 template <int FMT>
@@ -614,12 +663,18 @@ void launch_place(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_d
 {
     if (segs_dev) {
         SegsDevice sd{segs_dev};
-        hipLaunchKernelGGL((k_place<DT, FMT, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+        if (p.c.dense)
+            hipLaunchKernelGGL((k_place<DT, FMT, true, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+        else
+            hipLaunchKernelGGL((k_place<DT, FMT, false, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
     } else {
         SegsInline si;
         std::memset(&si, 0, sizeof si);
         std::memcpy(si.s, segs, (size_t)n * sizeof(Seg));
-        hipLaunchKernelGGL((k_place<DT, FMT, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+        if (p.c.dense)
+            hipLaunchKernelGGL((k_place<DT, FMT, true, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+        else
+            hipLaunchKernelGGL((k_place<DT, FMT, false, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
     }
 }
 

@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Throughput of the KDN hot path on one MI355X.
 
-One step carries one 4096-token context of Llama-3-8B-shaped KV (32 layers, 8 KV
-heads, head_dim 128, bf16, paged in blocks of 16 tokens) through the whole path:
+Default workload ("8b"): one step carries one 4096-token context of Llama-3-8B-shaped
+KV (32 layers, 8 KV heads, head_dim 128, bf16, paged in blocks of 16 tokens) through
+the whole path:
   store    paged KV -> stored int8 chunk              (kdn_store_chunk)
   load     stored chunk -> a fresh block table        (kdn_load_chunk, no shift)
   compose  the chunk as 8 slices of 512 tokens, in a seeded order, each shifted by
@@ -10,6 +11,11 @@ heads, head_dim 128, bf16, paged in blocks of 16 tokens) through the whole path:
 Inputs are resident in HBM before the timed region.  Four disjoint buffer sets are
 cycled, and a step reads chunks that were stored two or three steps earlier, so that
 the 256 MB last-level cache cannot serve a repeat or a just-written chunk.
+
+Other workloads (--workload): "70b_long" (80 layers, 32768 tokens: one store, one
+compose of four 8192-token slices) and "batched_reuse" (64 requests x 4 chunks of
+1024 tokens drawn by Zipf popularity from a resident pool of 256 chunks, one batched
+compose per step).
 
 Prints ONE JSON line: tokens/s over the whole step, the roofline of the dominant
 kernel (the place kernel behind load and compose) from HIP-event timings, and the
@@ -27,10 +33,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
+METRIC = "KV tokens composed/sec (store+load+RoPE shift) and achieved HBM GB/s"
 
-# HBM bytes per k_place launch of this workload from the FETCH_SIZE / WRITE_SIZE counter runs
-# summarised under profiles/, valid only for the kernel source they were taken with.
-COUNTER_TRAFFIC = {"source_sha256_16": "787f6808c77731d9", "k_place_bytes_per_launch": 815509774}
+# HBM bytes per k_place launch of the default workload from the FETCH_SIZE / WRITE_SIZE
+# counter runs summarised under profiles/, valid only for the kernel source they were
+# taken with.
+COUNTER_TRAFFIC = {"source_sha256_16": "75e341172648bf67", "k_place_bytes_per_launch": 816460977}
 
 
 def counter_traffic():
@@ -40,51 +48,68 @@ def counter_traffic():
     return COUNTER_TRAFFIC["k_place_bytes_per_launch"] if sha == COUNTER_TRAFFIC["source_sha256_16"] else None
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=8)
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy, a dispatch of known size for "
-                         "scaling hardware byte counters")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only; the path shards without any exchange "
-              "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
-        return 2
+def fill_normal(t, gen):
+    """N(0,1) into a bf16 tensor, one leading slab at a time (bounds the fp32 temporary)."""
+    import torch
+    for i in range(t.shape[0]):
+        t[i].copy_(torch.randn(t.shape[1:], generator=gen, device=t.device, dtype=torch.float32))
 
-    import numpy as np
+
+class Timed:
+    """Runs `step(i, rec)` W + K times; `rec(name, fn)` brackets a call with HIP events on
+    the current stream (the one the library launches on) during the K timed steps."""
+
+    def __init__(self, names, steps):
+        import torch
+        self.names, self.steps = names, steps
+        self.ev = [{n: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                    for n in names} for _ in range(steps)]
+
+    def run(self, step, warmup):
+        import numpy as np
+        import torch
+
+        def plain(name, fn):
+            fn()
+
+        def recorder(ev):
+            def rec(name, fn):
+                ev[name][0].record()
+                fn()
+                ev[name][1].record()
+            return rec
+
+        for i in range(warmup):
+            step(i, plain)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(self.steps):
+            step(warmup + i, recorder(self.ev[i]))
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        ms = {n: float(np.mean([e[n][0].elapsed_time(e[n][1]) for e in self.ev])) for n in self.names}
+        return wall, ms
+
+
+def workload_8b(args, dev):
     import torch
     from paper_2409_13761_amd import kdn, synth
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU", file=sys.stderr)
-        return 3
-    kdn.lib()                                   # fail loudly if the HIP library is not built
-    torch.cuda.set_device(0)
-    dev = torch.device("cuda:0")
-
     sh = synth.LLAMA8B
     T, n_slices = 4096, 8
-    base = synth.WORKLOADS["rag_compose"].rope_base
-    seed = synth.WORKLOADS["rag_compose"].seed
+    w = synth.WORKLOADS["rag_compose"]
     blocks = T // sh.bs
     n_sets = 4
     nb = n_sets * 3 * blocks
     g = torch.Generator(device=dev)
-    g.manual_seed(seed)
-    shape = (sh.L, nb, sh.bs, sh.H, sh.D)
-    k = torch.empty(shape, device=dev, dtype=torch.bfloat16)
-    v = torch.empty(shape, device=dev, dtype=torch.bfloat16)
-    for t in (k, v):                            # N(0,1) in slabs, to bound the fp32 temporary
-        for l in range(sh.L):
-            t[l].copy_(torch.randn(shape[1:], generator=g, device=dev, dtype=torch.float32))
+    g.manual_seed(w.seed)
+    k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+    v = torch.empty_like(k)
+    fill_normal(k, g)
+    fill_normal(v, g)
     cache = kdn.PagedCache(k, v)
-    tables = synth.disjoint_block_tables(seed, nb, [blocks] * (3 * n_sets))
-    order = synth.permutation(seed, n_slices)
+    tables = synth.disjoint_block_tables(w.seed, nb, [blocks] * (3 * n_sets))
+    order = synth.permutation(w.seed, n_slices)
     offsets = [int(j * (T // n_slices)) for j in range(n_slices)]   # j-th placed slice moves by 512*j
     sets = []
     for s in range(n_sets):
@@ -92,99 +117,138 @@ def main() -> int:
         chunk = kdn.alloc_chunk(cache, T, kdn.FMT_INT8_ROWSCALE)
         slices = [chunk.slice(int(i) * (T // n_slices), T // n_slices) for i in order]
         sets.append((src, dst_a, dst_b, chunk, slices))
-    kdn.kdn_rope_prepare(base, sh.D, offsets)
+    kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
+    for s in range(n_sets):                     # every chunk exists before any is read
+        kdn.kdn_store_chunk(cache, sets[s][0], 0, T, sets[s][3])
 
-    names = ("store", "load", "compose")
-    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in names] for _ in range(args.steps)]
-
-    def step(i, events=None):
+    def step(i, rec):
         # The chunk a step loads or composes was stored two or three steps earlier, with
         # gigabytes of traffic in between, so it comes from HBM, not from the cache.
         src, dst_a, dst_b, chunk, _ = sets[i % n_sets]
         load_chunk = sets[(i + 2) % n_sets][3]
         compose_slices = sets[(i + 1) % n_sets][4]
-        if events:
-            events[0][0].record()
-        kdn.kdn_store_chunk(cache, src, 0, T, chunk)
-        if events:
-            events[0][1].record()
-            events[1][0].record()
-        kdn.kdn_load_chunk(load_chunk, cache, dst_a, 0)
-        if events:
-            events[1][1].record()
-            events[2][0].record()
-        kdn.kdn_compose(compose_slices, offsets, cache, dst_b, base)
-        if events:
-            events[2][1].record()
+        rec("store", lambda: kdn.kdn_store_chunk(cache, src, 0, T, chunk))
+        rec("load", lambda: kdn.kdn_load_chunk(load_chunk, cache, dst_a, 0))
+        rec("compose", lambda: kdn.kdn_compose(compose_slices, offsets, cache, dst_b, w.rope_base))
 
-    for s in range(n_sets):                     # every chunk exists before any is read
-        kdn.kdn_store_chunk(cache, sets[s][0], 0, T, sets[s][3])
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i, ev[i])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-
-    if args.calibration_copy:
-        a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
-        b = torch.empty_like(a)
-        torch.cuda.synchronize()
-        b.copy_(a)                              # 1 GiB read, 1 GiB written
-        torch.cuda.synchronize()
-        del a, b
-
-    ms = {n: float(np.mean([ev[i][j][0].elapsed_time(ev[i][j][1]) for i in range(args.steps)]))
-          for j, n in enumerate(names)}
+    wall, ms = Timed(("store", "load", "compose"), args.steps).run(step, args.warmup)
     bytes_call = T * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)    # B_p + B_q per token
-    place_ms = 0.5 * (ms["load"] + ms["compose"])
-    achieved = bytes_call / (place_ms * 1e-3) / 1e9
-    tokens_per_s = T * args.steps / wall
-
-    out = {
-        "metric": "KV tokens composed/sec (store+load+RoPE shift) and achieved HBM GB/s",
-        "value": tokens_per_s,
-        "unit": "tokens/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": wall / args.steps * 1e3,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16 KV, int8 codes + fp32 scales stored, fp32 arithmetic",
-        "data": "synthetic N(0,1) bf16 KV, seeded; random disjoint block tables",
-        "config": {
-            "workload": "Llama-3-8B-shaped KV (L32 H8 D128 bs16): per step store 4096 tokens to int8, "
-                        "load them at offset 0, compose them as 8x512-token slices in seeded order with "
-                        "RoPE offsets 0..3584 (base %g); %d buffer sets cycled" % (base, n_sets),
-            "tokens_per_step": T,
-            "algorithmic_bytes_per_call": bytes_call,
-            "calls_per_step": 3,
-        },
-        "breakdown": {n: {"ms": ms[n], "GBps": bytes_call / (ms[n] * 1e-3) / 1e9,
-                          "frac_of_peak": bytes_call / (ms[n] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
-                      for n in names},
-        "roofline": {
-            "bound": "hbm",
-            "kernel": "k_place (load and compose launches)",
-            "achieved": achieved,
-            "peak": HBM_PEAK_GBPS,
-            "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": counter_traffic(),
-        },
+    res = {
+        "tokens_per_step": T, "wall": wall, "ms": ms,
+        "bytes": {n: bytes_call for n in ms},
+        "place_calls": ("load", "compose"),
+        "workload": "Llama-3-8B-shaped KV (L32 H8 D128 bs16): per step store 4096 tokens to int8, "
+                    "load them at offset 0, compose them as 8x512-token slices in seeded order with "
+                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled" % (w.rope_base, n_sets),
+        "traffic": counter_traffic(),
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cache, sets[0], order, offsets, base, T, n_slices, args.cpu_steps)
-    print(json.dumps(out))
-    return 0
+        res["cpu_baseline"] = cpu_baseline(cache, sets[0][0], order, offsets, w.rope_base, T, n_slices,
+                                           args.cpu_steps)
+    return res
 
 
-def cpu_baseline(cache, buf_set, order, offsets, base, T, n_slices, steps):
+def workload_70b(args, dev):
+    import torch
+    from paper_2409_13761_amd import kdn, synth
+
+    w = synth.WORKLOADS["70b_long"]
+    sh, T = w.shape, 32768
+    blocks = T // sh.bs
+    n_sets = 2
+    nb = n_sets * 2 * blocks
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+    v = torch.empty_like(k)
+    fill_normal(k, g)
+    fill_normal(v, g)
+    cache = kdn.PagedCache(k, v)
+    tables = synth.disjoint_block_tables(w.seed, nb, [blocks] * (2 * n_sets))
+    offsets = list(w.offsets)
+    sets = []
+    for s in range(n_sets):
+        src, dst = (torch.from_numpy(tables[2 * s + i]).to(dev) for i in range(2))
+        chunk = kdn.alloc_chunk(cache, T, kdn.FMT_INT8_ROWSCALE)
+        sets.append((src, dst, chunk, [chunk.slice(i * 8192, 8192) for i in range(4)]))
+    kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
+
+    def step(i, rec):
+        src, dst, chunk, slices = sets[i % n_sets]
+        rec("store", lambda: kdn.kdn_store_chunk(cache, src, 0, T, chunk))
+        rec("compose", lambda: kdn.kdn_compose(slices, offsets, cache, dst, w.rope_base))
+
+    wall, ms = Timed(("store", "compose"), args.steps).run(step, args.warmup)
+    bytes_call = T * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)
+    return {
+        "tokens_per_step": T, "wall": wall, "ms": ms, "bytes": {n: bytes_call for n in ms},
+        "place_calls": ("compose",),
+        "workload": "Llama-3-70B-shaped KV (L80 H8 D128 bs16): per step store 32768 tokens to int8 and "
+                    "compose them back as 4x8192-token slices with RoPE offsets 0/8192/16384/24576; "
+                    "%d buffer sets cycled" % n_sets,
+        "traffic": None,
+    }
+
+
+def workload_batched(args, dev):
+    import numpy as np
+    import torch
+    from paper_2409_13761_amd import kdn, synth
+
+    w = synth.WORKLOADS["batched_reuse"]
+    sh = w.shape
+    n_pool, n_req, per_req, Tc = w.extra["pool"], w.extra["requests"], 4, 1024
+    cb = Tc // sh.bs
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    # the pool: 256 chunks stored from 16 rounds of a 16384-token source cache
+    rb = 16 * cb
+    k = torch.empty((sh.L, rb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+    v = torch.empty_like(k)
+    src_cache = kdn.PagedCache(k, v)
+    pool = []
+    for rnd in range(n_pool // 16):
+        fill_normal(k, g)
+        fill_normal(v, g)
+        perm = synth.permutation(w.seed + 100 + rnd, rb)
+        for i in range(16):
+            out = kdn.alloc_chunk(src_cache, Tc, kdn.FMT_INT8_ROWSCALE)
+            kdn.kdn_store_chunk(src_cache, torch.from_numpy(perm[i * cb:(i + 1) * cb].copy()).to(dev), 0, Tc, out)
+            pool.append(out)
+        torch.cuda.synchronize()
+    del k, v, src_cache
+    draws = synth.zipf_distinct_draws(w.seed, n_req, per_req, n_pool, w.extra["alpha"])
+    blocks_req = per_req * cb
+    nb = n_req * blocks_req
+    tables = synth.disjoint_block_tables(w.seed, nb, [blocks_req] * n_req)
+    dst = kdn.PagedCache(torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16),
+                         torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16))
+    offsets = list(w.offsets)
+    plan = kdn.BatchPlan([([pool[int(c)] for c in draws[r]], offsets, torch.from_numpy(tables[r]).to(dev), 0)
+                          for r in range(n_req)])
+    kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
+
+    def step(i, rec):
+        rec("compose_batch", lambda: kdn.kdn_compose_batch(plan, dst, w.rope_base))
+
+    wall, ms = Timed(("compose_batch",), args.steps).run(step, args.warmup)
+    tokens = n_req * per_req * Tc
+    unique = int(len(np.unique(draws)))
+    return {
+        "tokens_per_step": tokens, "wall": wall, "ms": ms,
+        "bytes": {"compose_batch": tokens * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)},
+        "place_calls": ("compose_batch",),
+        "workload": "batched reuse (L32 H8 D128 bs16): 64 requests x 4 chunks of 1024 tokens drawn by "
+                    "Zipf(1.0) from a resident pool of 256 int8 chunks (%d distinct drawn), one batched "
+                    "compose per step into 64 disjoint random tables" % unique,
+        "extra": {"distinct_chunks": unique,
+                  "bytes_if_each_distinct_chunk_read_once":
+                      unique * Tc * sh.int8_bytes_per_token + tokens * sh.paged_bytes_per_token},
+        "traffic": None,
+    }
+
+
+def cpu_baseline(cache, src, order, offsets, base, T, n_slices, steps):
     """The oracle as it stands, on the host cores: the same step (store, load, compose
     of one 4096-token context, all layers), layers split over threads."""
     import numpy as np
@@ -192,7 +256,6 @@ def cpu_baseline(cache, buf_set, order, offsets, base, T, n_slices, steps):
     from oracle import kdn_oracle as O
 
     L, nb, bs, H, D = cache.shape
-    src, _, _, _, _ = buf_set
     blocks = T // bs
     # host copy of the source blocks only; destination blocks start as zeros
     hk = np.zeros((L, 3 * blocks, bs, H, D), dtype=np.uint16)
@@ -226,6 +289,89 @@ def cpu_baseline(cache, buf_set, order, offsets, base, T, n_slices, steps):
             "sample": "%d full steps of the same workload (store+load+compose of 4096 tokens, "
                       "all %d layers), layers split over %d threads" % (steps, L, cores),
             "seconds": dt}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", choices=("8b", "70b_long", "batched_reuse"), default="8b")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=8)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, a dispatch of known size for "
+                         "scaling hardware byte counters")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only; the path shards without any exchange "
+              "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
+        return 2
+    defaults = {"8b": (40, 8), "70b_long": (10, 3), "batched_reuse": (10, 3)}[args.workload]
+    args.steps = defaults[0] if args.steps is None else args.steps
+    args.warmup = defaults[1] if args.warmup is None else args.warmup
+
+    import torch
+    from paper_2409_13761_amd import kdn
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        return 3
+    kdn.lib()                                   # fail loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    res = {"8b": workload_8b, "70b_long": workload_70b, "batched_reuse": workload_batched}[args.workload](args, dev)
+
+    if args.calibration_copy:
+        a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                              # 1 GiB read, 1 GiB written
+        torch.cuda.synchronize()
+        del a, b
+
+    ms, nbytes = res["ms"], res["bytes"]
+    gbps = {n: nbytes[n] / (ms[n] * 1e-3) / 1e9 for n in ms}
+    place = res["place_calls"]
+    place_ms = sum(ms[n] for n in place) / len(place)
+    achieved = nbytes[place[0]] / (place_ms * 1e-3) / 1e9
+    out = {
+        "metric": METRIC,
+        "value": res["tokens_per_step"] * args.steps / res["wall"],
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": res["wall"] / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16 KV, int8 codes + fp32 scales stored, fp32 arithmetic",
+        "data": "synthetic N(0,1) bf16 KV, seeded; random disjoint block tables",
+        "config": {
+            "workload": res["workload"],
+            "tokens_per_step": res["tokens_per_step"],
+            "algorithmic_bytes_per_call": nbytes,
+            "calls_per_step": len(ms),
+        },
+        "breakdown": {n: {"ms": ms[n], "GBps": gbps[n], "frac_of_peak": gbps[n] / HBM_PEAK_GBPS} for n in ms},
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "k_place (%s launches)" % " and ".join(place),
+            "achieved": achieved,
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": res["traffic"],
+        },
+    }
+    if "extra" in res:
+        out["config"].update(res["extra"])
+    if "cpu_baseline" in res:
+        out["cpu_baseline"] = res["cpu_baseline"]
+    print(json.dumps(out))
+    return 0
 
 
 if __name__ == "__main__":

@@ -14,6 +14,7 @@
 // dense layout) and contiguous in the stored chunk.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -799,6 +800,12 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
         }
     }
     for (int f = 0; f < 2; ++f) {
+        // Segments that read the same stored rows run back to back, so that a popular
+        // chunk is fetched from HBM once and from the last-level cache afterwards.
+        if (n_reqs > 1)
+            std::stable_sort(segs[f].begin(), segs[f].end(), [](const Seg &a, const Seg &b) {
+                return a.data != b.data ? a.data < b.data : a.tok0 < b.tok0;
+            });
         st = place_segments(ds, p, f, segs[f], static_cast<hipStream_t>(stream));
         if (st != KDN_OK)
             return st;

@@ -17,6 +17,10 @@ compose of four 8192-token slices) and "batched_reuse" (64 requests x 4 chunks o
 1024 tokens drawn by Zipf popularity from a resident pool of 256 chunks, one batched
 compose per step).
 
+"host_stream_int8" / "host_stream_raw" compose a chunk that lives in pinned host memory
+(the rate there includes PCIe and is link bound; its roofline entry is still priced
+against HBM and is not a kernel-quality figure).
+
 Prints ONE JSON line: tokens/s over the whole step, the roofline of the dominant
 kernel (the place kernel behind load and compose) from HIP-event timings, and the
 CPU oracle's throughput on the host cores as a reported baseline.
@@ -248,6 +252,59 @@ def workload_batched(args, dev):
     }
 
 
+def workload_host_stream(args, dev, fmt_name):
+    """A 4096-token chunk that lives in pinned host memory is composed as 8 shifted slices:
+    the stored rows cross PCIe in their compact form, 4 layers per stage, while the previous
+    stage is dequantised and scattered.  The rate is link bound (PCIe-inclusive)."""
+    import torch
+    from paper_2409_13761_amd import kdn, synth
+
+    sh = synth.LLAMA8B
+    T, n_slices = 4096, 8
+    w = synth.WORKLOADS["rag_compose"]
+    fmt = kdn.FMT_INT8_ROWSCALE if fmt_name == "int8" else kdn.FMT_RAW_BF16
+    blocks = T // sh.bs
+    nb = 3 * blocks
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+    v = torch.empty_like(k)
+    fill_normal(k, g)
+    fill_normal(v, g)
+    cache = kdn.PagedCache(k, v)
+    src, dst_a, dst_b = (torch.from_numpy(t).to(dev) for t in
+                         synth.disjoint_block_tables(w.seed, nb, [blocks] * 3))
+    chunk = kdn.alloc_chunk(cache, T, fmt)
+    kdn.kdn_store_chunk(cache, src, 0, T, chunk)
+    torch.cuda.synchronize()
+    host = kdn.pinned_host_copy(chunk)
+    order = synth.permutation(w.seed, n_slices)
+    slices = [host.slice(int(i) * (T // n_slices), T // n_slices) for i in order]
+    offsets = [int(j * (T // n_slices)) for j in range(n_slices)]
+    lps = 4
+    staging = torch.empty(kdn.kdn_staging_bytes(slices, lps), dtype=torch.uint8, device=dev)
+    kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
+    dsts = (dst_a, dst_b)
+
+    def step(i, rec):
+        rec("compose_from_host", lambda: kdn.kdn_compose_from_host(
+            slices, offsets, cache, dsts[i % 2], w.rope_base, staging, lps))
+
+    wall, ms = Timed(("compose_from_host",), args.steps).run(step, args.warmup)
+    stored = T * (sh.int8_bytes_per_token if fmt_name == "int8" else sh.paged_bytes_per_token)
+    return {
+        "tokens_per_step": T, "wall": wall, "ms": ms,
+        "bytes": {"compose_from_host": stored + T * sh.paged_bytes_per_token},
+        "place_calls": ("compose_from_host",),
+        "workload": "Llama-3-8B-shaped KV: one 4096-token %s chunk in pinned host memory composed as "
+                    "8x512-token shifted slices, %d layers per stage (PCIe-inclusive, link bound)"
+                    % (fmt_name, lps),
+        "extra": {"stored_bytes_over_link": stored,
+                  "link_GBps": stored / (ms["compose_from_host"] * 1e-3) / 1e9},
+        "traffic": None,
+    }
+
+
 def cpu_baseline(cache, src, order, offsets, base, T, n_slices, steps):
     """The oracle as it stands, on the host cores: the same step (store, load, compose
     of one 4096-token context, all layers), layers split over threads."""
@@ -296,7 +353,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=("8b", "70b_long", "batched_reuse"), default="8b")
+    ap.add_argument("--workload", choices=("8b", "70b_long", "batched_reuse", "host_stream_int8", "host_stream_raw"),
+                    default="8b")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=8)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -307,7 +365,8 @@ def main() -> int:
         print("bench.py: this build runs on one GPU only; the path shards without any exchange "
               "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
         return 2
-    defaults = {"8b": (40, 8), "70b_long": (10, 3), "batched_reuse": (10, 3)}[args.workload]
+    defaults = {"8b": (40, 8), "70b_long": (10, 3), "batched_reuse": (10, 3),
+                "host_stream_int8": (10, 3), "host_stream_raw": (10, 3)}[args.workload]
     args.steps = defaults[0] if args.steps is None else args.steps
     args.warmup = defaults[1] if args.warmup is None else args.warmup
 
@@ -321,7 +380,9 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
-    res = {"8b": workload_8b, "70b_long": workload_70b, "batched_reuse": workload_batched}[args.workload](args, dev)
+    res = {"8b": workload_8b, "70b_long": workload_70b, "batched_reuse": workload_batched,
+           "host_stream_int8": lambda a, d: workload_host_stream(a, d, "int8"),
+           "host_stream_raw": lambda a, d: workload_host_stream(a, d, "raw")}[args.workload](args, dev)
 
     if args.calibration_copy:
         a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()

@@ -166,6 +166,30 @@ kdn_status kdn_compose(const kdn_chunk *chunks, const int32_t *offsets, int32_t 
 kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
                              const kdn_cache_desc *cache, double rope_base, void *stream);
 
+/* Compose from chunks held in pinned HOST memory: the delivery module's path from a
+ * storage device to the GPU (Sec. 3.1; bandwidth of loading KV into GPU memory, Sec. 3
+ * "Limited storage"; transfer over links, Sec. 3.2).  Same result as kdn_compose.
+ * chunks[i].data: [host], allocated with hipHostMalloc (or a pinned torch tensor), in the
+ * stored form; it must stay unchanged until `stream` has run the call.  The stored rows
+ * cross the link in their compact form, layers_per_stage layers at a time, into
+ * staging_dev [device, 16-byte aligned, at least kdn_staging_bytes(...) bytes] on a
+ * copy stream the library owns, while the previous stage is dequantised, rotated and
+ * scattered on `stream`: copy and kernels overlap, and the two halves of the staging
+ * buffer alternate.  The staging buffer may be reused by the next call on any stream.
+ * KDN_EINVAL if a chunk is not in pinned host memory, KDN_ESIZE if the staging buffer is
+ * too small. */
+kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                                 const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                                 int32_t table_len, int32_t dest_token_start, double rope_base,
+                                 void *staging_dev, uint64_t staging_bytes, int32_t layers_per_stage,
+                                 void *stream);
+
+/* Bytes of staging memory kdn_compose_from_host needs for these chunk views at this
+ * stage depth: two stages of compact rows; views of one host buffer share one staged
+ * copy of the token range they span; each copy is padded to 256 bytes.  0 on invalid
+ * arguments.  chunks: [host] array; the data they point to is not read. */
+uint64_t kdn_staging_bytes(const kdn_chunk *chunks, int32_t n_chunks, int32_t layers_per_stage);
+
 /* Make the cos/sin rows of the given offsets resident so that later composes with
  * them enqueue no copy (needed before capturing composes into a HIP graph).
  * offsets: [host] array of n. */

@@ -76,8 +76,9 @@ struct StoreP {
 };
 
 struct PlaceP {
-    CacheP c;
+    CacheP c;          // c.L counts the layers the stored rows hold (and the grid covers)
     const f32x2 *rope; // [rows][D/2] (cos, sin)
+    int32_t layer0;    // cache layer that stored layer 0 goes to
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
@@ -300,7 +301,7 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
         return;
     const int blk = sg.bt[tok_lo / bs];
     const int slot0 = tok_lo % bs;
-    uint16_t *tile = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(ls >> 1) * p.c.layer_stride
+    uint16_t *tile = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(p.layer0 + (ls >> 1)) * p.c.layer_stride
                      + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
     const int Tp = sg.Tp;
     const int64_t row_base = ((int64_t)ls * Tp + sg.tok0 + (tok_lo - S)) * H;
@@ -460,6 +461,12 @@ struct DeviceState {
     hipEvent_t seg_done[kSegSlots] = {};
     bool seg_used[kSegSlots] = {};
     int next_slot = 0;
+    // streaming of host-resident chunks: a copy stream and, per half of the caller's
+    // staging buffer, "filled" and "drained" events
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t filled[2] = {};
+    hipEvent_t drained[2] = {};
+    bool drained_valid[2] = {};
 };
 
 std::mutex g_mu;
@@ -775,6 +782,7 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
         return KDN_EDEVICE;
     PlaceP p;
     p.c = make_cache_p(cache);
+    p.layer0 = 0;
     std::vector<int32_t> rows(offs.size());
     st = rope_rows(ds, rope_base, cache->head_dim, offs.data(), (int32_t)offs.size(), rows.data(), &p.rope);
     if (st != KDN_OK)
@@ -811,6 +819,33 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
             return st;
     }
     return KDN_OK;
+}
+
+// Views of the same host buffer are staged once: the token range [lo, hi) that the
+// views of one buffer span crosses the link as one copy per stage.
+struct HostParent {
+    const uint8_t *data;
+    int32_t fmt, L, H, D, Tp, lo, hi;
+};
+
+void plan_host_parents(const kdn_chunk *chunks, int32_t n, std::vector<HostParent> &parents,
+                       std::vector<int32_t> &parent_of)
+{
+    parents.clear();
+    parent_of.assign((size_t)n, 0);
+    for (int32_t i = 0; i < n; ++i) {
+        const kdn_chunk &ch = chunks[i];
+        size_t k = 0;
+        for (; k < parents.size(); ++k)
+            if (parents[k].data == ch.data && parents[k].fmt == ch.fmt && parents[k].Tp == ch.parent_tokens)
+                break;
+        if (k == parents.size())
+            parents.push_back({static_cast<const uint8_t *>(ch.data), ch.fmt, ch.num_layers, ch.num_kv_heads,
+                               ch.head_dim, ch.parent_tokens, ch.token_start, ch.token_start + ch.num_tokens});
+        parents[k].lo = std::min(parents[k].lo, ch.token_start);
+        parents[k].hi = std::max(parents[k].hi, ch.token_start + ch.num_tokens);
+        parent_of[(size_t)i] = (int32_t)k;
+    }
 }
 
 } // namespace
@@ -943,6 +978,161 @@ kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
     return compose_impl(requests, n_requests, cache, rope_base, stream);
 }
 
+uint64_t kdn_staging_bytes(const kdn_chunk *chunks, int32_t n_chunks, int32_t layers_per_stage)
+{
+    if (!chunks || n_chunks <= 0 || layers_per_stage <= 0)
+        return 0;
+    std::vector<HostParent> parents;
+    std::vector<int32_t> parent_of;
+    plan_host_parents(chunks, n_chunks, parents, parent_of);
+    uint64_t stage = 0;
+    for (const HostParent &hp : parents) {
+        const uint64_t b = kdn_chunk_bytes(std::min(layers_per_stage, hp.L), hp.H, hp.D, hp.hi - hp.lo, hp.fmt);
+        if (b == 0)
+            return 0;
+        stage += (b + 255) & ~(uint64_t)255;
+    }
+    return 2 * stage;
+}
+
+kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                                 const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                                 int32_t table_len, int32_t dest_token_start, double rope_base,
+                                 void *staging_dev, uint64_t staging_bytes, int32_t layers_per_stage,
+                                 void *stream)
+{
+    if (!chunks || !offsets || n_chunks <= 0 || !block_table_dev || table_len <= 0
+        || dest_token_start < 0 || !staging_dev || layers_per_stage <= 0)
+        return KDN_EINVAL;
+    kdn_status st = check_cache(cache);
+    if (st != KDN_OK)
+        return st;
+    if (!aligned16(staging_dev))
+        return KDN_EALIGN;
+    int64_t total = dest_token_start;
+    for (int32_t i = 0; i < n_chunks; ++i) {
+        st = check_chunk(&chunks[i], cache);
+        if (st != KDN_OK)
+            return st;
+        hipPointerAttribute_t attr;
+        if (hipPointerGetAttributes(&attr, chunks[i].data) != hipSuccess) {
+            (void)hipGetLastError();
+            return KDN_EINVAL; // ordinary pageable memory
+        }
+        if (attr.type != hipMemoryTypeHost)
+            return KDN_EINVAL;
+        total += chunks[i].num_tokens;
+    }
+    if (total > (int64_t)table_len * cache->block_size)
+        return KDN_ERANGE;
+    const uint64_t need = kdn_staging_bytes(chunks, n_chunks, layers_per_stage);
+    if (need == 0 || staging_bytes < need)
+        return KDN_ESIZE;
+    std::vector<HostParent> parents;
+    std::vector<int32_t> parent_of;
+    plan_host_parents(chunks, n_chunks, parents, parent_of);
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *ds = device_state(nullptr);
+    if (!ds)
+        return KDN_EDEVICE;
+    if (!ds->copy_stream) {
+        if (hipStreamCreateWithFlags(&ds->copy_stream, hipStreamNonBlocking) != hipSuccess)
+            return KDN_EDEVICE;
+        for (int b = 0; b < 2; ++b)
+            if (hipEventCreateWithFlags(&ds->filled[b], hipEventDisableTiming) != hipSuccess
+                || hipEventCreateWithFlags(&ds->drained[b], hipEventDisableTiming) != hipSuccess)
+                return KDN_EDEVICE;
+    }
+    hipStream_t user = static_cast<hipStream_t>(stream);
+    PlaceP p;
+    p.c = make_cache_p(cache);
+    std::vector<int32_t> rows((size_t)n_chunks);
+    st = rope_rows(ds, rope_base, cache->head_dim, offsets, n_chunks, rows.data(), &p.rope);
+    if (st != KDN_OK)
+        return st;
+
+    const int32_t L = cache->num_layers, H = cache->num_kv_heads, D = cache->head_dim;
+    uint8_t *staging = static_cast<uint8_t *>(staging_dev);
+    const uint64_t half_bytes = need / 2;
+    std::vector<uint8_t *> staged(parents.size());
+    int stage_no = 0;
+    for (int32_t l0 = 0; l0 < L; l0 += layers_per_stage, ++stage_no) {
+        const int32_t Lg = std::min(layers_per_stage, L - l0);
+        const int b = stage_no & 1;
+        uint8_t *buf = staging + (uint64_t)b * half_bytes;
+        // the copy may overwrite this half only after the kernel that last read it
+        if (ds->drained_valid[b] && hipStreamWaitEvent(ds->copy_stream, ds->drained[b], 0) != hipSuccess)
+            return KDN_EDEVICE;
+        uint64_t at = 0;
+        for (size_t k = 0; k < parents.size(); ++k) {
+            const HostParent &hp = parents[k];
+            const int32_t Tu = hp.hi - hp.lo, Tp = hp.Tp;
+            const uint64_t esz = hp.fmt == KDN_FMT_RAW_BF16 ? 2 : 1;
+            uint8_t *dst = buf + at;
+            staged[k] = dst;
+            // rows of layers [l0, l0+Lg), both sides, tokens [lo, hi) of this host buffer:
+            // 2*Lg planes of Tu*H*D elements, Tp*H*D apart
+            const uint64_t w_codes = (uint64_t)Tu * H * D * esz, pitch_codes = (uint64_t)Tp * H * D * esz;
+            const uint8_t *src_codes = hp.data + ((uint64_t)l0 * 2 * Tp + hp.lo) * H * D * esz;
+            hipError_t e;
+            if (Tu == Tp)
+                e = hipMemcpyAsync(dst, src_codes, w_codes * 2 * Lg, hipMemcpyHostToDevice, ds->copy_stream);
+            else
+                e = hipMemcpy2DAsync(dst, w_codes, src_codes, pitch_codes, w_codes, (size_t)2 * Lg,
+                                     hipMemcpyHostToDevice, ds->copy_stream);
+            if (e != hipSuccess)
+                return KDN_EDEVICE;
+            if (hp.fmt == KDN_FMT_INT8_ROWSCALE) {
+                const uint64_t w_sc = (uint64_t)Tu * H * 4, pitch_sc = (uint64_t)Tp * H * 4;
+                const uint8_t *src_sc = hp.data + (uint64_t)L * 2 * Tp * H * D
+                                        + ((uint64_t)l0 * 2 * Tp + hp.lo) * H * 4;
+                uint8_t *dst_sc = dst + w_codes * 2 * Lg;
+                if (Tu == Tp)
+                    e = hipMemcpyAsync(dst_sc, src_sc, w_sc * 2 * Lg, hipMemcpyHostToDevice, ds->copy_stream);
+                else
+                    e = hipMemcpy2DAsync(dst_sc, w_sc, src_sc, pitch_sc, w_sc, (size_t)2 * Lg,
+                                         hipMemcpyHostToDevice, ds->copy_stream);
+                if (e != hipSuccess)
+                    return KDN_EDEVICE;
+            }
+            const uint64_t bytes = kdn_chunk_bytes(Lg, H, D, Tu, hp.fmt);
+            at += (bytes + 255) & ~(uint64_t)255;
+        }
+        std::vector<Seg> segs[2];
+        int32_t S = dest_token_start;
+        for (int32_t i = 0; i < n_chunks; ++i) {
+            const kdn_chunk &ch = chunks[i];
+            const HostParent &hp = parents[parent_of[i]];
+            Seg s;
+            s.data = staged[parent_of[i]];
+            s.bt = block_table_dev;
+            s.Tp = hp.hi - hp.lo;
+            s.tok0 = ch.token_start - hp.lo;
+            s.T = ch.num_tokens;
+            s.S = S;
+            s.rope_row = rows[i];
+            s.pad = 0;
+            segs[ch.fmt].push_back(s);
+            S += ch.num_tokens;
+        }
+        if (hipEventRecord(ds->filled[b], ds->copy_stream) != hipSuccess
+            || hipStreamWaitEvent(user, ds->filled[b], 0) != hipSuccess)
+            return KDN_EDEVICE;
+        p.c.L = Lg;
+        p.layer0 = l0;
+        for (int f = 0; f < 2; ++f) {
+            st = place_segments(ds, p, f, segs[f], user);
+            if (st != KDN_OK)
+                return st;
+        }
+        if (hipEventRecord(ds->drained[b], user) != hipSuccess)
+            return KDN_EDEVICE;
+        ds->drained_valid[b] = true;
+    }
+    return KDN_OK;
+}
+
 kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *offsets, int32_t n)
 {
     if (!offsets || n <= 0)
@@ -1024,6 +1214,13 @@ kdn_status kdn_shutdown(void)
         for (int i = 0; i < kSegSlots; ++i)
             if (ds.seg_done[i])
                 (void)hipEventDestroy(ds.seg_done[i]);
+        if (ds.copy_stream) {
+            (void)hipStreamDestroy(ds.copy_stream);
+            for (int b = 0; b < 2; ++b) {
+                (void)hipEventDestroy(ds.filled[b]);
+                (void)hipEventDestroy(ds.drained[b]);
+            }
+        }
     }
     g_dev.clear();
     (void)hipSetDevice(cur);

@@ -76,6 +76,12 @@ def lib() -> C.CDLL:
         L.kdn_compose_batch.restype = C.c_int
         L.kdn_compose_batch.argtypes = [C.POINTER(RequestDesc), i32, C.POINTER(CacheDesc),
                                         C.c_double, vp]
+        L.kdn_compose_from_host.restype = C.c_int
+        L.kdn_compose_from_host.argtypes = [C.POINTER(ChunkDesc), C.POINTER(i32), i32,
+                                            C.POINTER(CacheDesc), vp, i32, i32, C.c_double,
+                                            vp, u64, i32, vp]
+        L.kdn_staging_bytes.restype = u64
+        L.kdn_staging_bytes.argtypes = [C.POINTER(ChunkDesc), i32, i32]
         L.kdn_rope_prepare.restype = C.c_int
         L.kdn_rope_prepare.argtypes = [C.c_double, i32, C.POINTER(i32), i32]
         L.kdn_validate_block_table.restype = C.c_int
@@ -94,7 +100,8 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk",
-           "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_rope_prepare",
+           "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_from_host",
+           "kdn_staging_bytes", "kdn_rope_prepare",
            "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version"]
 
@@ -271,6 +278,34 @@ def kdn_compose_batch(plan_or_requests, cache: PagedCache, rope_base: float, str
     cd = cache.desc()
     _check(lib().kdn_compose_batch(plan.arr, plan.n, C.byref(cd), float(rope_base), _stream(stream)),
            "kdn_compose_batch")
+
+
+def pinned_host_copy(chunk: Chunk) -> Chunk:
+    """The same stored bytes in pinned host memory (a torch pinned tensor), described as
+    a chunk whose data pointer is a host address, for kdn_compose_from_host."""
+    host = torch.empty(chunk.data.shape, dtype=torch.uint8, pin_memory=True)
+    host.copy_(chunk.data)
+    d = ChunkDesc.from_buffer_copy(chunk.desc)
+    d.data = host.data_ptr()
+    return Chunk(host, d)
+
+
+def kdn_staging_bytes(chunks, layers_per_stage: int) -> int:
+    return int(lib().kdn_staging_bytes(_chunk_array(chunks), len(chunks), layers_per_stage))
+
+
+def kdn_compose_from_host(chunks, offsets, cache: PagedCache, block_table: torch.Tensor,
+                          rope_base: float, staging: torch.Tensor, layers_per_stage: int,
+                          dest_token_start: int = 0, stream=None) -> None:
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous()
+    assert len(chunks) == len(offsets) and staging.is_cuda and staging.is_contiguous()
+    cd = cache.desc()
+    arr = _chunk_array(chunks)
+    off = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
+    _check(lib().kdn_compose_from_host(arr, off, len(chunks), C.byref(cd), block_table.data_ptr(),
+                                       block_table.numel(), dest_token_start, float(rope_base),
+                                       staging.data_ptr(), staging.numel() * staging.element_size(),
+                                       layers_per_stage, _stream(stream)), "kdn_compose_from_host")
 
 
 def kdn_rope_prepare(rope_base: float, head_dim: int, offsets) -> None:

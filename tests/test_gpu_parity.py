@@ -282,3 +282,38 @@ def test_rope_prepare_then_compose_and_shutdown_are_repeatable():
         assert_cache_equal(dd, hd)
         torch.cuda.synchronize()
         kdn.kdn_shutdown()
+
+
+# ------------------------------------------------------------------ chunks streamed from host memory
+@pytest.mark.parametrize("layers_per_stage", [1, 2, 3, 8])
+def test_compose_from_pinned_host_chunks_equals_compose(layers_per_stage):
+    """Stored chunks (int8 and raw, whole and sliced) that live in pinned host memory are
+    streamed in stages of layers; the result is the oracle's compose."""
+    L, nb, bs, H, D = 5, 64, 16, 2, 64
+    _say("compose_from_host layers_per_stage=%d" % layers_per_stage)
+    src = host_cache(71, L, nb, bs, H, D)
+    t1, t2, t3, dst_bt = synth.disjoint_block_tables(71, nb, [6, 5, 4, 20])
+    a = O.store(src, t1, 0, 90, INT8)
+    b = O.store(src, t2, 3, 70, RAW)
+    c = O.store(src, t3, 0, 64, INT8)
+    chunks = [a.slice(10, 75), b, c, a.slice(0, 10), b.slice(20, 31)]
+    offsets = [0, 75, -12, 300, 7]
+    hd = host_cache(72, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose(chunks, offsets, hd, dst_bt, 10000.0, dest=5)
+    ha, hb, hc = (kdn.pinned_host_copy(chunk_to_dev(x)) for x in (a, b, c))
+    hchunks = [ha.slice(10, 75), hb, hc, ha.slice(0, 10), hb.slice(20, 31)]
+    need = kdn.kdn_staging_bytes(hchunks, layers_per_stage)
+    assert need > 0
+    staging = torch.empty(need, dtype=torch.uint8, device="cuda")
+    for _ in range(2):          # a second call reuses the staging halves
+        kdn.kdn_compose_from_host(hchunks, offsets, dd, dev_table(dst_bt), 10000.0, staging,
+                                  layers_per_stage, dest_token_start=5)
+    assert_cache_equal(dd, hd)
+    small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(kdn.KdnError) as e:
+        kdn.kdn_compose_from_host(hchunks, offsets, dd, dev_table(dst_bt), 10000.0, small, layers_per_stage)
+    assert e.value.status == kdn.ESIZE
+    with pytest.raises(kdn.KdnError) as e:       # device-resident chunks are refused here
+        kdn.kdn_compose_from_host([chunk_to_dev(c)], [0], dd, dev_table(dst_bt), 10000.0, staging, layers_per_stage)
+    assert e.value.status == kdn.EINVAL

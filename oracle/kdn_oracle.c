@@ -29,7 +29,8 @@
 #include <stdint.h>
 #include <string.h>
 
-enum { KDNO_FMT_RAW_BF16 = 0, KDNO_FMT_INT8_ROWSCALE = 1 };
+enum { KDNO_FMT_RAW_BF16 = 0, KDNO_FMT_INT8_ROWSCALE = 1, KDNO_FMT_INT4_GROUP32 = 2 };
+enum { KDNO_GROUP = 32 };
 
 /* Engine paged KV memory (Sec. 3.2, "paged memory" of the serving engine).
  * READING: per layer l and side (K or V) an array addressed as
@@ -77,12 +78,18 @@ void kdno_f32_to_bf16_array(const float *in, uint16_t *out, int64_t n)
  *   raw  : bf16  [L][2][Tp][H][D]                      (side 0 = K, 1 = V)
  *   int8 : int8  [L][2][Tp][H][D]   codes, then
  *          fp32  [L][2][Tp][H]      one scale per (token, kv-head) row.
+ *   int4 : uint8 [L][2][Tp][H][D/2] two codes per byte (element 2k in the low
+ *                                   nibble, 2k+1 in the high nibble, two's
+ *                                   complement), then
+ *          fp32  [L][2][Tp][H][D/32] one scale per group of 32 elements.
  * Tokens stay sliceable: a view is (Tp, tok_start, T). */
 int64_t kdno_chunk_bytes(int32_t L, int32_t H, int32_t D, int32_t Tp, int32_t fmt)
 {
     int64_t rows = (int64_t)L * 2 * Tp * H;
     if (fmt == KDNO_FMT_RAW_BF16)
         return rows * D * 2;
+    if (fmt == KDNO_FMT_INT4_GROUP32)
+        return rows * (D / 2) + rows * (D / KDNO_GROUP) * 4;
     return rows * D + rows * 4;
 }
 
@@ -139,6 +146,52 @@ void kdno_dequantise_row(const int8_t *q, float scale, int32_t D, float *y)
         y[j] = (float)q[j] * scale;
 }
 
+/* ---- group-wise symmetric int4 ----------------------------------------------
+ * READING (a tighter stored form toward the footprint reductions of Sec. 3.2,
+ * "KV-cache delivery"): the row is cut into groups of 32 consecutive elements.
+ * Per group: amax = max|x_j|; a group with amax < 2^-121 is stored as scale 0,
+ * codes 0; otherwise scale = amax/7, inv = 7/amax (IEEE fp32 divisions) and
+ * q_j = clamp(rint(x_j * inv), -7, 7), ties to even.  Codes are packed two per
+ * byte as two's-complement nibbles, the even element in the low nibble.  D must
+ * be a multiple of 32. */
+void kdno_quantise_row_int4(const uint16_t *x, int32_t D, uint8_t *packed, float *scales)
+{
+    for (int32_t g = 0; g < D / KDNO_GROUP; ++g) {
+        const uint16_t *xg = x + g * KDNO_GROUP;
+        float amax = 0.0f;
+        for (int32_t j = 0; j < KDNO_GROUP; ++j) {
+            float a = fabsf(kdno_bf16_to_f32(xg[j]));
+            if (a > amax)
+                amax = a;
+        }
+        int keep = !(amax < 0x1p-121f);
+        scales[g] = keep ? amax / 7.0f : 0.0f;
+        float inv = keep ? 7.0f / amax : 0.0f;
+        for (int32_t j = 0; j < KDNO_GROUP; j += 2) {
+            int q[2];
+            for (int32_t e = 0; e < 2; ++e) {
+                float r = keep ? rintf(kdno_bf16_to_f32(xg[j + e]) * inv) : 0.0f;
+                if (r > 7.0f)
+                    r = 7.0f;
+                if (r < -7.0f)
+                    r = -7.0f;
+                q[e] = (int)r;
+            }
+            packed[(g * KDNO_GROUP + j) / 2] = (uint8_t)((q[0] & 0xF) | ((q[1] & 0xF) << 4));
+        }
+    }
+}
+
+/* READING: y_j = (float)q_j * scale_group(j), one fp32 multiply. */
+void kdno_dequantise_row_int4(const uint8_t *packed, const float *scales, int32_t D, float *y)
+{
+    for (int32_t j = 0; j < D; ++j) {
+        int nib = (packed[j / 2] >> (4 * (j & 1))) & 0xF;
+        int q = nib >= 8 ? nib - 16 : nib;
+        y[j] = (float)q * scales[j / KDNO_GROUP];
+    }
+}
+
 /* ---- RoPE shift -------------------------------------------------------------
  * READING (reuse of a chunk "at different positions", Sec. 3.2 blending): keys
  * carry rotary position embedding; moving a chunk by d positions multiplies
@@ -183,10 +236,14 @@ int kdno_store(const kdno_cache *c, const int32_t *bt, int32_t table_len,
     if (t0 < 0 || T < 0 || (int64_t)t0 + T > (int64_t)table_len * c->bs)
         return -1;
     const int32_t H = c->H, D = c->D;
+    if (fmt == KDNO_FMT_INT4_GROUP32 && D % KDNO_GROUP != 0)
+        return -1;
     int64_t n_rows = (int64_t)c->L * 2 * T * H;
     uint16_t *raw = (uint16_t *)out;
     int8_t *codes = (int8_t *)out;
     float *scales = (float *)((char *)out + n_rows * D);
+    uint8_t *codes4 = (uint8_t *)out;
+    float *scales4 = (float *)((char *)out + n_rows * (D / 2));
     for (int32_t l = l0; l < l1; ++l)
         for (int32_t side = 0; side < 2; ++side)
             for (int32_t t = 0; t < T; ++t) {
@@ -200,6 +257,8 @@ int kdno_store(const kdno_cache *c, const int32_t *bt, int32_t table_len,
                     int64_t r = row_index(l, side, T, t, H, h);
                     if (fmt == KDNO_FMT_RAW_BF16)
                         memcpy(raw + r * D, src, (size_t)D * 2);
+                    else if (fmt == KDNO_FMT_INT4_GROUP32)
+                        kdno_quantise_row_int4(src, D, codes4 + r * (D / 2), scales4 + r * (D / KDNO_GROUP));
                     else
                         kdno_quantise_row(src, D, codes + r * D, scales + r);
                 }
@@ -221,8 +280,10 @@ static int place(const void *data, int32_t fmt, int32_t Tp, int32_t tok_start,
     const uint16_t *raw = (const uint16_t *)data;
     const int8_t *codes = (const int8_t *)data;
     const float *scales = (const float *)((const char *)data + n_rows * D);
+    const uint8_t *codes4 = (const uint8_t *)data;
+    const float *scales4 = (const float *)((const char *)data + n_rows * (D / 2));
     float y[4096];
-    if (D > 4096)
+    if (D > 4096 || (fmt == KDNO_FMT_INT4_GROUP32 && D % KDNO_GROUP != 0))
         return -1;
     for (int32_t l = l0; l < l1; ++l)
         for (int32_t side = 0; side < 2; ++side)
@@ -243,6 +304,8 @@ static int place(const void *data, int32_t fmt, int32_t Tp, int32_t tok_start,
                     if (fmt == KDNO_FMT_RAW_BF16) {
                         for (int32_t j = 0; j < D; ++j)
                             y[j] = kdno_bf16_to_f32(raw[r * D + j]);
+                    } else if (fmt == KDNO_FMT_INT4_GROUP32) {
+                        kdno_dequantise_row_int4(codes4 + r * (D / 2), scales4 + r * (D / KDNO_GROUP), D, y);
                     } else {
                         kdno_dequantise_row(codes + r * D, scales[r], D, y);
                     }

@@ -19,6 +19,8 @@ _LIB = os.path.join(_HERE, "libkdn_oracle.so")
 
 FMT_RAW_BF16 = 0
 FMT_INT8_ROWSCALE = 1
+FMT_INT4_GROUP32 = 2
+GROUP = 32
 
 
 def build(force: bool = False) -> str:
@@ -60,6 +62,10 @@ def lib():
             L.kdno_chunk_bytes.argtypes = [C.c_int32] * 5
             L.kdno_quantise_row.restype = None
             L.kdno_quantise_row.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+            L.kdno_quantise_row_int4.restype = None
+            L.kdno_quantise_row_int4.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+            L.kdno_dequantise_row_int4.restype = None
+            L.kdno_dequantise_row_int4.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
             L.kdno_dequantise_row.restype = None
             L.kdno_dequantise_row.argtypes = [C.c_void_p, C.c_float, C.c_int32, C.c_void_p]
             L.kdno_rope_table.restype = None
@@ -139,6 +145,16 @@ class Chunk:
         assert self.fmt == FMT_RAW_BF16
         return self.data.view(np.uint16).reshape(self.L, 2, self.Tp, self.H, self.D)
 
+    def packed4(self) -> np.ndarray:
+        assert self.fmt == FMT_INT4_GROUP32
+        n = self.L * 2 * self.Tp * self.H * (self.D // 2)
+        return self.data[:n].reshape(self.L, 2, self.Tp, self.H, self.D // 2)
+
+    def scales4(self) -> np.ndarray:
+        assert self.fmt == FMT_INT4_GROUP32
+        n = self.L * 2 * self.Tp * self.H * (self.D // 2)
+        return self.data[n:].view(np.float32).reshape(self.L, 2, self.Tp, self.H, self.D // GROUP)
+
 
 def chunk_bytes(L: int, H: int, D: int, Tp: int, fmt: int) -> int:
     return int(lib().kdno_chunk_bytes(L, H, D, Tp, fmt))
@@ -169,6 +185,22 @@ def dequantise_row(q: np.ndarray, scale) -> np.ndarray:
     q = np.ascontiguousarray(q, dtype=np.int8)
     y = np.empty(q.size, dtype=np.float32)
     lib().kdno_dequantise_row(_ptr(q), C.c_float(float(scale)), q.size, _ptr(y))
+    return y
+
+
+def quantise_row_int4(x_bf16: np.ndarray):
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    packed = np.empty(x.size // 2, dtype=np.uint8)
+    s = np.empty(x.size // GROUP, dtype=np.float32)
+    lib().kdno_quantise_row_int4(_ptr(x), x.size, _ptr(packed), _ptr(s))
+    return packed, s
+
+
+def dequantise_row_int4(packed: np.ndarray, scales: np.ndarray) -> np.ndarray:
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    scales = np.ascontiguousarray(scales, dtype=np.float32)
+    y = np.empty(packed.size * 2, dtype=np.float32)
+    lib().kdno_dequantise_row_int4(_ptr(packed), _ptr(scales), y.size, _ptr(y))
     return y
 
 

@@ -12,7 +12,7 @@ import torch
 
 from paper_2409_13761_amd import synth
 
-RAW, INT8 = 0, 1
+RAW, INT8, INT4 = 0, 1, 2
 
 
 def bf16_bits_to_f64(b):
@@ -266,6 +266,97 @@ def test_zero_and_tiny_rows(oracle):
     assert np.all(np.abs(bf16_bits_to_f64(db) - y) <= float(s) * 0.5001)
 
 
+# ------------------------------------------------------------------- int4, groups of 32
+def unpack_nibbles(packed):
+    """Independent decode: even element in the low nibble, two's complement."""
+    lo = (packed & 0xF).astype(np.int8)
+    hi = (packed >> 4).astype(np.int8)
+    lo = np.where(lo >= 8, lo - 16, lo)
+    hi = np.where(hi >= 8, hi - 16, hi)
+    return np.stack([lo, hi], axis=-1).reshape(packed.shape[:-1] + (packed.shape[-1] * 2,))
+
+
+def test_golden_int4_groups(oracle):
+    """Hand-worked groups from tests/golden/int4_groups.txt (first 8 elements of a group
+    are listed, the other 24 are zero)."""
+    path = os.path.join(os.path.dirname(__file__), "golden", "int4_groups.txt")
+    n = 0
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        xs, bs_, sc = (p.strip() for p in line.split("|"))
+        x = np.zeros(32, dtype=np.float32)
+        vals = [float(t) for t in xs.split()]
+        x[:len(vals)] = vals
+        xb = torch.from_numpy(x).to(torch.bfloat16)
+        assert np.array_equal(xb.float().numpy(), x)
+        packed, s = oracle.quantise_row_int4(xb.view(torch.int16).numpy().view(np.uint16))
+        want = [int(t, 16) for t in bs_.split()]
+        assert packed[:len(want)].tolist() == want and not packed[len(want):].any()
+        assert float(s[0]) == float(sc)
+        n += 1
+    assert n >= 4
+
+
+def test_int4_codes_scales_and_error_bound(oracle):
+    D = 128
+    rows = _rows(35, 300, D)
+    for r in rows:
+        x = bf16_bits_to_f64(r)
+        packed, s = oracle.quantise_row_int4(r)
+        q = unpack_nibbles(packed).astype(np.float64)
+        xg, qg = x.reshape(-1, 32), q.reshape(-1, 32)
+        amax = np.max(np.abs(xg), axis=1)
+        assert np.array_equal(s, (amax / 7.0).astype(np.float32))       # exact quotient, one rounding
+        assert np.all(np.max(np.abs(qg), axis=1) == 7) and q.min() >= -7
+        exact = 7.0 * xg / amax[:, None]
+        near_tie = np.abs(np.abs(exact - np.floor(exact)) - 0.5) < 2.0 ** -16
+        assert not np.any((qg != np.rint(exact)) & ~near_tie)
+        y = oracle.dequantise_row_int4(packed, s).astype(np.float64)
+        assert np.all(np.abs(x - y) <= np.repeat(s.astype(np.float64), 32) * (0.5 + 1e-4))
+        assert np.array_equal(y.astype(np.float32), (q * np.repeat(s.astype(np.float64), 32)).astype(np.float32))
+
+
+def test_int4_groups_are_independent_and_tiny_groups_flush(oracle):
+    D = 64
+    r = _rows(36, 1, D)[0].copy()
+    p0, s0 = oracle.quantise_row_int4(r)
+    r2 = r.copy()
+    r2[32:] = _rows(37, 1, D)[0][32:]
+    p1, s1 = oracle.quantise_row_int4(r2)
+    assert np.array_equal(p0[:16], p1[:16]) and s0[0] == s1[0] and not np.array_equal(p0[16:], p1[16:])
+    z = np.zeros(D, dtype=np.uint16)
+    z[5] = 0x8000
+    z[40] = 0x02FF                       # below 2^-121: the group is flushed
+    p, s = oracle.quantise_row_int4(z)
+    assert not p.any() and not s.any()
+    z[41] = 0x0300                       # exactly 2^-121: kept
+    p, s = oracle.quantise_row_int4(z)
+    assert s[0] == 0 and s[1] > 0 and unpack_nibbles(p)[41] == 7
+
+
+def test_int4_every_bf16_value_against_mathematical_rounding(oracle):
+    allb = np.arange(0, 65536, dtype=np.uint32)
+    allb = allb[(allb & 0x7F80) != 0x7F80].astype(np.uint16)
+    vals = bf16_bits_to_f64(allb)
+    n_slop = 0
+    for amax_bits in (0x3F80, 0x40E0, 0x4049, 0x0880, 0x7E12):
+        amax = float(bf16_bits_to_f64(np.array([amax_bits]))[0])
+        xb = allb[np.abs(vals) <= amax]
+        xb = np.concatenate([xb, np.zeros((-len(xb)) % 31, dtype=np.uint16)])
+        for grp in xb.reshape(-1, 31):
+            g = np.concatenate([[np.uint16(amax_bits)], grp])
+            packed, s = oracle.quantise_row_int4(g)
+            q = unpack_nibbles(packed).astype(np.float64)
+            exact = 7.0 * bf16_bits_to_f64(g) / amax
+            bad = q != np.rint(exact)
+            near_tie = np.abs(np.abs(exact - np.floor(exact)) - 0.5) < 2.0 ** -16
+            assert not np.any(bad & ~near_tie)
+            n_slop += int(bad.sum())
+    assert n_slop < 500
+
+
 # --------------------------------------------------------------------- rotation
 def test_rope_table_values(oracle):
     for base, D, d in ((10000.0, 64, 256), (500000.0, 128, 24576), (10000.0, 128, -777)):
@@ -343,7 +434,7 @@ def test_rotation_keeps_pair_norm_and_inverts(oracle):
 
 # ----------------------------------------------------------------------- compose
 def _setup_compose(oracle, fmt, seed=41):
-    L, nb, bs, H, D = 2, 48, 8, 2, 32
+    L, nb, bs, H, D = 2, 48, 8, 2, 64
     src = make_cache(oracle, seed, L, nb, bs, H, D)
     t1, t2, t3, dst_bt = synth.disjoint_block_tables(seed, nb, [4, 3, 5, 12])
     chunks = [oracle.store(src, t1, 0, 29, fmt), oracle.store(src, t2, 2, 20, fmt),
@@ -351,7 +442,7 @@ def _setup_compose(oracle, fmt, seed=41):
     return src, chunks, dst_bt
 
 
-@pytest.mark.parametrize("fmt", [RAW, INT8])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
 def test_zero_offset_compose_is_concatenation(oracle, fmt):
     src, chunks, dst_bt = _setup_compose(oracle, fmt)
     a = make_cache(oracle, 77, src.L, src.nb, src.bs, src.H, src.D)
@@ -369,7 +460,10 @@ def test_zero_offset_compose_is_concatenation(oracle, fmt):
         if fmt == RAW:
             rows = c.raw()
         else:
-            y = c.codes().astype(np.float32) * c.scales()[..., None]
+            if fmt == INT8:
+                y = c.codes().astype(np.float32) * c.scales()[..., None]
+            else:
+                y = unpack_nibbles(c.packed4()).astype(np.float32) * np.repeat(c.scales4(), 32, axis=-1)
             rows = torch.from_numpy(y).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
         for t in range(c.T):
             blk, slot = int(dst_bt[(S + t) // bs]), (S + t) % bs
@@ -378,7 +472,7 @@ def test_zero_offset_compose_is_concatenation(oracle, fmt):
         S += c.T
 
 
-@pytest.mark.parametrize("fmt", [RAW, INT8])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
 def test_compose_equals_independent_single_chunk_composes(oracle, fmt):
     src, chunks, dst_bt = _setup_compose(oracle, fmt, seed=42)
     offs = [0, 29, -7]

@@ -38,6 +38,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 METRIC = "KV tokens composed/sec (store+load+RoPE shift) and achieved HBM GB/s"
+FMT_IDS = {"raw": 0, "int8": 1, "int4": 2}
 
 # HBM bytes per k_place launch of the default workload from the FETCH_SIZE / WRITE_SIZE
 # counter runs summarised under profiles/, valid only for the kernel source they were
@@ -118,7 +119,7 @@ def workload_8b(args, dev):
     sets = []
     for s in range(n_sets):
         src, dst_a, dst_b = (torch.from_numpy(tables[3 * s + i]).to(dev) for i in range(3))
-        chunk = kdn.alloc_chunk(cache, T, kdn.FMT_INT8_ROWSCALE)
+        chunk = kdn.alloc_chunk(cache, T, FMT_IDS[args.fmt])
         slices = [chunk.slice(int(i) * (T // n_slices), T // n_slices) for i in order]
         sets.append((src, dst_a, dst_b, chunk, slices))
     kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
@@ -136,17 +137,17 @@ def workload_8b(args, dev):
         rec("compose", lambda: kdn.kdn_compose(compose_slices, offsets, cache, dst_b, w.rope_base))
 
     wall, ms = Timed(("store", "load", "compose"), args.steps).run(step, args.warmup)
-    bytes_call = T * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)    # B_p + B_q per token
+    bytes_call = T * (sh.paged_bytes_per_token + sh.stored_bytes_per_token(args.fmt))   # B_p + B_q per token
     res = {
         "tokens_per_step": T, "wall": wall, "ms": ms,
         "bytes": {n: bytes_call for n in ms},
         "place_calls": ("load", "compose"),
-        "workload": "Llama-3-8B-shaped KV (L32 H8 D128 bs16): per step store 4096 tokens to int8, "
+        "workload": "Llama-3-8B-shaped KV (L32 H8 D128 bs16): per step store 4096 tokens to %s, "
                     "load them at offset 0, compose them as 8x512-token slices in seeded order with "
-                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled" % (w.rope_base, n_sets),
-        "traffic": counter_traffic(),
+                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled" % (args.fmt, w.rope_base, n_sets),
+        "traffic": counter_traffic() if args.fmt == "int8" else None,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.fmt == "int8":
         res["cpu_baseline"] = cpu_baseline(cache, sets[0][0], order, offsets, w.rope_base, T, n_slices,
                                            args.cpu_steps)
     return res
@@ -173,7 +174,7 @@ def workload_70b(args, dev):
     sets = []
     for s in range(n_sets):
         src, dst = (torch.from_numpy(tables[2 * s + i]).to(dev) for i in range(2))
-        chunk = kdn.alloc_chunk(cache, T, kdn.FMT_INT8_ROWSCALE)
+        chunk = kdn.alloc_chunk(cache, T, FMT_IDS[args.fmt])
         sets.append((src, dst, chunk, [chunk.slice(i * 8192, 8192) for i in range(4)]))
     kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
 
@@ -183,13 +184,13 @@ def workload_70b(args, dev):
         rec("compose", lambda: kdn.kdn_compose(slices, offsets, cache, dst, w.rope_base))
 
     wall, ms = Timed(("store", "compose"), args.steps).run(step, args.warmup)
-    bytes_call = T * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)
+    bytes_call = T * (sh.paged_bytes_per_token + sh.stored_bytes_per_token(args.fmt))
     return {
         "tokens_per_step": T, "wall": wall, "ms": ms, "bytes": {n: bytes_call for n in ms},
         "place_calls": ("compose",),
-        "workload": "Llama-3-70B-shaped KV (L80 H8 D128 bs16): per step store 32768 tokens to int8 and "
+        "workload": "Llama-3-70B-shaped KV (L80 H8 D128 bs16): per step store 32768 tokens to %s and "
                     "compose them back as 4x8192-token slices with RoPE offsets 0/8192/16384/24576; "
-                    "%d buffer sets cycled" % n_sets,
+                    "%d buffer sets cycled" % (args.fmt, n_sets),
         "traffic": None,
     }
 
@@ -355,6 +356,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", choices=("8b", "70b_long", "batched_reuse", "host_stream_int8", "host_stream_raw"),
                     default="8b")
+    ap.add_argument("--fmt", choices=("int8", "int4", "raw"), default="int8",
+                    help="stored form used by the 8b and 70b_long workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=8)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -408,7 +411,10 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 KV, int8 codes + fp32 scales stored, fp32 arithmetic",
+        "dtype": "bf16 KV, %s stored form, fp32 arithmetic" % (
+            "int8 codes + fp32 row scales" if args.fmt == "int8" or args.workload == "batched_reuse"
+            or args.workload == "host_stream_int8" else
+            "int4 codes + fp32 group scales" if args.fmt == "int4" else "raw bf16"),
         "data": "synthetic N(0,1) bf16 KV, seeded; random disjoint block tables",
         "config": {
             "workload": res["workload"],

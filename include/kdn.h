@@ -48,6 +48,14 @@
  * inv = 127/amax (IEEE fp32 divisions) and code_j = clamp(rint(x_j*inv), -127, 127),
  * rint rounding halves to even; -128 is never produced.  Dequantisation is the
  * single fp32 product (float)code_j * scale, rounded to bf16 (nearest even).
+ *   KDN_FMT_INT4_GROUP32   uint8 [L][2][Tp][H][D/2] packed codes, followed at byte
+ *                          L*2*Tp*H*D/2 by fp32 [L][2][Tp][H][D/32] scales, one per
+ *                          group of 32 consecutive elements (head_dim % 32 == 0).
+ * int4 rule per group: amax over the group; amax < 2^-121 gives scale 0, codes 0;
+ * otherwise scale = amax/7, inv = 7/amax, code_j = clamp(rint(x_j*inv), -7, 7), two
+ * codes per byte as two's-complement nibbles, the even element in the low nibble;
+ * dequantisation (float)code_j * scale_group.  5 bits per element instead of 8.25: a
+ * tighter form toward the footprint reductions of Sec. 3.2, "KV-cache delivery".
  *
  * RoPE shift.  Keys carry rotary position embedding with half-split pairing:
  * element j pairs with j + D/2, j in [0, D/2), at frequency
@@ -75,12 +83,13 @@ typedef enum {
     KDN_ERANGE = -3,       /* token range outside the block table / chunk, bad block id (validator) */
     KDN_ESIZE = -4,        /* chunk buffer too small, too many chunks, grid limit exceeded */
     KDN_EDEVICE = -5,      /* a HIP call failed, or no usable device */
-    KDN_EUNSUPPORTED = -6  /* head_dim not a multiple of 16 or above 512 */
+    KDN_EUNSUPPORTED = -6  /* head_dim not a multiple of 16 (32 for int4) or above 512 */
 } kdn_status;
 
 typedef enum {
     KDN_FMT_RAW_BF16 = 0,
-    KDN_FMT_INT8_ROWSCALE = 1
+    KDN_FMT_INT8_ROWSCALE = 1,
+    KDN_FMT_INT4_GROUP32 = 2
 } kdn_format;
 
 /* The engine's paged KV memory.  k_base, v_base: [device] bf16, 16-byte aligned;
@@ -117,8 +126,8 @@ typedef struct {
     int32_t dest_token_start;
 } kdn_request;
 
-/* Bytes of a stored chunk of num_tokens tokens: L*2*T*H*D*2 (raw) or L*2*T*H*(D+4)
- * (int8).  Returns 0 on invalid arguments. */
+/* Bytes of a stored chunk of num_tokens tokens: L*2*T*H*D*2 (raw), L*2*T*H*(D+4)
+ * (int8) or L*2*T*H*(D/2 + D/8) (int4).  Returns 0 on invalid arguments. */
 uint64_t kdn_chunk_bytes(int32_t num_layers, int32_t num_kv_heads, int32_t head_dim,
                          int32_t num_tokens, int32_t fmt);
 

@@ -187,8 +187,10 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     const int64_t row_base = ((int64_t)ls * p.T + (tok_lo - p.t0)) * H;
     const int n_items = ((tok_hi - tok_lo) * H) << LOGP;
     const int64_t total_rows = (int64_t)p.c.L * 2 * p.T * H;
-    uint8_t *codes = p.out + row_base * D * (FMT == KDN_FMT_RAW_BF16 ? 2 : 1);
-    float *scales = reinterpret_cast<float *>(p.out + total_rows * D) + row_base;
+    constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT8_ROWSCALE ? 2 : 1; // words per 8 stored elements
+    const int spr = FMT == KDN_FMT_INT4_GROUP32 ? D >> 5 : 1;                              // scales per row
+    uint8_t *codes = p.out + ((row_base * D * W) >> 1);
+    float *scales = reinterpret_cast<float *>(p.out + ((total_rows * D * W) >> 1)) + row_base * spr;
 
     const int sub = threadIdx.x & (P - 1);
     const int lane = __lane_id();
@@ -220,6 +222,45 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
                 if (it < n_items && sub < R)
                     __builtin_nontemporal_store(
                         w[u], reinterpret_cast<u32x4 *>(codes + (uint32_t)(r * D + sub * 8) * 2));
+            }
+            continue;
+        }
+        if (FMT == KDN_FMT_INT4_GROUP32) {
+            // a group of 32 elements is a quad of lanes; lane (sub & 3) of the quad forms
+            // 7/amax and amax/7 of item (sub & 3): two division sequences serve the batch
+            uint32_t m4[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                m4[u] = group_max<4>(lane_absmax_bits(w[u]));
+            const int us = sub & 3;
+            const uint32_t msel = us == 0 ? m4[0] : us == 1 ? m4[1] : us == 2 ? m4[2] : m4[U - 1];
+            const float amax = __uint_as_float(msel << 16);
+            const bool keep = amax >= 0x1p-121f;
+            const float q_inv = keep ? 7.0f / amax : 0.0f;
+            const float q_scale = keep ? amax / 7.0f : 0.0f;
+            const int it_s = base + us * kThreads + threadIdx.x;
+            if (it_s < n_items && sub < R)
+                scales[(it_s >> LOGP) * spr + (sub >> 2)] = q_scale;
+            float inv4[U];
+            inv4[0] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(q_inv), 0x00, 0xf, 0xf, true));
+            inv4[1] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(q_inv), 0x55, 0xf, 0xf, true));
+            inv4[2] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(q_inv), 0xAA, 0xf, 0xf, true));
+            inv4[U - 1] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(q_inv), 0xFF, 0xf, 0xf, true));
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int it = base + u * kThreads + threadIdx.x;
+                const int r = it >> LOGP;
+                if (it < n_items && sub < R) {
+                    const float magic = 12582912.0f; // see quantise4: rint by adding 1.5 * 2^23
+                    uint32_t acc = 0;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t word = w[u][e >> 1];
+                        const float x = (e & 1) ? bf16_hi(word) : bf16_lo(word);
+                        acc |= (__float_as_uint(x * inv4[u] + magic) & 0xfu) << (4 * e);
+                    }
+                    __builtin_nontemporal_store(acc, reinterpret_cast<uint32_t *>(codes + (((uint32_t)(r * D + sub * 8)) >> 1)));
+                }
             }
             continue;
         }
@@ -281,7 +322,8 @@ template <int DT, int FMT, bool DENSE, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 {
     constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 2 : 4;
-    constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : 2; // 32-bit words per 8 stored elements
+    constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT8_ROWSCALE ? 2 : 1; // 32-bit words per 8 stored elements
+    constexpr int NS = FMT == KDN_FMT_INT4_GROUP32 ? 2 : 1;                                // scales per item
     const int D = DT ? DT : p.c.D;
     const int half = D >> 1;
     const int R = D >> 4;
@@ -307,8 +349,10 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
     const int64_t row_base = ((int64_t)ls * Tp + sg.tok0 + (tok_lo - S)) * H;
     const int64_t total_rows = (int64_t)p.c.L * 2 * Tp * H;
     const int n_items = ((tok_hi - tok_lo) * H) << LOGP;
-    const uint8_t *data = sg.data + row_base * D * (W / 2); // first stored row of this tile
-    const float *scales = reinterpret_cast<const float *>(sg.data + total_rows * D) + row_base;
+    const uint8_t *data = sg.data + ((row_base * D * W) >> 1); // first stored row of this tile
+    // int8: one scale per row after the codes; int4: D/32 scales per row after the codes
+    const int spr = FMT == KDN_FMT_INT4_GROUP32 ? D >> 5 : 1;
+    const float *scales = reinterpret_cast<const float *>(sg.data + ((total_rows * D * W) >> 1)) + row_base * spr;
     const bool rotate = (ls & 1) == 0 && sg.rope_row >= 0;
 
     const int sub = threadIdx.x & (P - 1);
@@ -330,14 +374,19 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 
     for (int it0 = threadIdx.x; it0 < n_items; it0 += kThreads * U) {
         uint32_t lo[U][W], hi[U][W];
-        float sc[U];
+        float sc[U][NS];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int it = it0 + u * kThreads;
             if (it < n_items) {
                 const int r = it >> LOGP;
-                const uint8_t *src = data + (uint32_t)(r * D + sub * 8) * (W / 2);
-                if (FMT == KDN_FMT_RAW_BF16) {
+                const uint8_t *src = data + (((uint32_t)(r * D + sub * 8) * W) >> 1);
+                if (FMT == KDN_FMT_INT4_GROUP32) {
+                    lo[u][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src));
+                    hi[u][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src + (half >> 1)));
+                    sc[u][0] = scales[r * spr + (sub >> 2)];
+                    sc[u][NS - 1] = scales[r * spr + ((half + sub * 8) >> 5)];
+                } else if (FMT == KDN_FMT_RAW_BF16) {
                     const u32x4 l4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
                     const u32x4 h4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + D));
 #pragma unroll
@@ -353,7 +402,7 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                         lo[u][w] = l2[w & 1];
                         hi[u][w] = h2[w & 1];
                     }
-                    sc[u] = scales[r];
+                    sc[u][0] = scales[r];
                 }
             }
         }
@@ -387,11 +436,17 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                         b[2 * e] = bf16_lo(hi[u][e % W]);
                         b[2 * e + 1] = bf16_hi(hi[u][e % W]);
                     }
+                } else if (FMT == KDN_FMT_INT4_GROUP32) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        a[e] = (float)((int32_t)(lo[u][0] << (28 - 4 * e)) >> 28) * sc[u][0];
+                        b[e] = (float)((int32_t)(hi[u][0] << (28 - 4 * e)) >> 28) * sc[u][NS - 1];
+                    }
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        a[e] = code_f32(lo[u][(e >> 2) % W], e & 3) * sc[u];
-                        b[e] = code_f32(hi[u][(e >> 2) % W], e & 3) * sc[u];
+                        a[e] = code_f32(lo[u][(e >> 2) % W], e & 3) * sc[u][0];
+                        b[e] = code_f32(hi[u][(e >> 2) % W], e & 3) * sc[u][0];
                     }
                 }
                 if (rotate) {
@@ -508,12 +563,19 @@ kdn_status check_cache(const kdn_cache_desc *c)
     return KDN_OK;
 }
 
+bool known_format(int32_t fmt)
+{
+    return fmt == KDN_FMT_RAW_BF16 || fmt == KDN_FMT_INT8_ROWSCALE || fmt == KDN_FMT_INT4_GROUP32;
+}
+
 kdn_status check_chunk(const kdn_chunk *ch, const kdn_cache_desc *c)
 {
     if (!ch || !ch->data)
         return KDN_EINVAL;
-    if (ch->fmt != KDN_FMT_RAW_BF16 && ch->fmt != KDN_FMT_INT8_ROWSCALE)
+    if (!known_format(ch->fmt))
         return KDN_EINVAL;
+    if (ch->fmt == KDN_FMT_INT4_GROUP32 && ch->head_dim % 32 != 0)
+        return KDN_EUNSUPPORTED;
     if (ch->num_layers != c->num_layers || ch->num_kv_heads != c->num_kv_heads
         || ch->head_dim != c->head_dim)
         return KDN_EINVAL;
@@ -740,8 +802,10 @@ kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const s
     }
     if (fmt == KDN_FMT_RAW_BF16)
         launch_place_d<KDN_FMT_RAW_BF16>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
-    else
+    else if (fmt == KDN_FMT_INT8_ROWSCALE)
         launch_place_d<KDN_FMT_INT8_ROWSCALE>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
+    else
+        launch_place_d<KDN_FMT_INT4_GROUP32>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
     kdn_status rc = hip_status(hipGetLastError());
     if (slot >= 0) {
         if (hipEventRecord(ds->seg_done[slot], st) != hipSuccess)
@@ -787,7 +851,7 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
     st = rope_rows(ds, rope_base, cache->head_dim, offs.data(), (int32_t)offs.size(), rows.data(), &p.rope);
     if (st != KDN_OK)
         return st;
-    std::vector<Seg> segs[2];
+    std::vector<Seg> segs[3];
     size_t k = 0;
     for (int32_t r = 0; r < n_reqs; ++r) {
         const kdn_request &q = reqs[r];
@@ -807,7 +871,7 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
             S += ch.num_tokens;
         }
     }
-    for (int f = 0; f < 2; ++f) {
+    for (int f = 0; f < 3; ++f) {
         // Segments that read the same stored rows run back to back, so that a popular
         // chunk is fetched from HBM once and from the last-level cache afterwards.
         if (n_reqs > 1)
@@ -864,6 +928,8 @@ uint64_t kdn_chunk_bytes(int32_t L, int32_t H, int32_t D, int32_t T, int32_t fmt
         return rows * (uint64_t)D * 2;
     if (fmt == KDN_FMT_INT8_ROWSCALE)
         return rows * ((uint64_t)D + 4);
+    if (fmt == KDN_FMT_INT4_GROUP32 && D % 32 == 0)
+        return rows * ((uint64_t)D / 2 + (uint64_t)D / 32 * 4);
     return 0;
 }
 
@@ -872,11 +938,13 @@ kdn_status kdn_chunk_init(kdn_chunk *out, void *data_dev, uint64_t bytes, int32_
 {
     if (!out || !data_dev || T <= 0)
         return KDN_EINVAL;
-    if (fmt != KDN_FMT_RAW_BF16 && fmt != KDN_FMT_INT8_ROWSCALE)
+    if (!known_format(fmt))
         return KDN_EINVAL;
     kdn_status st = check_shape(L, H, D);
     if (st != KDN_OK)
         return st;
+    if (fmt == KDN_FMT_INT4_GROUP32 && D % 32 != 0)
+        return KDN_EUNSUPPORTED;
     if (!aligned16(data_dev))
         return KDN_EALIGN;
     if (bytes < kdn_chunk_bytes(L, H, D, T, fmt))
@@ -916,8 +984,10 @@ kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_tab
         return st;
     if (!block_table_dev || !out || !out->data || table_len <= 0 || num_tokens <= 0 || token_start < 0)
         return KDN_EINVAL;
-    if (out->fmt != KDN_FMT_RAW_BF16 && out->fmt != KDN_FMT_INT8_ROWSCALE)
+    if (!known_format(out->fmt))
         return KDN_EINVAL;
+    if (out->fmt == KDN_FMT_INT4_GROUP32 && cache->head_dim % 32 != 0)
+        return KDN_EUNSUPPORTED;
     if (!aligned16(out->data))
         return KDN_EALIGN;
     if ((int64_t)token_start + num_tokens > (int64_t)table_len * cache->block_size)
@@ -939,8 +1009,10 @@ kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_tab
     hipStream_t hs = static_cast<hipStream_t>(stream);
     if (out->fmt == KDN_FMT_RAW_BF16)
         launch_store_d<KDN_FMT_RAW_BF16>(p, grid, hs);
-    else
+    else if (out->fmt == KDN_FMT_INT8_ROWSCALE)
         launch_store_d<KDN_FMT_INT8_ROWSCALE>(p, grid, hs);
+    else
+        launch_store_d<KDN_FMT_INT4_GROUP32>(p, grid, hs);
     st = hip_status(hipGetLastError());
     if (st != KDN_OK)
         return st;
@@ -1099,7 +1171,7 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
             const uint64_t bytes = kdn_chunk_bytes(Lg, H, D, Tu, hp.fmt);
             at += (bytes + 255) & ~(uint64_t)255;
         }
-        std::vector<Seg> segs[2];
+        std::vector<Seg> segs[3];
         int32_t S = dest_token_start;
         for (int32_t i = 0; i < n_chunks; ++i) {
             const kdn_chunk &ch = chunks[i];
@@ -1121,7 +1193,7 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
             return KDN_EDEVICE;
         p.c.L = Lg;
         p.layer0 = l0;
-        for (int f = 0; f < 2; ++f) {
+        for (int f = 0; f < 3; ++f) {
             st = place_segments(ds, p, f, segs[f], user);
             if (st != KDN_OK)
                 return st;

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG, "libkdn.so")
 
 FMT_RAW_BF16 = 0
 FMT_INT8_ROWSCALE = 1
+FMT_INT4_GROUP32 = 2
 
 OK, EINVAL, EALIGN, ERANGE, ESIZE, EDEVICE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 
@@ -179,6 +180,17 @@ class Chunk:
         assert d.fmt == FMT_INT8_ROWSCALE
         return self.data[n:n + n // d.head_dim * 4].view(torch.float32).view(
             d.num_layers, 2, d.parent_tokens, d.num_kv_heads)
+
+    def packed4(self) -> torch.Tensor:
+        d, n = self._split()
+        assert d.fmt == FMT_INT4_GROUP32
+        return self.data[:n // 2].view(d.num_layers, 2, d.parent_tokens, d.num_kv_heads, d.head_dim // 2)
+
+    def scales4(self) -> torch.Tensor:
+        d, n = self._split()
+        assert d.fmt == FMT_INT4_GROUP32
+        return self.data[n // 2:n // 2 + n // 32 * 4].view(torch.float32).view(
+            d.num_layers, 2, d.parent_tokens, d.num_kv_heads, d.head_dim // 32)
 
     def raw(self) -> torch.Tensor:
         d, n = self._split()

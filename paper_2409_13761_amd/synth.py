@@ -84,6 +84,14 @@ class KVShape:
     def int8_bytes_per_token(self) -> int:       # B_q
         return self.L * 2 * self.H * (self.D + 4)
 
+    @property
+    def int4_bytes_per_token(self) -> int:
+        return self.L * 2 * self.H * (self.D // 2 + self.D // 32 * 4)
+
+    def stored_bytes_per_token(self, fmt_name: str) -> int:
+        return {"raw": self.paged_bytes_per_token, "int8": self.int8_bytes_per_token,
+                "int4": self.int4_bytes_per_token}[fmt_name]
+
 
 @dataclass(frozen=True)
 class Workload:

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import (INT8, RAW, assert_cache_equal, assert_chunk_equal, bits_of, chunk_to_dev,
+from helpers import (INT4, INT8, RAW, assert_cache_equal, assert_chunk_equal, bits_of, chunk_to_dev,
                      dev_cache, dev_table, host_cache, to_dev_bf16)
 from oracle import kdn_oracle as O
 from paper_2409_13761_amd import kdn, synth
@@ -21,7 +21,7 @@ def _say(msg):
 
 
 # ------------------------------------------------------------------ store
-@pytest.mark.parametrize("fmt", [RAW, INT8])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
 @pytest.mark.parametrize("shape", [
     # L, nb, bs, H, D, t0, T
     (2, 24, 16, 4, 64, 0, 128),        # block aligned, several tiles
@@ -37,6 +37,8 @@ def _say(msg):
 ])
 def test_store_matches_oracle(fmt, shape):
     L, nb, bs, H, D, t0, T = shape
+    if fmt == INT4 and D % 32:
+        pytest.skip("int4 groups need head_dim % 32 == 0")
     _say("store fmt=%d shape=%s" % (fmt, shape))
     hc = host_cache(100 + D + bs, L, nb, bs, H, D)
     n_tab = (t0 + T + bs - 1) // bs
@@ -115,7 +117,7 @@ def test_store_strided_cache():
 
 
 # ------------------------------------------------------------------ load / compose
-@pytest.mark.parametrize("fmt", [RAW, INT8])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
 @pytest.mark.parametrize("shape", [
     # L, nb, bs, H, D, dest, T
     (2, 24, 16, 4, 64, 0, 128),
@@ -131,6 +133,8 @@ def test_store_strided_cache():
 ])
 def test_load_matches_oracle_and_touches_nothing_else(fmt, shape):
     L, nb, bs, H, D, dest, T = shape
+    if fmt == INT4 and D % 32:
+        pytest.skip("int4 groups need head_dim % 32 == 0")
     _say("load fmt=%d shape=%s" % (fmt, shape))
     src = host_cache(200 + D, L, nb, bs, H, D)
     n_src = (T + bs - 1) // bs
@@ -148,10 +152,13 @@ def test_load_matches_oracle_and_touches_nothing_else(fmt, shape):
     assert_cache_equal(dd, hd)
 
 
-@pytest.mark.parametrize("fmt", [RAW, INT8])
-@pytest.mark.parametrize("D,base", [(64, 10000.0), (128, 500000.0), (96, 10000.0), (16, 10000.0), (256, 1e6)])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("D,base", [(64, 10000.0), (128, 500000.0), (96, 10000.0), (16, 10000.0), (256, 1e6),
+                                    (32, 10000.0), (512, 10000.0)])
 def test_compose_ragged_chunks_with_offsets(fmt, D, base):
     L, nb, bs, H = 2, 64, 16, 2
+    if fmt == INT4 and D % 32:
+        pytest.skip("int4 groups need head_dim % 32 == 0")
     _say("compose fmt=%d D=%d" % (fmt, D))
     src = host_cache(400 + D, L, nb, bs, H, D)
     t1, t2, t3, t4, dst_bt = synth.disjoint_block_tables(11, nb, [4, 3, 5, 2, 16])
@@ -172,14 +179,48 @@ def test_compose_mixed_formats_and_slices():
     a, b, dst_bt = synth.disjoint_block_tables(21, nb, [10, 6, 14])
     whole = O.store(src, a, 0, 160, INT8)
     rawc = O.store(src, b, 3, 90, RAW)
-    chunks = [whole.slice(100, 50), rawc.slice(10, 33), whole.slice(0, 64), rawc.slice(0, 10)]
-    offsets = [7, 0, 50, -90]
+    four = O.store(src, a, 16, 70, INT4)
+    chunks = [whole.slice(100, 50), rawc.slice(10, 33), whole.slice(0, 64), rawc.slice(0, 10), four.slice(5, 60)]
+    offsets = [7, 0, 50, -90, 33]
     hd = host_cache(22, L, nb, bs, H, D)
     dd = dev_cache(hd)
     O.compose(chunks, offsets, hd, dst_bt, 10000.0, dest=1)
-    dw, dr = chunk_to_dev(whole), chunk_to_dev(rawc)
-    dchunks = [dw.slice(100, 50), dr.slice(10, 33), dw.slice(0, 64), dr.slice(0, 10)]
+    dw, dr, d4 = chunk_to_dev(whole), chunk_to_dev(rawc), chunk_to_dev(four)
+    dchunks = [dw.slice(100, 50), dr.slice(10, 33), dw.slice(0, 64), dr.slice(0, 10), d4.slice(5, 60)]
     kdn.kdn_compose(dchunks, offsets, dd, dev_table(dst_bt), 10000.0, dest_token_start=1)
+    assert_cache_equal(dd, hd)
+
+
+def test_int4_special_groups():
+    """Zero groups, groups under the 2^-121 threshold, ties, and every positive finite
+    bf16 as a group's amax."""
+    L, nb, bs, H, D = 1, 2100, 16, 1, 32
+    k = np.zeros((L, nb, bs, H, D), dtype=np.uint16)
+    rows = k.reshape(-1, D)
+    amax_bits = np.arange(1, 0x7F80, dtype=np.uint16)
+    n = amax_bits.size
+    rows[:n, 0] = amax_bits
+    f = (amax_bits.astype(np.uint32) << 16).view(np.float32)
+    for j, ratio in enumerate((0.5, -0.25, 0.75, -0.999, 0.0714, 0.2143, -0.3571, 0.6429, -0.9286), start=1):
+        rows[:n, j] = bits_of(torch.from_numpy((f * np.float32(ratio)).astype(np.float32)).to(torch.bfloat16))
+    rows[n, 3] = 0x8000
+    rows[n + 1, :] = 0x02FF
+    rows[n + 2, :4] = [0x0300, 0x8300, 0x0280, 0x0001]
+    ties = torch.zeros(32)
+    ties[:11] = torch.tensor([7.0, 3.5, -3.5, 0.5, -0.5, 1.5, 2.5, -2.5, 6.5, -6.5, 4.5])
+    rows[n + 3] = bits_of(ties.to(torch.bfloat16))
+    hc = O.PagedCache(k, synth.normal_bf16(6, k.shape))
+    T = nb * bs
+    bt = np.arange(nb, dtype=np.int32)
+    want = O.store(hc, bt, 0, T, INT4)
+    dc = dev_cache(hc)
+    out = kdn.alloc_chunk(dc, T, INT4)
+    kdn.kdn_store_chunk(dc, dev_table(bt), 0, T, out)
+    assert_chunk_equal(out, want)
+    hd = O.PagedCache(np.zeros_like(hc.k), np.zeros_like(hc.v))
+    O.load(want, hd, bt, 0)
+    dd = dev_cache(O.PagedCache(np.zeros_like(hc.k), np.zeros_like(hc.v)))
+    kdn.kdn_load_chunk(out, dd, dev_table(bt), 0)
     assert_cache_equal(dd, hd)
 
 

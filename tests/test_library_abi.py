@@ -39,6 +39,8 @@ def test_chunk_bytes(lib):
     assert kdn.kdn_chunk_bytes(2, 4, 64, 256, 1) == 256 * 1088
     assert kdn.kdn_chunk_bytes(2, 4, 64, 0, 1) == 0
     assert kdn.kdn_chunk_bytes(2, 4, 64, 4, 7) == 0
+    assert kdn.kdn_chunk_bytes(32, 8, 128, 1, 2) == 40960        # int4: 5 bits per element
+    assert kdn.kdn_chunk_bytes(2, 4, 48, 4, 2) == 0              # int4 needs head_dim % 32 == 0
     # 32768 tokens of the 80-layer shape need more than 32 bits
     assert kdn.kdn_chunk_bytes(80, 8, 128, 32768, 1) == 32768 * 168960
 
@@ -75,6 +77,7 @@ def test_argument_errors_are_reported_on_the_host(lib):
     assert f(C.byref(good), bt, 4, 0, 16, C.byref(_chunk(nbytes=100)), None) == kdn.ESIZE
     assert f(C.byref(good), bt, 4, 0, 16, C.byref(_chunk(fmt=5, nbytes=1 << 20)), None) == kdn.EINVAL
     assert f(C.byref(good), bt, 4, 0, 16, C.byref(_chunk(data=0x4004)), None) == kdn.EALIGN
+    assert f(C.byref(_cache(D=48)), bt, 4, 0, 16, C.byref(_chunk(fmt=2, D=48, nbytes=1 << 20)), None) == kdn.EUNSUPPORTED
 
     g = lib.kdn_load_chunk
     assert g(None, C.byref(good), bt, 4, 0, None) == kdn.EINVAL

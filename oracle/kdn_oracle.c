@@ -209,6 +209,42 @@ void kdno_rope_table(double base, int32_t D, int32_t d, float *cs)
     }
 }
 
+/* ---- RoPE variants ------------------------------------------------------------
+ * READING (what real models need before a chunk can be reused "at different
+ * positions", Sec. 3.2 blending): only the first rot_dim elements of a row may be
+ * rotary (partial rotary; rot_dim == D is the plain case), pairs may be half-split
+ * (j, j + rot_dim/2) or interleaved (2j, 2j + 1), and the rot_dim/2 frequencies may
+ * be given explicitly (for rescaled-frequency models) instead of base^(-2j/rot_dim).
+ * Elements at and beyond rot_dim are never changed. */
+enum { KDNO_PAIR_HALF_SPLIT = 0, KDNO_PAIR_INTERLEAVED = 1 };
+
+void kdno_rope_table_spec(double base, const double *inv_freq, int32_t rot_dim, int32_t d, float *cs)
+{
+    for (int32_t j = 0; j < rot_dim / 2; ++j) {
+        double theta = inv_freq ? inv_freq[j] : pow(base, -(double)(2 * j) / (double)rot_dim);
+        double phi = (double)d * theta;
+        cs[2 * j] = (float)cos(phi);
+        cs[2 * j + 1] = (float)sin(phi);
+    }
+}
+
+/* Same two-operation form as kdno_rotate_row, on the pairs the variant names:
+ * first' = fma(-second, s, first*c), second' = fma(first, s, second*c). */
+void kdno_rotate_row_spec(float *y, int32_t rot_dim, int32_t pairing, const float *cs)
+{
+    int32_t half = rot_dim / 2;
+    for (int32_t j = 0; j < half; ++j) {
+        int32_t ia = pairing == KDNO_PAIR_INTERLEAVED ? 2 * j : j;
+        int32_t ib = pairing == KDNO_PAIR_INTERLEAVED ? 2 * j + 1 : j + half;
+        float c = cs[2 * j], s = cs[2 * j + 1];
+        float a = y[ia], b = y[ib];
+        float ac = a * c;
+        float bc = b * c;
+        y[ia] = fmaf(-b, s, ac);
+        y[ib] = fmaf(a, s, bc);
+    }
+}
+
 /* Rotate one row held in fp32, in place:
  *   lo' = fma(-hi, s, lo*c)     hi' = fma(lo, s, hi*c)
  * (one rounded product, then one fused multiply-add, per output). */
@@ -272,8 +308,8 @@ int kdno_store(const kdno_cache *c, const int32_t *bt, int32_t table_len,
  * cos 0), so a zero-offset compose is bit-identical to a load; V rows are
  * never rotated; raw-format rows with d == 0 are bit copies. */
 static int place(const void *data, int32_t fmt, int32_t Tp, int32_t tok_start,
-                 int32_t T, int32_t d, const float *cs, const kdno_cache *c,
-                 const int32_t *bt, int32_t dest, int32_t l0, int32_t l1)
+                 int32_t T, int32_t d, const float *cs, int32_t rot_dim, int32_t pairing,
+                 const kdno_cache *c, const int32_t *bt, int32_t dest, int32_t l0, int32_t l1)
 {
     const int32_t H = c->H, D = c->D;
     int64_t n_rows = (int64_t)c->L * 2 * Tp * H;
@@ -309,8 +345,10 @@ static int place(const void *data, int32_t fmt, int32_t Tp, int32_t tok_start,
                     } else {
                         kdno_dequantise_row(codes + r * D, scales[r], D, y);
                     }
-                    if (rotate)
+                    if (rotate && rot_dim == D && pairing == KDNO_PAIR_HALF_SPLIT)
                         kdno_rotate_row(y, D, cs);
+                    else if (rotate)
+                        kdno_rotate_row_spec(y, rot_dim, pairing, cs);
                     for (int32_t j = 0; j < D; ++j)
                         dst[j] = kdno_f32_to_bf16(y[j]);
                 }
@@ -327,7 +365,7 @@ int kdno_load(const void *data, int32_t fmt, int32_t Tp, int32_t tok_start,
     if (tok_start < 0 || T < 0 || tok_start + (int64_t)T > Tp || dest < 0
         || (int64_t)dest + T > (int64_t)table_len * c->bs)
         return -1;
-    return place(data, fmt, Tp, tok_start, T, 0, 0, c, bt, dest, l0, l1);
+    return place(data, fmt, Tp, tok_start, T, 0, 0, c->D, KDNO_PAIR_HALF_SPLIT, c, bt, dest, l0, l1);
 }
 
 /* ---- compose (the blending module, Sec. 3.1) -------------------------------------
@@ -356,10 +394,69 @@ int kdno_compose(int32_t n, const void *const *data, const int32_t *fmt,
         if (offsets[i] != 0)
             kdno_rope_table(rope_base, c->D, offsets[i], cs);
         int rc = place(data[i], fmt[i], Tp[i], tok_start[i], T[i], offsets[i],
-                       cs, c, bt, S, l0, l1);
+                       cs, c->D, KDNO_PAIR_HALF_SPLIT, c, bt, S, l0, l1);
         if (rc)
             return rc;
         S += T[i];
     }
+    return 0;
+}
+
+/* Compose with a RoPE variant: rot_dim (even, <= D; 0 means D), pairing, and either
+ * rope_base or rot_dim/2 explicit frequencies. */
+int kdno_compose_spec(int32_t n, const void *const *data, const int32_t *fmt,
+                      const int32_t *Tp, const int32_t *tok_start, const int32_t *T,
+                      const int32_t *offsets, const kdno_cache *c, const int32_t *bt,
+                      int32_t table_len, int32_t dest, double rope_base,
+                      const double *inv_freq, int32_t rot_dim, int32_t pairing,
+                      int32_t l0, int32_t l1)
+{
+    if (rot_dim == 0)
+        rot_dim = c->D;
+    if (rot_dim < 0 || rot_dim > c->D || rot_dim % 2 != 0 || c->D > 4096)
+        return -1;
+    int64_t total = 0;
+    for (int32_t i = 0; i < n; ++i) {
+        if (tok_start[i] < 0 || T[i] < 0 || tok_start[i] + (int64_t)T[i] > Tp[i])
+            return -1;
+        total += T[i];
+    }
+    if (dest < 0 || (int64_t)dest + total > (int64_t)table_len * c->bs)
+        return -1;
+    float cs[4096];
+    int32_t S = dest;
+    for (int32_t i = 0; i < n; ++i) {
+        if (offsets[i] != 0)
+            kdno_rope_table_spec(rope_base, inv_freq, rot_dim, offsets[i], cs);
+        int rc = place(data[i], fmt[i], Tp[i], tok_start[i], T[i], offsets[i],
+                       cs, rot_dim, pairing, c, bt, S, l0, l1);
+        if (rc)
+            return rc;
+        S += T[i];
+    }
+    return 0;
+}
+
+/* ---- patch (the write-back half of selective recompute, Sec. 3.2 blending) -------
+ * READING: after a compose, an engine may recompute the K/V of a few tokens and must
+ * put them over the composed ones.  rows holds bf16 [L][2][n][H][D]; row i replaces
+ * request token tokens[i] (bit copy).  Token indices must be distinct. */
+int kdno_patch_rows(const uint16_t *rows, const int32_t *tokens, int32_t n,
+                    const kdno_cache *c, const int32_t *bt, int32_t table_len)
+{
+    for (int32_t i = 0; i < n; ++i)
+        if (tokens[i] < 0 || tokens[i] >= (int64_t)table_len * c->bs)
+            return -1;
+    for (int32_t l = 0; l < c->L; ++l)
+        for (int32_t side = 0; side < 2; ++side)
+            for (int32_t i = 0; i < n; ++i) {
+                int32_t block = bt[tokens[i] / c->bs], slot = tokens[i] % c->bs;
+                if (block < 0 || block >= c->nb)
+                    return -1;
+                for (int32_t h = 0; h < c->H; ++h)
+                    memcpy(cache_row(c, l, side, block, slot, h),
+                           rows + ((((int64_t)l * 2 + side) * n + i) * c->H + h) * c->D,
+                           (size_t)c->D * 2);
+            }
     return 0;
 }

@@ -21,6 +21,8 @@ FMT_RAW_BF16 = 0
 FMT_INT8_ROWSCALE = 1
 FMT_INT4_GROUP32 = 2
 GROUP = 32
+PAIR_HALF_SPLIT = 0
+PAIR_INTERLEAVED = 1
 
 
 def build(force: bool = False) -> str:
@@ -84,6 +86,19 @@ def lib():
                                        C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.POINTER(_Cache), C.c_void_p, C.c_int32, C.c_int32,
                                        C.c_double, C.c_int32, C.c_int32]
+            L.kdno_rope_table_spec.restype = None
+            L.kdno_rope_table_spec.argtypes = [C.c_double, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+            L.kdno_rotate_row_spec.restype = None
+            L.kdno_rotate_row_spec.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+            L.kdno_compose_spec.restype = C.c_int
+            L.kdno_compose_spec.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.POINTER(_Cache), C.c_void_p, C.c_int32, C.c_int32,
+                                            C.c_double, C.c_void_p, C.c_int32, C.c_int32,
+                                            C.c_int32, C.c_int32]
+            L.kdno_patch_rows.restype = C.c_int
+            L.kdno_patch_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(_Cache),
+                                          C.c_void_p, C.c_int32]
             _lib = L
     return _lib
 
@@ -264,3 +279,52 @@ def compose(chunks, offsets, cache: PagedCache, block_table, rope_base: float,
                             float(rope_base), l0, l1)
     if rc:
         raise ValueError("kdno_compose: bad range or block id")
+
+
+def rope_table_spec(base: float, inv_freq, rot_dim: int, d: int) -> np.ndarray:
+    cs = np.empty((rot_dim // 2, 2), dtype=np.float32)
+    f = None if inv_freq is None else np.ascontiguousarray(inv_freq, dtype=np.float64)
+    lib().kdno_rope_table_spec(float(base), None if f is None else _ptr(f), rot_dim, int(d), _ptr(cs))
+    return cs
+
+
+def rotate_row_spec(y: np.ndarray, rot_dim: int, pairing: int, cs: np.ndarray) -> np.ndarray:
+    y = np.array(y, dtype=np.float32, copy=True)
+    cs = np.ascontiguousarray(cs, dtype=np.float32)
+    lib().kdno_rotate_row_spec(_ptr(y), rot_dim, pairing, _ptr(cs))
+    return y
+
+
+def compose_spec(chunks, offsets, cache: PagedCache, block_table, rope_base: float = 10000.0,
+                 inv_freq=None, rot_dim: int = 0, pairing: int = PAIR_HALF_SPLIT, dest: int = 0,
+                 layers: tuple[int, int] | None = None) -> None:
+    bt = _bt(block_table)
+    n = len(chunks)
+    assert len(offsets) == n
+    data = (C.c_void_p * max(n, 1))(*[_ptr(c.data) for c in chunks])
+    fmt = np.array([c.fmt for c in chunks], dtype=np.int32)
+    Tp = np.array([c.Tp for c in chunks], dtype=np.int32)
+    ts = np.array([c.tok_start for c in chunks], dtype=np.int32)
+    T = np.array([c.T for c in chunks], dtype=np.int32)
+    off = np.ascontiguousarray(offsets, dtype=np.int32)
+    f = None if inv_freq is None else np.ascontiguousarray(inv_freq, dtype=np.float64)
+    l0, l1 = layers if layers is not None else (0, cache.L)
+    d = cache.desc()
+    rc = lib().kdno_compose_spec(n, C.cast(data, C.c_void_p), _ptr(fmt), _ptr(Tp), _ptr(ts),
+                                 _ptr(T), _ptr(off), C.byref(d), _ptr(bt), bt.size, dest,
+                                 float(rope_base), None if f is None else _ptr(f), rot_dim, pairing,
+                                 l0, l1)
+    if rc:
+        raise ValueError("kdno_compose_spec: bad range, block id or rope variant")
+
+
+def patch_rows(rows: np.ndarray, tokens, cache: PagedCache, block_table) -> None:
+    """rows: uint16 [L][2][n][H][D]; tokens: n distinct request token indices."""
+    bt = _bt(block_table)
+    tok = np.ascontiguousarray(tokens, dtype=np.int32)
+    rows = np.ascontiguousarray(rows, dtype=np.uint16)
+    assert rows.shape == (cache.L, 2, tok.size, cache.H, cache.D)
+    d = cache.desc()
+    rc = lib().kdno_patch_rows(_ptr(rows), _ptr(tok), tok.size, C.byref(d), _ptr(bt), bt.size)
+    if rc:
+        raise ValueError("kdno_patch_rows: token or block id out of range")

@@ -560,3 +560,107 @@ def test_bad_ranges_are_refused(oracle):
         oracle.load(ch, src, bt, 1)
     with pytest.raises(ValueError):
         oracle.load(ch, src, np.array([0, 1, 2, 99], dtype=np.int32), 0)   # block id out of range
+
+
+# ------------------------------------------------------------- RoPE variants, patching
+def test_interleaved_pairs_are_complex_multiplications(oracle):
+    """Pair (2j, 2j+1) as a complex number times exp(i d theta_j)."""
+    rng = np.random.default_rng(21)
+    for base, D, d in ((10000.0, 64, 100), (500000.0, 128, -3000)):
+        x = rng.standard_normal(D).astype(np.float32)
+        cs = oracle.rope_table_spec(base, None, D, d)
+        y = oracle.rotate_row_spec(x, D, oracle.PAIR_INTERLEAVED, cs).astype(np.float64)
+        theta = base ** (-2.0 * np.arange(D // 2) / D)
+        z = (x[0::2].astype(np.float64) + 1j * x[1::2]) * np.exp(1j * d * theta)
+        assert np.allclose(y[0::2], z.real, atol=2e-6) and np.allclose(y[1::2], z.imag, atol=2e-6)
+        # and shifting K(p) by d gives K(p+d) in this pairing too
+        k_raw = rng.standard_normal(D)
+        zr = k_raw[0::2] + 1j * k_raw[1::2]
+        kp, kpd = zr * np.exp(1j * 17 * theta), zr * np.exp(1j * (17 + d) * theta)
+        xin = np.empty(D, dtype=np.float32)
+        xin[0::2], xin[1::2] = kp.real, kp.imag
+        got = oracle.rotate_row_spec(xin, D, oracle.PAIR_INTERLEAVED, cs).astype(np.float64)
+        assert np.allclose(got[0::2], kpd.real, atol=1e-5) and np.allclose(got[1::2], kpd.imag, atol=1e-5)
+
+
+def test_partial_rotary_rotates_the_leading_dims_only(oracle):
+    rng = np.random.default_rng(22)
+    D, rot, base, d = 128, 64, 10000.0, 77
+    x = rng.standard_normal(D).astype(np.float32)
+    cs = oracle.rope_table_spec(base, None, rot, d)
+    for pairing in (oracle.PAIR_HALF_SPLIT, oracle.PAIR_INTERLEAVED):
+        y = oracle.rotate_row_spec(x, rot, pairing, cs)
+        assert np.array_equal(y[rot:], x[rot:])
+        # the rotated part is what a full rotation of a rot-wide row gives (theta from rot, not D)
+        small = oracle.rotate_row_spec(x[:rot].copy(), rot, pairing, cs)
+        assert np.array_equal(y[:rot], small)
+        assert not np.array_equal(y[:rot], x[:rot])
+    theta = base ** (-2.0 * np.arange(rot // 2) / rot)
+    assert np.allclose(cs[:, 0], np.cos(d * theta), atol=6.1e-8)
+    # half-split with rot_dim == D is the plain rotation, bit for bit
+    full = oracle.rope_table(base, D, d)
+    assert np.array_equal(oracle.rope_table_spec(base, None, D, d), full)
+    assert np.array_equal(oracle.rotate_row_spec(x, D, oracle.PAIR_HALF_SPLIT, full), oracle.rotate_row(x, full))
+
+
+def test_explicit_frequencies(oracle):
+    D, d = 64, 123
+    base = 10000.0
+    freq = np.array([base ** (-(2.0 * j) / D) for j in range(D // 2)])
+    assert np.array_equal(oracle.rope_table_spec(base, freq, D, d), oracle.rope_table(base, D, d))
+    scaled = freq / np.where(np.arange(D // 2) >= 16, 8.0, 1.0)        # low frequencies slowed down
+    cs = oracle.rope_table_spec(base, scaled, D, d).astype(np.float64)
+    assert np.allclose(cs[:, 0], np.cos(d * scaled), atol=6.1e-8)
+    assert np.allclose(cs[:, 1], np.sin(d * scaled), atol=6.1e-8)
+
+
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+def test_compose_spec_matches_row_wise_rotation(oracle, fmt):
+    """compose with a variant = dequantise, rotate each K row with rotate_row_spec, round, place."""
+    src, chunks, dst_bt = _setup_compose(oracle, fmt, seed=47)
+    D, bs = src.D, src.bs
+    freq = 10000.0 ** (-2.0 * np.arange(16) / 32) / 3.0
+    for pairing, rot, inv_freq in ((oracle.PAIR_INTERLEAVED, 0, None), (oracle.PAIR_HALF_SPLIT, 32, freq),
+                                   (oracle.PAIR_INTERLEAVED, 32, None)):
+        dst = make_cache(oracle, 81, src.L, src.nb, src.bs, src.H, src.D)
+        before = dst.copy()
+        d = 45
+        oracle.compose_spec([chunks[0]], [d], dst, dst_bt, 10000.0, inv_freq=inv_freq, rot_dim=rot,
+                            pairing=pairing, dest=2)
+        c = chunks[0]
+        if fmt == RAW:
+            y = bf16_bits_to_f32(c.raw())
+        elif fmt == INT8:
+            y = c.codes().astype(np.float32) * c.scales()[..., None]
+        else:
+            y = unpack_nibbles(c.packed4()).astype(np.float32) * np.repeat(c.scales4(), 32, axis=-1)
+        cs = oracle.rope_table_spec(10000.0, inv_freq, rot or D, d)
+        for t in range(c.T):
+            blk, slot = int(dst_bt[(2 + t) // bs]), (2 + t) % bs
+            for l in range(src.L):
+                for h in range(src.H):
+                    want_k = oracle.f32_to_bf16(oracle.rotate_row_spec(y[l, 0, t, h], rot or D, pairing, cs))
+                    assert np.array_equal(dst.k[l, blk, slot, h], want_k)
+                    assert np.array_equal(dst.v[l, blk, slot, h], oracle.f32_to_bf16(y[l, 1, t, h]))
+        outside = np.setdiff1d(np.arange(src.nb), dst_bt)
+        assert np.array_equal(dst.k[:, outside], before.k[:, outside])
+
+
+def test_patch_rows_overwrites_exactly_the_named_tokens(oracle):
+    L, nb, bs, H, D = 2, 16, 4, 2, 8
+    cache = make_cache(oracle, 48, L, nb, bs, H, D)
+    before = cache.copy()
+    bt = synth.disjoint_block_tables(48, nb, [6])[0]
+    tokens = np.array([3, 0, 17, 22, 9], dtype=np.int32)
+    rows = synth.normal_bf16(49, (L, 2, len(tokens), H, D))
+    oracle.patch_rows(rows, tokens, cache, bt)
+    touched = np.zeros((nb, bs), dtype=bool)
+    for i, t in enumerate(tokens):
+        blk, slot = int(bt[t // bs]), t % bs
+        touched[blk, slot] = True
+        assert np.array_equal(cache.k[:, blk, slot], rows[:, 0, i])
+        assert np.array_equal(cache.v[:, blk, slot], rows[:, 1, i])
+    assert np.array_equal(cache.k[:, ~touched], before.k[:, ~touched])
+    assert np.array_equal(cache.v[:, ~touched], before.v[:, ~touched])
+    with pytest.raises(ValueError):
+        oracle.patch_rows(rows, np.array([3, 0, 17, 24, 9]), cache, bt)     # token 24 is past the table

@@ -114,6 +114,26 @@ typedef struct {
     int32_t num_tokens;
 } kdn_chunk;
 
+/* RoPE variants for composes (what real models need before a chunk can be reused at
+ * another position, Sec. 3.2 "KV-cache blending"). */
+typedef enum {
+    KDN_ROPE_HALF_SPLIT = 0,  /* element j pairs with j + rot_dim/2 */
+    KDN_ROPE_INTERLEAVED = 1  /* element 2j pairs with 2j + 1 */
+} kdn_rope_pairing;
+
+/* base: frequencies theta_j = base^(-2j/rot_dim), used when inv_freq is NULL.
+ * inv_freq: [host] rot_dim/2 explicit frequencies in double (for models whose
+ * frequencies are rescaled), or NULL.  rot_dim: only the first rot_dim elements of a
+ * row are rotary, the rest pass through unrotated; a multiple of 16, at most head_dim;
+ * 0 means head_dim.  pairing: kdn_rope_pairing.  The rotation is the one defined above,
+ * applied to the pairs the variant names. */
+typedef struct {
+    double base;
+    const double *inv_freq;
+    int32_t rot_dim;
+    int32_t pairing;
+} kdn_rope_spec;
+
 /* One request of a batched compose: chunks [host array of n_chunks], offsets [host
  * array of n_chunks RoPE position deltas], the request's block table [device], and
  * the first request token to write. */
@@ -174,6 +194,24 @@ kdn_status kdn_compose(const kdn_chunk *chunks, const int32_t *offsets, int32_t 
  * segment table is copied to the device on `stream` before the kernel. */
 kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
                              const kdn_cache_desc *cache, double rope_base, void *stream);
+
+/* kdn_compose / kdn_compose_batch with a RoPE variant (rope: [host], not NULL).
+ * KDN_EUNSUPPORTED if rot_dim is not a multiple of 16. */
+kdn_status kdn_compose_rope(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                            const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                            int32_t table_len, int32_t dest_token_start, const kdn_rope_spec *rope,
+                            void *stream);
+kdn_status kdn_compose_batch_rope(const kdn_request *requests, int32_t n_requests,
+                                  const kdn_cache_desc *cache, const kdn_rope_spec *rope, void *stream);
+
+/* Patch: the write-back half of selective recompute after a blend (Sec. 3.2, "KV-cache
+ * blending": recomputing a small part of the composed KV).  rows_dev [device, 16-byte
+ * aligned]: bf16 [L][2][n_tokens][H][D] recomputed K and V rows; row i replaces request
+ * token tokens_dev[i] ([device] int32, distinct) through block_table_dev.  Bit copy, no
+ * arithmetic.  A token index outside [0, table_len*block_size) is skipped. */
+kdn_status kdn_patch_rows(const void *rows_dev, const int32_t *tokens_dev, int32_t n_tokens,
+                          const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                          int32_t table_len, void *stream);
 
 /* Compose from chunks held in pinned HOST memory: the delivery module's path from a
  * storage device to the GPU (Sec. 3.1; bandwidth of loading KV into GPU memory, Sec. 3

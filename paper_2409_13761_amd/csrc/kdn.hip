@@ -77,8 +77,10 @@ struct StoreP {
 
 struct PlaceP {
     CacheP c;          // c.L counts the layers the stored rows hold (and the grid covers)
-    const f32x2 *rope; // [rows][D/2] (cos, sin)
+    const f32x2 *rope; // [rows][rot/2] (cos, sin)
     int32_t layer0;    // cache layer that stored layer 0 goes to
+    int32_t rot;       // rotary leading dimensions (head_dim unless partial rotary)
+    int32_t pairing;   // kdn_rope_pairing
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
@@ -318,7 +320,11 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 // read twice.
 // Grid: x = group * 2L + (layer, side), so that neighbouring workgroups write to
 // different (layer, side) planes; y = segment.
-template <int DT, int FMT, bool DENSE, typename Segs>
+// VAR selects the RoPE variants (partial rotary, interleaved pairs): lanes of the rotary
+// part keep the 8 + 8 paired ownership (half-split) or own 16 consecutive elements whose
+// pairs are neighbours (interleaved); lanes beyond the rotary part own 16 consecutive
+// elements and never rotate.
+template <int DT, int FMT, bool DENSE, bool VAR, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 {
     constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 2 : 4;
@@ -356,14 +362,32 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
     const bool rotate = (ls & 1) == 0 && sg.rope_row >= 0;
 
     const int sub = threadIdx.x & (P - 1);
+    // element offsets, within the row, of the two 8-element vectors this lane owns
+    int lo_off = sub * 8, hi_off = half + sub * 8;
+    bool rot_lane = true, interleaved = false;
+    if (VAR) {
+        const int rl = p.rot >> 4; // lanes of the rotary part
+        interleaved = p.pairing == KDN_ROPE_INTERLEAVED;
+        rot_lane = sub < rl;
+        if (interleaved) {
+            lo_off = sub * 16;
+            hi_off = lo_off + 8;
+        } else if (rot_lane) {
+            hi_off = (p.rot >> 1) + sub * 8;
+        } else {
+            lo_off = p.rot + (sub - rl) * 16;
+            hi_off = lo_off + 8;
+        }
+    }
+    const int rhalf = VAR ? p.rot >> 1 : half; // entries of a cos/sin row
     __shared__ f32x2 s_cs[kMaxHeadDim / 2];
     f32x2 cs[8];
     if (rotate) {
-        const f32x2 *row = p.rope + (int64_t)sg.rope_row * half;
-        for (int i = threadIdx.x; i < half; i += kThreads)
+        const f32x2 *row = p.rope + (int64_t)sg.rope_row * rhalf;
+        for (int i = threadIdx.x; i < rhalf; i += kThreads)
             s_cs[i] = row[i];
         __syncthreads();
-        if (sub < R) {
+        if (sub < R && rot_lane) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 cs[e] = s_cs[sub * 8 + e];
@@ -371,6 +395,7 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
     }
     if (sub >= R)
         return;
+    const bool rotate_lane = rotate && rot_lane;
 
     for (int it0 = threadIdx.x; it0 < n_items; it0 += kThreads * U) {
         uint32_t lo[U][W], hi[U][W];
@@ -380,15 +405,16 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
             const int it = it0 + u * kThreads;
             if (it < n_items) {
                 const int r = it >> LOGP;
-                const uint8_t *src = data + (((uint32_t)(r * D + sub * 8) * W) >> 1);
+                const uint8_t *src = data + (((uint32_t)(r * D + lo_off) * W) >> 1);
+                const uint8_t *src_hi = data + (((uint32_t)(r * D + hi_off) * W) >> 1);
                 if (FMT == KDN_FMT_INT4_GROUP32) {
                     lo[u][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src));
-                    hi[u][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src + (half >> 1)));
-                    sc[u][0] = scales[r * spr + (sub >> 2)];
-                    sc[u][NS - 1] = scales[r * spr + ((half + sub * 8) >> 5)];
+                    hi[u][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src_hi));
+                    sc[u][0] = scales[r * spr + (lo_off >> 5)];
+                    sc[u][NS - 1] = scales[r * spr + (hi_off >> 5)];
                 } else if (FMT == KDN_FMT_RAW_BF16) {
                     const u32x4 l4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
-                    const u32x4 h4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + D));
+                    const u32x4 h4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src_hi));
 #pragma unroll
                     for (int w = 0; w < W; ++w) {
                         lo[u][w] = l4[w];
@@ -396,7 +422,7 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                     }
                 } else {
                     const u32x2 l2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src));
-                    const u32x2 h2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src + half));
+                    const u32x2 h2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src_hi));
 #pragma unroll
                     for (int w = 0; w < W; ++w) {
                         lo[u][w] = l2[w & 1];
@@ -412,15 +438,15 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
             if (it >= n_items)
                 continue;
             const int r = it >> LOGP;
-            uint16_t *dst;
+            uint16_t *dst; // the row's first element
             if (DENSE) {
-                dst = tile + (uint32_t)(r * D + sub * 8);
+                dst = tile + (uint32_t)(r * D);
             } else {
                 const int tok = r / H, h = r - tok * H;
-                dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride + sub * 8;
+                dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
             }
             u32x4 olo, ohi;
-            if (FMT == KDN_FMT_RAW_BF16 && !rotate) { // bit copy
+            if (FMT == KDN_FMT_RAW_BF16 && !rotate_lane) { // bit copy
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
                     olo[w] = lo[u][w % W];
@@ -449,7 +475,19 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                         b[e] = code_f32(hi[u][(e >> 2) % W], e & 3) * sc[u][0];
                     }
                 }
-                if (rotate) {
+                if (VAR && rotate_lane && interleaved) {
+                    // pairs are neighbours: (a0,a1)..(a6,a7) take cs[0..3], (b0,b1).. cs[4..7]
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float c0 = cs[e].x, s0 = cs[e].y, c1 = cs[4 + e].x, s1 = cs[4 + e].y;
+                        const float x0 = a[2 * e], y0 = a[2 * e + 1], x1 = b[2 * e], y1 = b[2 * e + 1];
+                        const float x0c = x0 * c0, y0c = y0 * c0, x1c = x1 * c1, y1c = y1 * c1;
+                        a[2 * e] = __builtin_fmaf(-y0, s0, x0c);
+                        a[2 * e + 1] = __builtin_fmaf(x0, s0, y0c);
+                        b[2 * e] = __builtin_fmaf(-y1, s1, x1c);
+                        b[2 * e + 1] = __builtin_fmaf(x1, s1, y1c);
+                    }
+                } else if (rotate_lane) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const float c = cs[e].x, s = cs[e].y;
@@ -466,9 +504,41 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                     ohi[w] = pack_bf16(b[2 * w], b[2 * w + 1]);
                 }
             }
-            __builtin_nontemporal_store(olo, reinterpret_cast<u32x4 *>(dst));
-            __builtin_nontemporal_store(ohi, reinterpret_cast<u32x4 *>(dst + half));
+            __builtin_nontemporal_store(olo, reinterpret_cast<u32x4 *>(dst + lo_off));
+            __builtin_nontemporal_store(ohi, reinterpret_cast<u32x4 *>(dst + hi_off));
         }
+    }
+}
+
+// patch: rows [L][2][n][H][D] replace the rows of n request tokens (bit copy).
+// One workgroup per (token, layer, side); a token outside the table is skipped.
+struct PatchP {
+    CacheP c;
+    const uint16_t *rows;
+    const int32_t *tokens;
+    const int32_t *bt;
+    int32_t n, limit;
+};
+
+__global__ __launch_bounds__(kThreads) void k_patch(PatchP p)
+{
+    const int L2 = 2 * p.c.L;
+    const int i = blockIdx.x / L2;
+    const int ls = blockIdx.x - i * L2;
+    const int tok = p.tokens[i];
+    if (tok < 0 || tok >= p.limit)
+        return;
+    const int blk = p.bt[tok / p.c.bs];
+    const int slot = tok % p.c.bs;
+    uint16_t *dst = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(ls >> 1) * p.c.layer_stride
+                    + (int64_t)blk * p.c.block_stride + (int64_t)slot * p.c.token_stride;
+    const int D = p.c.D, H = p.c.H;
+    const uint16_t *src = p.rows + ((int64_t)ls * p.n + i) * H * D;
+    const int vec_per_row = D >> 3;
+    for (int v = threadIdx.x; v < H * vec_per_row; v += kThreads) {
+        const int h = v / vec_per_row, j = (v - h * vec_per_row) * 8;
+        const u32x4 w = *reinterpret_cast<const u32x4 *>(src + (int64_t)h * D + j);
+        *reinterpret_cast<u32x4 *>(dst + (int64_t)h * p.c.head_stride + j) = w;
     }
 }
 
@@ -503,14 +573,25 @@ __global__ void k_validate(const int32_t *bt, int32_t n, int32_t num_blocks, uin
 // ---------------------------------------------------------------------------------
 // host planner
 
+// Resolved RoPE variant of one call: frequencies either derived from `base` or given.
+struct RopeSpec {
+    double base = 0.0;
+    std::vector<double> freq; // rot/2 explicit frequencies, empty: base^(-2j/rot)
+    int32_t rot = 0;
+    int32_t pairing = KDN_ROPE_HALF_SPLIT;
+};
+
+// cos/sin rows of one (frequencies, rot) pair, one row per offset seen so far
 struct RopeTable {
     f32x2 *dev = nullptr;
-    int32_t D = 0;
+    double base = 0.0;
+    std::vector<double> freq;
+    int32_t rot = 0;
     std::unordered_map<int32_t, int32_t> row_of;
 };
 
 struct DeviceState {
-    std::unordered_map<uint64_t, RopeTable> rope; // key: bits of base xor D<<52 ... see rope_key
+    std::vector<RopeTable> rope;
     uint8_t *seg_dev = nullptr;                   // kSegSlots * kSegSlotBytes
     uint8_t *seg_host = nullptr;                  // pinned mirror
     hipEvent_t seg_done[kSegSlots] = {};
@@ -526,13 +607,6 @@ struct DeviceState {
 
 std::mutex g_mu;
 std::unordered_map<int, DeviceState> g_dev;
-
-uint64_t rope_key(double base, int32_t D)
-{
-    uint64_t b;
-    std::memcpy(&b, &base, sizeof b);
-    return b * 1000003ull + (uint64_t)D;
-}
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -626,9 +700,32 @@ DeviceState *device_state(int *dev_out)
     return &g_dev[dev];
 }
 
-// Returns the cos/sin table of (base, D) and fills rows[i] for offsets[i] (-1 for a
+// Validates a caller's RoPE variant for head_dim D.  NULL selects the default
+// (all of D rotary, half-split pairs, frequencies from `base`).
+kdn_status resolve_spec(const kdn_rope_spec *in, double base, int32_t D, RopeSpec &out)
+{
+    out = RopeSpec();
+    out.base = in ? in->base : base;
+    out.rot = in && in->rot_dim ? in->rot_dim : D;
+    out.pairing = in ? in->pairing : (int32_t)KDN_ROPE_HALF_SPLIT;
+    if (out.pairing != KDN_ROPE_HALF_SPLIT && out.pairing != KDN_ROPE_INTERLEAVED)
+        return KDN_EINVAL;
+    if (out.rot <= 0 || out.rot > D)
+        return KDN_EINVAL;
+    if (out.rot % 16 != 0) // a lane rotates 8 pairs
+        return KDN_EUNSUPPORTED;
+    if (in && in->inv_freq) {
+        out.freq.assign(in->inv_freq, in->inv_freq + out.rot / 2);
+        for (double f : out.freq)
+            if (!std::isfinite(f))
+                return KDN_EINVAL;
+    }
+    return KDN_OK;
+}
+
+// Returns the cos/sin table of the variant and fills rows[i] for offsets[i] (-1 for a
 // zero offset).  New rows are computed in double and uploaded before returning.
-kdn_status rope_rows(DeviceState *ds, double base, int32_t D, const int32_t *offsets, int32_t n,
+kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t *offsets, int32_t n,
                      int32_t *rows, const f32x2 **table)
 {
     *table = nullptr;
@@ -640,7 +737,7 @@ kdn_status rope_rows(DeviceState *ds, double base, int32_t D, const int32_t *off
             rows[i] = -1;
         return KDN_OK;
     }
-    if (!(base > 0.0) || !std::isfinite(base))
+    if (spec.freq.empty() && (!(spec.base > 0.0) || !std::isfinite(spec.base)))
         return KDN_EINVAL;
     {
         std::unordered_map<int32_t, int32_t> distinct;
@@ -650,14 +747,25 @@ kdn_status rope_rows(DeviceState *ds, double base, int32_t D, const int32_t *off
         if ((int32_t)distinct.size() > kRopeRowsCap)
             return KDN_ESIZE;
     }
-    RopeTable &rt = ds->rope[rope_key(base, D)];
-    const int32_t half = D / 2;
-    if (!rt.dev) {
-        if (hipMalloc(reinterpret_cast<void **>(&rt.dev), (size_t)kRopeRowsCap * half * sizeof(f32x2))
-            != hipSuccess)
-            return KDN_EDEVICE;
-        rt.D = D;
+    size_t ti = 0;
+    for (; ti < ds->rope.size(); ++ti) {
+        const RopeTable &t = ds->rope[ti];
+        if (t.rot == spec.rot && t.freq == spec.freq && (!spec.freq.empty() || t.base == spec.base))
+            break;
     }
+    if (ti == ds->rope.size()) {
+        RopeTable t;
+        t.base = spec.base;
+        t.freq = spec.freq;
+        t.rot = spec.rot;
+        ds->rope.push_back(std::move(t));
+    }
+    RopeTable &rt = ds->rope[ti];
+    const int32_t half = spec.rot / 2;
+    if (!rt.dev
+        && hipMalloc(reinterpret_cast<void **>(&rt.dev), (size_t)kRopeRowsCap * half * sizeof(f32x2))
+               != hipSuccess)
+        return KDN_EDEVICE;
     std::vector<float> row((size_t)half * 2);
     for (int32_t i = 0; i < n; ++i) {
         const int32_t d = offsets[i];
@@ -680,7 +788,8 @@ kdn_status rope_rows(DeviceState *ds, double base, int32_t D, const int32_t *off
                     rows[k] = -2;
         }
         for (int32_t j = 0; j < half; ++j) {
-            const double theta = std::pow(base, -(double)(2 * j) / (double)D);
+            const double theta = spec.freq.empty() ? std::pow(spec.base, -(double)(2 * j) / (double)spec.rot)
+                                                   : spec.freq[(size_t)j];
             const double phi = (double)d * theta;
             row[2 * j] = (float)std::cos(phi);
             row[2 * j + 1] = (float)std::sin(phi);
@@ -695,7 +804,7 @@ kdn_status rope_rows(DeviceState *ds, double base, int32_t D, const int32_t *off
     }
     for (int32_t i = 0; i < n; ++i)
         if (rows[i] == -2) // only after a table reset inside this call
-            return rope_rows(ds, base, D, offsets, n, rows, table);
+            return rope_rows(ds, spec, offsets, n, rows, table);
     *table = rt.dev;
     return KDN_OK;
 }
@@ -727,24 +836,36 @@ void launch_store_d(const StoreP &p, dim3 grid, hipStream_t st)
     }
 }
 
-template <int DT, int FMT>
-void launch_place(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
-                  hipStream_t st)
+template <int DT, int FMT, bool DENSE, bool VAR>
+void launch_place_v(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
+                    hipStream_t st)
 {
     if (segs_dev) {
         SegsDevice sd{segs_dev};
-        if (p.c.dense)
-            hipLaunchKernelGGL((k_place<DT, FMT, true, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
-        else
-            hipLaunchKernelGGL((k_place<DT, FMT, false, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
     } else {
         SegsInline si;
         std::memset(&si, 0, sizeof si);
         std::memcpy(si.s, segs, (size_t)n * sizeof(Seg));
-        if (p.c.dense)
-            hipLaunchKernelGGL((k_place<DT, FMT, true, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+    }
+}
+
+template <int DT, int FMT>
+void launch_place(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
+                  hipStream_t st)
+{
+    const bool var = p.rot != p.c.D || p.pairing != KDN_ROPE_HALF_SPLIT;
+    if (p.c.dense) {
+        if (var)
+            launch_place_v<DT, FMT, true, true>(p, segs, n, segs_dev, grid, st);
         else
-            hipLaunchKernelGGL((k_place<DT, FMT, false, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+            launch_place_v<DT, FMT, true, false>(p, segs, n, segs_dev, grid, st);
+    } else {
+        if (var)
+            launch_place_v<DT, FMT, false, true>(p, segs, n, segs_dev, grid, st);
+        else
+            launch_place_v<DT, FMT, false, false>(p, segs, n, segs_dev, grid, st);
     }
 }
 
@@ -816,11 +937,15 @@ kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const s
 }
 
 kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
-                        double rope_base, void *stream)
+                        double rope_base, const kdn_rope_spec *variant, void *stream)
 {
     if (!reqs || n_reqs <= 0)
         return KDN_EINVAL;
     kdn_status st = check_cache(cache);
+    if (st != KDN_OK)
+        return st;
+    RopeSpec spec;
+    st = resolve_spec(variant, rope_base, cache->head_dim, spec);
     if (st != KDN_OK)
         return st;
     std::vector<int32_t> offs;
@@ -847,8 +972,10 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
     PlaceP p;
     p.c = make_cache_p(cache);
     p.layer0 = 0;
+    p.rot = spec.rot;
+    p.pairing = spec.pairing;
     std::vector<int32_t> rows(offs.size());
-    st = rope_rows(ds, rope_base, cache->head_dim, offs.data(), (int32_t)offs.size(), rows.data(), &p.rope);
+    st = rope_rows(ds, spec, offs.data(), (int32_t)offs.size(), rows.data(), &p.rope);
     if (st != KDN_OK)
         return st;
     std::vector<Seg> segs[3];
@@ -1033,7 +1160,7 @@ kdn_status kdn_load_chunk(const kdn_chunk *chunk, const kdn_cache_desc *cache,
     kdn_request q = {chunk, &zero, 1, block_table_dev, table_len, dest_token_start};
     if (!chunk)
         return KDN_EINVAL;
-    return compose_impl(&q, 1, cache, 1.0, stream);
+    return compose_impl(&q, 1, cache, 1.0, nullptr, stream);
 }
 
 kdn_status kdn_compose(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
@@ -1041,13 +1168,58 @@ kdn_status kdn_compose(const kdn_chunk *chunks, const int32_t *offsets, int32_t 
                        int32_t table_len, int32_t dest_token_start, double rope_base, void *stream)
 {
     kdn_request q = {chunks, offsets, n_chunks, block_table_dev, table_len, dest_token_start};
-    return compose_impl(&q, 1, cache, rope_base, stream);
+    return compose_impl(&q, 1, cache, rope_base, nullptr, stream);
 }
 
 kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
                              const kdn_cache_desc *cache, double rope_base, void *stream)
 {
-    return compose_impl(requests, n_requests, cache, rope_base, stream);
+    return compose_impl(requests, n_requests, cache, rope_base, nullptr, stream);
+}
+
+kdn_status kdn_compose_rope(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                            const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                            int32_t table_len, int32_t dest_token_start, const kdn_rope_spec *rope,
+                            void *stream)
+{
+    if (!rope)
+        return KDN_EINVAL;
+    kdn_request q = {chunks, offsets, n_chunks, block_table_dev, table_len, dest_token_start};
+    return compose_impl(&q, 1, cache, rope->base, rope, stream);
+}
+
+kdn_status kdn_compose_batch_rope(const kdn_request *requests, int32_t n_requests,
+                                  const kdn_cache_desc *cache, const kdn_rope_spec *rope, void *stream)
+{
+    if (!rope)
+        return KDN_EINVAL;
+    return compose_impl(requests, n_requests, cache, rope->base, rope, stream);
+}
+
+kdn_status kdn_patch_rows(const void *rows_dev, const int32_t *tokens_dev, int32_t n_tokens,
+                          const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                          int32_t table_len, void *stream)
+{
+    kdn_status st = check_cache(cache);
+    if (st != KDN_OK)
+        return st;
+    if (!rows_dev || !tokens_dev || !block_table_dev || n_tokens <= 0 || table_len <= 0)
+        return KDN_EINVAL;
+    if (!aligned16(rows_dev))
+        return KDN_EALIGN;
+    if ((int64_t)n_tokens * 2 * cache->num_layers > 0x7fffffff / kThreads)
+        return KDN_ESIZE;
+    PatchP p;
+    p.c = make_cache_p(cache);
+    p.rows = static_cast<const uint16_t *>(rows_dev);
+    p.tokens = tokens_dev;
+    p.bt = block_table_dev;
+    p.n = n_tokens;
+    p.limit = (int64_t)table_len * cache->block_size > 0x7fffffff ? 0x7fffffff
+                                                                   : table_len * cache->block_size;
+    dim3 grid((unsigned)(n_tokens * 2 * cache->num_layers), 1, 1);
+    hipLaunchKernelGGL(k_patch, grid, dim3(kThreads), 0, static_cast<hipStream_t>(stream), p);
+    return hip_status(hipGetLastError());
 }
 
 uint64_t kdn_staging_bytes(const kdn_chunk *chunks, int32_t n_chunks, int32_t layers_per_stage)
@@ -1119,8 +1291,14 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
     hipStream_t user = static_cast<hipStream_t>(stream);
     PlaceP p;
     p.c = make_cache_p(cache);
+    RopeSpec spec;
+    st = resolve_spec(nullptr, rope_base, cache->head_dim, spec);
+    if (st != KDN_OK)
+        return st;
+    p.rot = spec.rot;
+    p.pairing = spec.pairing;
     std::vector<int32_t> rows((size_t)n_chunks);
-    st = rope_rows(ds, rope_base, cache->head_dim, offsets, n_chunks, rows.data(), &p.rope);
+    st = rope_rows(ds, spec, offsets, n_chunks, rows.data(), &p.rope);
     if (st != KDN_OK)
         return st;
 
@@ -1218,7 +1396,11 @@ kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *o
         return KDN_EDEVICE;
     std::vector<int32_t> rows((size_t)n);
     const f32x2 *table;
-    return rope_rows(ds, rope_base, head_dim, offsets, n, rows.data(), &table);
+    RopeSpec spec;
+    st = resolve_spec(nullptr, rope_base, head_dim, spec);
+    if (st != KDN_OK)
+        return st;
+    return rope_rows(ds, spec, offsets, n, rows.data(), &table);
 }
 
 kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t table_len,
@@ -1277,8 +1459,8 @@ kdn_status kdn_shutdown(void)
         }
         DeviceState &ds = kv.second;
         for (auto &rt : ds.rope)
-            if (rt.second.dev)
-                (void)hipFree(rt.second.dev);
+            if (rt.dev)
+                (void)hipFree(rt.dev);
         if (ds.seg_dev)
             (void)hipFree(ds.seg_dev);
         if (ds.seg_host)

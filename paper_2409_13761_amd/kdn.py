@@ -43,6 +43,15 @@ class ChunkDesc(C.Structure):
                 ("parent_tokens", C.c_int32), ("token_start", C.c_int32), ("num_tokens", C.c_int32)]
 
 
+class RopeSpecDesc(C.Structure):
+    _fields_ = [("base", C.c_double), ("inv_freq", C.POINTER(C.c_double)),
+                ("rot_dim", C.c_int32), ("pairing", C.c_int32)]
+
+
+ROPE_HALF_SPLIT = 0
+ROPE_INTERLEAVED = 1
+
+
 class RequestDesc(C.Structure):
     _fields_ = [("chunks", C.POINTER(ChunkDesc)), ("offsets", C.POINTER(C.c_int32)),
                 ("n_chunks", C.c_int32), ("block_table_dev", C.c_void_p),
@@ -77,6 +86,14 @@ def lib() -> C.CDLL:
         L.kdn_compose_batch.restype = C.c_int
         L.kdn_compose_batch.argtypes = [C.POINTER(RequestDesc), i32, C.POINTER(CacheDesc),
                                         C.c_double, vp]
+        L.kdn_compose_rope.restype = C.c_int
+        L.kdn_compose_rope.argtypes = [C.POINTER(ChunkDesc), C.POINTER(i32), i32, C.POINTER(CacheDesc),
+                                       vp, i32, i32, C.POINTER(RopeSpecDesc), vp]
+        L.kdn_compose_batch_rope.restype = C.c_int
+        L.kdn_compose_batch_rope.argtypes = [C.POINTER(RequestDesc), i32, C.POINTER(CacheDesc),
+                                             C.POINTER(RopeSpecDesc), vp]
+        L.kdn_patch_rows.restype = C.c_int
+        L.kdn_patch_rows.argtypes = [vp, vp, i32, C.POINTER(CacheDesc), vp, i32, vp]
         L.kdn_compose_from_host.restype = C.c_int
         L.kdn_compose_from_host.argtypes = [C.POINTER(ChunkDesc), C.POINTER(i32), i32,
                                             C.POINTER(CacheDesc), vp, i32, i32, C.c_double,
@@ -101,7 +118,8 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk",
-           "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_from_host",
+           "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_rope",
+           "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host",
            "kdn_staging_bytes", "kdn_rope_prepare",
            "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version"]
@@ -290,6 +308,51 @@ def kdn_compose_batch(plan_or_requests, cache: PagedCache, rope_base: float, str
     cd = cache.desc()
     _check(lib().kdn_compose_batch(plan.arr, plan.n, C.byref(cd), float(rope_base), _stream(stream)),
            "kdn_compose_batch")
+
+
+def rope_spec(base: float = 10000.0, inv_freq=None, rot_dim: int = 0,
+              pairing: int = ROPE_HALF_SPLIT):
+    """Marshal a RoPE variant; returns (RopeSpecDesc, keep-alive)."""
+    arr = None
+    if inv_freq is not None:
+        arr = (C.c_double * len(inv_freq))(*[float(f) for f in inv_freq])
+    d = RopeSpecDesc(float(base), C.cast(arr, C.POINTER(C.c_double)) if arr is not None else None,
+                     int(rot_dim), int(pairing))
+    return d, arr
+
+
+def kdn_compose_rope(chunks, offsets, cache: PagedCache, block_table: torch.Tensor, spec,
+                     dest_token_start: int = 0, stream=None) -> None:
+    """spec: the pair returned by rope_spec()."""
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous()
+    assert len(chunks) == len(offsets)
+    cd = cache.desc()
+    arr = _chunk_array(chunks)
+    off = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
+    _check(lib().kdn_compose_rope(arr, off, len(chunks), C.byref(cd), block_table.data_ptr(),
+                                  block_table.numel(), dest_token_start, C.byref(spec[0]),
+                                  _stream(stream)), "kdn_compose_rope")
+
+
+def kdn_compose_batch_rope(plan_or_requests, cache: PagedCache, spec, stream=None) -> None:
+    plan = plan_or_requests if isinstance(plan_or_requests, BatchPlan) else BatchPlan(plan_or_requests)
+    cd = cache.desc()
+    _check(lib().kdn_compose_batch_rope(plan.arr, plan.n, C.byref(cd), C.byref(spec[0]), _stream(stream)),
+           "kdn_compose_batch_rope")
+
+
+def kdn_patch_rows(rows: torch.Tensor, tokens: torch.Tensor, cache: PagedCache,
+                   block_table: torch.Tensor, stream=None) -> None:
+    """rows: bf16 [L][2][n][H][D] on the device; tokens: int32 [n] on the device."""
+    L, _, _, H, D = cache.shape
+    assert rows.dtype == torch.bfloat16 and rows.is_contiguous() and rows.is_cuda
+    assert tokens.dtype == torch.int32 and tokens.is_contiguous() and tokens.is_cuda
+    assert tuple(rows.shape) == (L, 2, tokens.numel(), H, D)
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous()
+    cd = cache.desc()
+    _check(lib().kdn_patch_rows(rows.data_ptr(), tokens.data_ptr(), tokens.numel(), C.byref(cd),
+                                block_table.data_ptr(), block_table.numel(), _stream(stream)),
+           "kdn_patch_rows")
 
 
 def pinned_host_copy(chunk: Chunk) -> Chunk:

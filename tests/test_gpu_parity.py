@@ -358,3 +358,98 @@ def test_compose_from_pinned_host_chunks_equals_compose(layers_per_stage):
     with pytest.raises(kdn.KdnError) as e:       # device-resident chunks are refused here
         kdn.kdn_compose_from_host([chunk_to_dev(c)], [0], dd, dev_table(dst_bt), 10000.0, staging, layers_per_stage)
     assert e.value.status == kdn.EINVAL
+
+
+# ------------------------------------------------------------------ RoPE variants, patching
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("variant", [
+    # D, rot_dim, pairing, explicit frequencies?
+    (128, 0, 1, False),        # interleaved pairs, whole row
+    (128, 64, 0, False),       # partial rotary, half-split
+    (128, 64, 1, False),       # partial rotary, interleaved
+    (64, 32, 0, True),         # explicit (rescaled) frequencies, partial
+    (128, 0, 0, True),         # explicit frequencies, plain pairing
+    (256, 16, 1, False),       # smallest rotary part
+    (96, 32, 0, False),        # head_dim whose lane group is padded
+])
+def test_compose_rope_variants(fmt, variant):
+    D, rot, pairing, explicit = variant
+    _say("compose_rope fmt=%d variant=%s" % (fmt, variant))
+    L, nb, bs, H = 2, 64, 16, 2
+    base = 500000.0
+    r = rot or D
+    inv_freq = None
+    if explicit:
+        j = np.arange(r // 2, dtype=np.float64)
+        inv_freq = base ** (-2.0 * j / r) / np.where(j >= r // 4, 8.0, 1.0)
+    src = host_cache(600 + D, L, nb, bs, H, D)
+    t1, t2, t3, dst_bt = synth.disjoint_block_tables(13, nb, [4, 3, 5, 16])
+    chunks = [O.store(src, t1, 0, 61, fmt), O.store(src, t2, 2, 40, fmt), O.store(src, t3, 5, 70, fmt)]
+    offsets = [0, 61, -1000]
+    hd = host_cache(700 + D, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose_spec(chunks, offsets, hd, dst_bt, base, inv_freq=inv_freq, rot_dim=rot, pairing=pairing, dest=9)
+    spec = kdn.rope_spec(base, inv_freq, rot, pairing)
+    kdn.kdn_compose_rope([chunk_to_dev(c) for c in chunks], offsets, dd, dev_table(dst_bt), spec,
+                         dest_token_start=9)
+    assert_cache_equal(dd, hd)
+
+
+def test_compose_rope_default_spec_is_compose():
+    L, nb, bs, H, D = 2, 32, 16, 2, 64
+    src = host_cache(81, L, nb, bs, H, D)
+    a, b = synth.disjoint_block_tables(81, nb, [5, 8])
+    ch = O.store(src, a, 0, 77, INT8)
+    hd = host_cache(82, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose([ch], [33], hd, b, 10000.0, dest=4)
+    kdn.kdn_compose_rope([chunk_to_dev(ch)], [33], dd, dev_table(b), kdn.rope_spec(10000.0), dest_token_start=4)
+    assert_cache_equal(dd, hd)
+    bad = kdn.rope_spec(10000.0, None, 24, 0)                 # rot_dim not a multiple of 16
+    with pytest.raises(kdn.KdnError) as e:
+        kdn.kdn_compose_rope([chunk_to_dev(ch)], [33], dd, dev_table(b), bad)
+    assert e.value.status == kdn.EUNSUPPORTED
+    bad = kdn.rope_spec(10000.0, None, 0, 5)
+    with pytest.raises(kdn.KdnError) as e:
+        kdn.kdn_compose_rope([chunk_to_dev(ch)], [33], dd, dev_table(b), bad)
+    assert e.value.status == kdn.EINVAL
+
+
+def test_batched_compose_with_a_variant():
+    L, nb, bs, H, D = 2, 96, 16, 2, 128
+    src = host_cache(83, L, nb, bs, H, D)
+    tabs = synth.disjoint_block_tables(83, nb, [6] * 4 + [12] * 5)
+    pool = [O.store(src, tabs[i], 0, 90 - i, INT8) for i in range(4)]
+    dpool = [chunk_to_dev(c) for c in pool]
+    hd = host_cache(84, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    reqs = []
+    for r in range(5):
+        ids = [r % 4, (r + 1) % 4]
+        offs = [5 * r, -pool[ids[0]].T]
+        O.compose_spec([pool[i] for i in ids], offs, hd, tabs[4 + r], 10000.0, rot_dim=64, pairing=1, dest=r)
+        reqs.append(([dpool[i] for i in ids], offs, dev_table(tabs[4 + r]), r))
+    kdn.kdn_compose_batch_rope(reqs, dd, kdn.rope_spec(10000.0, None, 64, 1))
+    assert_cache_equal(dd, hd)
+
+
+@pytest.mark.parametrize("shape", [(2, 24, 16, 4, 64), (3, 40, 16, 8, 128), (1, 30, 8, 3, 96), (1, 64, 1, 2, 32)])
+def test_patch_rows_matches_oracle(shape):
+    L, nb, bs, H, D = shape
+    hc = host_cache(85 + D, L, nb, bs, H, D)
+    dc = dev_cache(hc)
+    n_tab = min(nb - 2, 12)
+    bt = synth.disjoint_block_tables(85, nb, [n_tab])[0]
+    cap = n_tab * bs
+    tokens = synth.permutation(86, cap)[:min(cap, 37)].astype(np.int32)
+    rows = synth.normal_bf16(87, (L, 2, len(tokens), H, D))
+    O.patch_rows(rows, tokens, hc, bt)
+    kdn.kdn_patch_rows(to_dev_bf16(rows), torch.from_numpy(tokens).cuda(), dc, dev_table(bt))
+    assert_cache_equal(dc, hc)
+    # a token outside the table is skipped, the others still land
+    tok2 = tokens.copy()
+    tok2[0] = cap + 5
+    rows2 = synth.normal_bf16(88, rows.shape)
+    O.patch_rows(rows2[:, :, 1:], tok2[1:], hc, bt)
+    kdn.kdn_patch_rows(to_dev_bf16(rows2), torch.from_numpy(tok2).cuda(), dc, dev_table(bt))
+    assert_cache_equal(dc, hc)

@@ -17,7 +17,8 @@ compose of four 8192-token slices) and "batched_reuse" (64 requests x 4 chunks o
 1024 tokens drawn by Zipf popularity from a resident pool of 256 chunks, one batched
 compose per step).
 
-"host_stream_int8" / "host_stream_raw" compose a chunk that lives in pinned host memory
+"pool_trace" is a serving loop over the text-keyed index (store on miss, compose on
+hit) and reports the hit rate.  "host_stream_int8" / "host_stream_raw" compose a chunk that lives in pinned host memory
 (the rate there includes PCIe and is link bound; its roofline entry is still priced
 against HBM and is not a kernel-quality figure).
 
@@ -108,8 +109,15 @@ def workload_8b(args, dev):
     nb = n_sets * 3 * blocks
     g = torch.Generator(device=dev)
     g.manual_seed(w.seed)
-    k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
-    v = torch.empty_like(k)
+    if args.layout == "planes":         # K and V tensors [L][num_blocks][bs][H][D]
+        k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+        v = torch.empty_like(k)
+    elif args.layout == "kv_pair":      # one tensor [L][num_blocks][2][bs][H][D]: a block's K and V adjoin
+        big = torch.empty((sh.L, nb, 2, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+        k, v = big[:, :, 0], big[:, :, 1]
+    else:                               # block_major: [num_blocks][L][2][bs][H][D], a block is one 2 MiB run
+        big = torch.empty((nb, sh.L, 2, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+        k, v = big[:, :, 0].permute(1, 0, 2, 3, 4), big[:, :, 1].permute(1, 0, 2, 3, 4)
     fill_normal(k, g)
     fill_normal(v, g)
     cache = kdn.PagedCache(k, v)
@@ -144,7 +152,8 @@ def workload_8b(args, dev):
         "place_calls": ("load", "compose"),
         "workload": "Llama-3-8B-shaped KV (L32 H8 D128 bs16): per step store 4096 tokens to %s, "
                     "load them at offset 0, compose them as 8x512-token slices in seeded order with "
-                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled" % (args.fmt, w.rope_base, n_sets),
+                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled; cache layout %s"
+                    % (args.fmt, w.rope_base, n_sets, args.layout),
         "traffic": counter_traffic() if args.fmt == "int8" else None,
     }
     if not args.no_cpu_baseline and args.fmt == "int8":
@@ -306,7 +315,81 @@ def workload_host_stream(args, dev, fmt_name):
     }
 
 
-def cpu_baseline(cache, src, order, offsets, base, T, n_slices, steps):
+def workload_pool_trace(args, dev):
+    """Serving loop over the text-keyed index: each step is one request that names 4 of 256
+    texts by Zipf(1.0) popularity.  A text whose KV is resident is a hit; on a miss its KV
+    is stored (int8) from the engine's paged memory into a buffer taken from the evicted
+    entries, and indexed.  The 4 chunks are then composed into the request's block table.
+    The index holds 64 chunks of 1024 tokens."""
+    import numpy as np
+    import torch
+    from paper_2409_13761_amd import kdn, synth
+
+    w = synth.WORKLOADS["batched_reuse"]
+    sh = w.shape
+    n_texts, per_req, Tc, resident = w.extra["pool"], 4, 1024, 64
+    cb = Tc // sh.bs
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    n_src = 16                                   # distinct source contexts standing in for 256 texts
+    nb = n_src * cb + 2 * per_req * cb
+    k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+    v = torch.empty_like(k)
+    fill_normal(k, g)
+    fill_normal(v, g)
+    cache = kdn.PagedCache(k, v)
+    tabs = synth.disjoint_block_tables(w.seed, nb, [cb] * n_src + [per_req * cb] * 2)
+    src_tabs = [torch.from_numpy(t).to(dev) for t in tabs[:n_src]]
+    dst_tabs = [torch.from_numpy(t).to(dev) for t in tabs[n_src:]]
+    chunk_bytes = kdn.kdn_chunk_bytes(sh.L, sh.H, sh.D, Tc, kdn.FMT_INT8_ROWSCALE)
+    free = [kdn.alloc_chunk(cache, Tc, kdn.FMT_INT8_ROWSCALE) for _ in range(resident + per_req)]
+    by_ptr = {c.data.data_ptr(): c for c in free}
+    pool = kdn.Pool(resident * chunk_bytes, 0)
+    total = args.warmup + args.steps
+    draws = synth.zipf_distinct_draws(w.seed, total, per_req, n_texts, w.extra["alpha"])
+    text_ids = [np.ascontiguousarray(synth._rng(w.seed + 7, 100 + t).integers(0, 128000, size=Tc), dtype=np.int32)
+                for t in range(n_texts)]
+    offsets = list(w.offsets)
+    kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
+    counts = {"hit": 0, "miss": 0}
+
+    def step(i, rec):
+        def body():
+            chunks = []
+            for t in draws[i]:
+                t = int(t)
+                d = pool.lookup(text_ids[t])
+                if d is None:
+                    counts["miss"] += 1
+                    buf = free.pop()
+                    kdn.kdn_store_chunk(cache, src_tabs[t % n_src], 0, Tc, buf)
+                    for e in pool.insert(text_ids[t], buf.desc):
+                        free.append(by_ptr[e.data])
+                    chunks.append(buf)
+                else:
+                    counts["hit"] += 1
+                    chunks.append(by_ptr[d.data])
+            kdn.kdn_compose(chunks, offsets, cache, dst_tabs[i % 2], w.rope_base)
+        rec("request", body)
+
+    wall, ms = Timed(("request",), args.steps).run(step, args.warmup)
+    st = pool.stats()
+    tokens = per_req * Tc
+    return {
+        "tokens_per_step": tokens, "wall": wall, "ms": ms,
+        "bytes": {"request": tokens * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)},
+        "place_calls": ("request",),
+        "workload": "serving loop over the text-keyed index (L32 H8 D128 bs16): per step one request of 4 "
+                    "texts of 1024 tokens drawn by Zipf(1.0) from 256; store-on-miss (int8) into an index of "
+                    "%d resident chunks (LRU), then one compose of the 4 chunks" % resident,
+        "extra": {"hit_rate": st.hits / max(1, st.hits + st.misses), "hits": st.hits, "misses": st.misses,
+                  "evictions": st.evictions,
+                  "note": "the request figure counts the compose bytes only; misses add a store each"},
+        "traffic": None,
+    }
+
+
+def cpu_baseline(cache, src, order, offsets, base, T, n_slices, steps):  # noqa: C901
     """The oracle as it stands, on the host cores: the same step (store, load, compose
     of one 4096-token context, all layers), layers split over threads."""
     import numpy as np
@@ -354,10 +437,15 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=("8b", "70b_long", "batched_reuse", "host_stream_int8", "host_stream_raw"),
+    ap.add_argument("--workload", choices=("8b", "70b_long", "batched_reuse", "host_stream_int8", "host_stream_raw",
+                             "pool_trace"),
                     default="8b")
     ap.add_argument("--fmt", choices=("int8", "int4", "raw"), default="int8",
                     help="stored form used by the 8b and 70b_long workloads")
+    ap.add_argument("--layout", choices=("planes", "kv_pair", "block_major"), default="planes",
+                    help="paged cache layout of the 8b workload, all expressed through the "
+                         "descriptor's strides: separate K and V tensors [L][blocks][bs][H][D] "
+                         "(default), K and V of a block adjoining, or all layers of a block adjoining")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=8)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -369,7 +457,7 @@ def main() -> int:
               "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
         return 2
     defaults = {"8b": (40, 8), "70b_long": (10, 3), "batched_reuse": (10, 3),
-                "host_stream_int8": (10, 3), "host_stream_raw": (10, 3)}[args.workload]
+                "host_stream_int8": (10, 3), "host_stream_raw": (10, 3), "pool_trace": (400, 100)}[args.workload]
     args.steps = defaults[0] if args.steps is None else args.steps
     args.warmup = defaults[1] if args.warmup is None else args.warmup
 
@@ -385,7 +473,8 @@ def main() -> int:
 
     res = {"8b": workload_8b, "70b_long": workload_70b, "batched_reuse": workload_batched,
            "host_stream_int8": lambda a, d: workload_host_stream(a, d, "int8"),
-           "host_stream_raw": lambda a, d: workload_host_stream(a, d, "raw")}[args.workload](args, dev)
+           "host_stream_raw": lambda a, d: workload_host_stream(a, d, "raw"),
+           "pool_trace": workload_pool_trace}[args.workload](args, dev)
 
     if args.calibration_copy:
         a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()

@@ -83,7 +83,8 @@ typedef enum {
     KDN_ERANGE = -3,       /* token range outside the block table / chunk, bad block id (validator) */
     KDN_ESIZE = -4,        /* chunk buffer too small, too many chunks, grid limit exceeded */
     KDN_EDEVICE = -5,      /* a HIP call failed, or no usable device */
-    KDN_EUNSUPPORTED = -6  /* head_dim not a multiple of 16 (32 for int4) or above 512 */
+    KDN_EUNSUPPORTED = -6, /* head_dim not a multiple of 16 (32 for int4) or above 512 */
+    KDN_ENOTFOUND = -7     /* no entry under this key (text-keyed pool) */
 } kdn_status;
 
 typedef enum {

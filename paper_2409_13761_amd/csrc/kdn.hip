@@ -1490,7 +1490,8 @@ const char *kdn_status_str(kdn_status s)
     case KDN_ERANGE: return "token range or block id out of range";
     case KDN_ESIZE: return "buffer too small or too many segments";
     case KDN_EDEVICE: return "HIP call failed";
-    case KDN_EUNSUPPORTED: return "head_dim must be a multiple of 16, at most 512";
+    case KDN_EUNSUPPORTED: return "head_dim must be a multiple of 16 (32 for int4), at most 512";
+    case KDN_ENOTFOUND: return "no entry under this key";
     }
     return "unknown status";
 }

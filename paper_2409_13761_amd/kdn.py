@@ -20,7 +20,7 @@ FMT_RAW_BF16 = 0
 FMT_INT8_ROWSCALE = 1
 FMT_INT4_GROUP32 = 2
 
-OK, EINVAL, EALIGN, ERANGE, ESIZE, EDEVICE, EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, EALIGN, ERANGE, ESIZE, EDEVICE, EUNSUPPORTED, ENOTFOUND = 0, -1, -2, -3, -4, -5, -6, -7
 
 
 class KdnError(RuntimeError):
@@ -50,6 +50,11 @@ class RopeSpecDesc(C.Structure):
 
 ROPE_HALF_SPLIT = 0
 ROPE_INTERLEAVED = 1
+
+
+class PoolStats(C.Structure):
+    _fields_ = [("hits", C.c_uint64), ("misses", C.c_uint64), ("inserts", C.c_uint64),
+                ("evictions", C.c_uint64), ("bytes", C.c_uint64), ("entries", C.c_uint64)]
 
 
 class RequestDesc(C.Structure):
@@ -94,6 +99,21 @@ def lib() -> C.CDLL:
                                              C.POINTER(RopeSpecDesc), vp]
         L.kdn_patch_rows.restype = C.c_int
         L.kdn_patch_rows.argtypes = [vp, vp, i32, C.POINTER(CacheDesc), vp, i32, vp]
+        L.kdn_pool_create.restype = C.c_int
+        L.kdn_pool_create.argtypes = [u64, i32, C.POINTER(vp)]
+        L.kdn_pool_destroy.restype = None
+        L.kdn_pool_destroy.argtypes = [vp]
+        L.kdn_pool_hash.restype = u64
+        L.kdn_pool_hash.argtypes = [vp, i32]
+        L.kdn_pool_lookup.restype = C.c_int
+        L.kdn_pool_lookup.argtypes = [vp, vp, i32, C.POINTER(ChunkDesc)]
+        L.kdn_pool_insert.restype = C.c_int
+        L.kdn_pool_insert.argtypes = [vp, vp, i32, C.POINTER(ChunkDesc), C.POINTER(ChunkDesc), i32,
+                                      C.POINTER(i32)]
+        L.kdn_pool_remove.restype = C.c_int
+        L.kdn_pool_remove.argtypes = [vp, vp, i32, C.POINTER(ChunkDesc)]
+        L.kdn_pool_get_stats.restype = C.c_int
+        L.kdn_pool_get_stats.argtypes = [vp, C.POINTER(PoolStats)]
         L.kdn_compose_from_host.restype = C.c_int
         L.kdn_compose_from_host.argtypes = [C.POINTER(ChunkDesc), C.POINTER(i32), i32,
                                             C.POINTER(CacheDesc), vp, i32, i32, C.c_double,
@@ -122,7 +142,8 @@ EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_ch
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host",
            "kdn_staging_bytes", "kdn_rope_prepare",
            "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
-           "kdn_version"]
+           "kdn_version", "kdn_pool_create", "kdn_pool_destroy", "kdn_pool_hash", "kdn_pool_lookup",
+           "kdn_pool_insert", "kdn_pool_remove", "kdn_pool_get_stats"]
 
 
 def status_str(status: int) -> str:
@@ -409,3 +430,59 @@ def kdn_shutdown() -> None:
 
 def kdn_version() -> str:
     return lib().kdn_version().decode()
+
+
+# ------------------------------------------------------------------ text-keyed index
+def _ids_arg(token_ids):
+    import numpy as np
+    a = np.ascontiguousarray(token_ids, dtype=np.int32)
+    return a, a.ctypes.data, int(a.size)
+
+
+def kdn_pool_hash(token_ids) -> int:
+    a, ptr, n = _ids_arg(token_ids)
+    return int(lib().kdn_pool_hash(ptr, n))
+
+
+class Pool:
+    """Binding of the kdn_pool_* calls: token ids -> chunk descriptor, byte-bounded."""
+
+    def __init__(self, capacity_bytes: int, policy: int = 0):
+        self._h = C.c_void_p()
+        _check(lib().kdn_pool_create(capacity_bytes, policy, C.byref(self._h)), "kdn_pool_create")
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.kdn_pool_destroy(self._h)
+            self._h = None
+
+    def lookup(self, token_ids):
+        a, ptr, n = _ids_arg(token_ids)
+        out = ChunkDesc()
+        st = lib().kdn_pool_lookup(self._h, ptr, n, C.byref(out))
+        if st == ENOTFOUND:
+            return None
+        _check(st, "kdn_pool_lookup")
+        return out
+
+    def insert(self, token_ids, chunk_desc: ChunkDesc, max_evicted: int = 64):
+        a, ptr, n = _ids_arg(token_ids)
+        ev = (ChunkDesc * max(max_evicted, 1))()
+        cnt = C.c_int32(0)
+        _check(lib().kdn_pool_insert(self._h, ptr, n, C.byref(chunk_desc), ev if max_evicted else None,
+                                     max_evicted, C.byref(cnt)), "kdn_pool_insert")
+        return [ChunkDesc.from_buffer_copy(ev[i]) for i in range(cnt.value)]
+
+    def remove(self, token_ids):
+        a, ptr, n = _ids_arg(token_ids)
+        out = ChunkDesc()
+        st = lib().kdn_pool_remove(self._h, ptr, n, C.byref(out))
+        if st == ENOTFOUND:
+            return None
+        _check(st, "kdn_pool_remove")
+        return out
+
+    def stats(self) -> PoolStats:
+        out = PoolStats()
+        _check(lib().kdn_pool_get_stats(self._h, C.byref(out)), "kdn_pool_get_stats")
+        return out

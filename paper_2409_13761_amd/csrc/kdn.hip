@@ -81,6 +81,7 @@ struct PlaceP {
     int32_t layer0;    // cache layer that stored layer 0 goes to
     int32_t rot;       // rotary leading dimensions (head_dim unless partial rotary)
     int32_t pairing;   // kdn_rope_pairing
+    int32_t reuse;     // some stored rows are read by more than one segment: let them stay cached
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
@@ -320,11 +321,23 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 // read twice.
 // Grid: x = group * 2L + (layer, side), so that neighbouring workgroups write to
 // different (layer, side) planes; y = segment.
+// Stored rows are streamed past the caches unless several segments read the same rows
+// (a popular chunk in a batched compose): then they are loaded normally, so that the
+// first reader leaves them in L2 and the last-level cache for the others.
+template <typename T, bool REUSE>
+__device__ __forceinline__ T load_stored(const uint8_t *ptr)
+{
+    const T *q = reinterpret_cast<const T *>(ptr);
+    if (REUSE)
+        return *q;
+    return __builtin_nontemporal_load(q);
+}
+
 // VAR selects the RoPE variants (partial rotary, interleaved pairs): lanes of the rotary
 // part keep the 8 + 8 paired ownership (half-split) or own 16 consecutive elements whose
 // pairs are neighbours (interleaved); lanes beyond the rotary part own 16 consecutive
 // elements and never rotate.
-template <int DT, int FMT, bool DENSE, bool VAR, typename Segs>
+template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 {
     constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 2 : 4;
@@ -408,21 +421,21 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                 const uint8_t *src = data + (((uint32_t)(r * D + lo_off) * W) >> 1);
                 const uint8_t *src_hi = data + (((uint32_t)(r * D + hi_off) * W) >> 1);
                 if (FMT == KDN_FMT_INT4_GROUP32) {
-                    lo[u][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src));
-                    hi[u][0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(src_hi));
+                    lo[u][0] = load_stored<uint32_t, REUSE>(src);
+                    hi[u][0] = load_stored<uint32_t, REUSE>(src_hi);
                     sc[u][0] = scales[r * spr + (lo_off >> 5)];
                     sc[u][NS - 1] = scales[r * spr + (hi_off >> 5)];
                 } else if (FMT == KDN_FMT_RAW_BF16) {
-                    const u32x4 l4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
-                    const u32x4 h4 = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src_hi));
+                    const u32x4 l4 = load_stored<u32x4, REUSE>(src);
+                    const u32x4 h4 = load_stored<u32x4, REUSE>(src_hi);
 #pragma unroll
                     for (int w = 0; w < W; ++w) {
                         lo[u][w] = l4[w];
                         hi[u][w] = h4[w];
                     }
                 } else {
-                    const u32x2 l2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src));
-                    const u32x2 h2 = __builtin_nontemporal_load(reinterpret_cast<const u32x2 *>(src_hi));
+                    const u32x2 l2 = load_stored<u32x2, REUSE>(src);
+                    const u32x2 h2 = load_stored<u32x2, REUSE>(src_hi);
 #pragma unroll
                     for (int w = 0; w < W; ++w) {
                         lo[u][w] = l2[w & 1];
@@ -836,18 +849,18 @@ void launch_store_d(const StoreP &p, dim3 grid, hipStream_t st)
     }
 }
 
-template <int DT, int FMT, bool DENSE, bool VAR>
+template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE>
 void launch_place_v(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
                     hipStream_t st)
 {
     if (segs_dev) {
         SegsDevice sd{segs_dev};
-        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, REUSE, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
     } else {
         SegsInline si;
         std::memset(&si, 0, sizeof si);
         std::memcpy(si.s, segs, (size_t)n * sizeof(Seg));
-        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, REUSE, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
     }
 }
 
@@ -856,16 +869,20 @@ void launch_place(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_d
                   hipStream_t st)
 {
     const bool var = p.rot != p.c.D || p.pairing != KDN_ROPE_HALF_SPLIT;
+    // the cache-friendly load flavour exists for the common serving case only (dense
+    // layout, default RoPE variant); elsewhere shared rows are streamed like any other
     if (p.c.dense) {
         if (var)
-            launch_place_v<DT, FMT, true, true>(p, segs, n, segs_dev, grid, st);
+            launch_place_v<DT, FMT, true, true, false>(p, segs, n, segs_dev, grid, st);
+        else if (p.reuse)
+            launch_place_v<DT, FMT, true, false, true>(p, segs, n, segs_dev, grid, st);
         else
-            launch_place_v<DT, FMT, true, false>(p, segs, n, segs_dev, grid, st);
+            launch_place_v<DT, FMT, true, false, false>(p, segs, n, segs_dev, grid, st);
     } else {
         if (var)
-            launch_place_v<DT, FMT, false, true>(p, segs, n, segs_dev, grid, st);
+            launch_place_v<DT, FMT, false, true, false>(p, segs, n, segs_dev, grid, st);
         else
-            launch_place_v<DT, FMT, false, false>(p, segs, n, segs_dev, grid, st);
+            launch_place_v<DT, FMT, false, false, false>(p, segs, n, segs_dev, grid, st);
     }
 }
 
@@ -1001,10 +1018,17 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
     for (int f = 0; f < 3; ++f) {
         // Segments that read the same stored rows run back to back, so that a popular
         // chunk is fetched from HBM once and from the last-level cache afterwards.
-        if (n_reqs > 1)
+        p.reuse = 0;
+        if (n_reqs > 1) {
             std::stable_sort(segs[f].begin(), segs[f].end(), [](const Seg &a, const Seg &b) {
                 return a.data != b.data ? a.data < b.data : a.tok0 < b.tok0;
             });
+            for (size_t i = 1; i < segs[f].size(); ++i) {
+                const Seg &a = segs[f][i - 1], &b = segs[f][i];
+                if (a.data == b.data && b.tok0 < a.tok0 + a.T)
+                    p.reuse = 1;
+            }
+        }
         st = place_segments(ds, p, f, segs[f], static_cast<hipStream_t>(stream));
         if (st != KDN_OK)
             return st;
@@ -1297,6 +1321,7 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
         return st;
     p.rot = spec.rot;
     p.pairing = spec.pairing;
+    p.reuse = 0;
     std::vector<int32_t> rows((size_t)n_chunks);
     st = rope_rows(ds, spec, offsets, n_chunks, rows.data(), &p.rope);
     if (st != KDN_OK)

@@ -453,3 +453,45 @@ def test_patch_rows_matches_oracle(shape):
     O.patch_rows(rows2[:, :, 1:], tok2[1:], hc, bt)
     kdn.kdn_patch_rows(to_dev_bf16(rows2), torch.from_numpy(tok2).cuda(), dc, dev_table(bt))
     assert_cache_equal(dc, hc)
+
+
+# ------------------------------------------------------------------ HIP graph capture
+def test_store_and_compose_replay_inside_a_hip_graph():
+    """With the cos/sin rows resident, store / load / compose enqueue kernels only, so a
+    captured sequence can be replayed: every replay is checked against the oracle with
+    fresh source data, with eager work and synchronisation between the replays."""
+    L, nb, bs, H, D = 2, 48, 16, 2, 128
+    a, b, c = synth.disjoint_block_tables(91, nb, [6, 6, 12])
+    offsets = [0, 96]
+    base = 500000.0
+    hc = host_cache(92, L, nb, bs, H, D)
+    dc = dev_cache(hc)
+    ta, tb, tc = dev_table(a), dev_table(b), dev_table(c)
+    out1 = kdn.alloc_chunk(dc, 96, INT8)
+    out2 = kdn.alloc_chunk(dc, 96, INT4)
+    kdn.kdn_rope_prepare(base, D, offsets)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        kdn.kdn_store_chunk(dc, ta, 0, 96, out1)            # warm-up outside the capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            kdn.kdn_store_chunk(dc, ta, 0, 96, out1)
+            kdn.kdn_store_chunk(dc, tb, 0, 96, out2)
+            kdn.kdn_compose([out1, out2], offsets, dc, tc, base)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        fresh = host_cache(100 + rep, L, nb, bs, H, D)
+        dc.k.copy_(to_dev_bf16(fresh.k))
+        dc.v.copy_(to_dev_bf16(fresh.v))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        h1 = O.store(fresh, a, 0, 96, INT8)
+        h2 = O.store(fresh, b, 0, 96, INT4)
+        O.compose([h1, h2], offsets, fresh, c, base)
+        assert_chunk_equal(out1, h1)
+        assert_chunk_equal(out2, h2)
+        assert_cache_equal(dc, fresh)
+        _ = (dc.k.float().sum() + dc.v.float().sum()).item()   # unrelated eager work between replays

@@ -171,6 +171,15 @@ kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_tab
                            int32_t table_len, int32_t token_start, int32_t num_tokens,
                            kdn_chunk *out, void *stream);
 
+/* Store of a token list: row t of the chunk holds request token tokens_dev[t] ([device]
+ * int32, num_tokens entries, each in [0, table_len*block_size); an entry outside is
+ * clamped into that range).  The gather a token-dropping compressor needs: only the
+ * tokens it keeps are stored (Sec. 3.2, "KV-cache delivery").  Otherwise as
+ * kdn_store_chunk. */
+kdn_status kdn_store_tokens(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                            int32_t table_len, const int32_t *tokens_dev, int32_t num_tokens,
+                            kdn_chunk *out, void *stream);
+
 /* Load (Sec. 3.2, interface (ii); decompression on the GPU, Sec. 3.1).  Writes the
  * chunk view's tokens to request tokens [dest_token_start, dest_token_start +
  * chunk->num_tokens) of the paged cache.  No rotation.  Slots and blocks outside

@@ -302,6 +302,42 @@ int kdno_store(const kdno_cache *c, const int32_t *bt, int32_t table_len,
     return 0;
 }
 
+/* Store of a token list: row t of the chunk holds request token tokens[t] (the gather
+ * a token-dropping compressor needs, Sec. 3.2 "KV-cache delivery": only the tokens it
+ * keeps are stored).  Same per-row rules as kdno_store. */
+int kdno_store_tokens(const kdno_cache *c, const int32_t *bt, int32_t table_len,
+                      const int32_t *tokens, int32_t n, int32_t fmt, void *out,
+                      int32_t l0, int32_t l1)
+{
+    const int32_t H = c->H, D = c->D;
+    if (fmt == KDNO_FMT_INT4_GROUP32 && D % KDNO_GROUP != 0)
+        return -1;
+    for (int32_t t = 0; t < n; ++t)
+        if (tokens[t] < 0 || tokens[t] >= (int64_t)table_len * c->bs)
+            return -1;
+    int64_t n_rows = (int64_t)c->L * 2 * n * H;
+    for (int32_t l = l0; l < l1; ++l)
+        for (int32_t side = 0; side < 2; ++side)
+            for (int32_t t = 0; t < n; ++t) {
+                int32_t block = bt[tokens[t] / c->bs], slot = tokens[t] % c->bs;
+                if (block < 0 || block >= c->nb)
+                    return -1;
+                for (int32_t h = 0; h < H; ++h) {
+                    const uint16_t *src = cache_row(c, l, side, block, slot, h);
+                    int64_t r = row_index(l, side, n, t, H, h);
+                    if (fmt == KDNO_FMT_RAW_BF16)
+                        memcpy((uint16_t *)out + r * D, src, (size_t)D * 2);
+                    else if (fmt == KDNO_FMT_INT4_GROUP32)
+                        kdno_quantise_row_int4(src, D, (uint8_t *)out + r * (D / 2),
+                                               (float *)((char *)out + n_rows * (D / 2)) + r * (D / KDNO_GROUP));
+                    else
+                        kdno_quantise_row(src, D, (int8_t *)out + r * D,
+                                          (float *)((char *)out + n_rows * D) + r);
+                }
+            }
+    return 0;
+}
+
 /* Place tokens [tok_start, tok_start+T) of a stored chunk (parent length Tp)
  * at request tokens [dest, dest+T), with RoPE offset d applied to K rows.
  * READING: d == 0 skips the rotation altogether (it is not a multiply by

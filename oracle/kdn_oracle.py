@@ -96,6 +96,9 @@ def lib():
                                             C.POINTER(_Cache), C.c_void_p, C.c_int32, C.c_int32,
                                             C.c_double, C.c_void_p, C.c_int32, C.c_int32,
                                             C.c_int32, C.c_int32]
+            L.kdno_store_tokens.restype = C.c_int
+            L.kdno_store_tokens.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_int32, C.c_void_p,
+                                            C.c_int32, C.c_int32, C.c_void_p, C.c_int32, C.c_int32]
             L.kdno_patch_rows.restype = C.c_int
             L.kdno_patch_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(_Cache),
                                           C.c_void_p, C.c_int32]
@@ -328,3 +331,17 @@ def patch_rows(rows: np.ndarray, tokens, cache: PagedCache, block_table) -> None
     rc = lib().kdno_patch_rows(_ptr(rows), _ptr(tok), tok.size, C.byref(d), _ptr(bt), bt.size)
     if rc:
         raise ValueError("kdno_patch_rows: token or block id out of range")
+
+
+def store_tokens(cache: PagedCache, block_table, tokens, fmt: int) -> Chunk:
+    """Chunk whose row t holds request token tokens[t]."""
+    bt = _bt(block_table)
+    tok = np.ascontiguousarray(tokens, dtype=np.int32)
+    out = Chunk(np.zeros(chunk_bytes(cache.L, cache.H, cache.D, tok.size, fmt), dtype=np.uint8),
+                fmt, cache.L, cache.H, cache.D, int(tok.size))
+    d = cache.desc()
+    rc = lib().kdno_store_tokens(C.byref(d), _ptr(bt), bt.size, _ptr(tok), tok.size, fmt,
+                                 _ptr(out.data), 0, cache.L)
+    if rc:
+        raise ValueError("kdno_store_tokens: token or block id out of range")
+    return out

@@ -73,6 +73,8 @@ struct StoreP {
     const int32_t *bt;
     uint8_t *out;
     int32_t t0, T;
+    const int32_t *tokens; // token-list store: row t holds request token tokens[t]; else NULL
+    int32_t limit;         // request tokens the block table covers (list entries are clamped to it)
 };
 
 struct PlaceP {
@@ -183,10 +185,12 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     const int tok_hi = min(p.t0 + p.T, (gi + 1) * G);
     if (tok_lo >= tok_hi)
         return;
-    const int blk = p.bt[tok_lo / bs];
-    const int slot0 = tok_lo % bs;
-    const uint16_t *tile = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(ls >> 1) * p.c.layer_stride
-                           + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
+    // a token list (strided instantiation only) resolves every row's token by itself
+    const bool listed = !DENSE && p.tokens != nullptr;
+    const uint16_t *plane = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(ls >> 1) * p.c.layer_stride;
+    const int blk = listed ? 0 : p.bt[tok_lo / bs];
+    const int slot0 = listed ? 0 : tok_lo % bs;
+    const uint16_t *tile = plane + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
     const int64_t row_base = ((int64_t)ls * p.T + (tok_lo - p.t0)) * H;
     const int n_items = ((tok_hi - tok_lo) * H) << LOGP;
     const int64_t total_rows = (int64_t)p.c.L * 2 * p.T * H;
@@ -212,7 +216,13 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
                     src = tile + (uint32_t)(r * D + sub * 8);
                 } else {
                     const int tok = r / H, h = r - tok * H;
-                    src = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride + sub * 8;
+                    if (listed) {
+                        const int t = min(max(p.tokens[tok_lo + tok], 0), p.limit - 1);
+                        src = plane + (int64_t)p.bt[t / bs] * p.c.block_stride + (int64_t)(t % bs) * p.c.token_stride
+                              + (int64_t)h * p.c.head_stride + sub * 8;
+                    } else {
+                        src = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride + sub * 8;
+                    }
                 }
                 w[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
             }
@@ -825,7 +835,7 @@ kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t *offse
 template <int DT, int FMT, int P>
 void launch_store(const StoreP &p, dim3 grid, hipStream_t st)
 {
-    if (p.c.dense)
+    if (p.c.dense && !p.tokens)
         hipLaunchKernelGGL((k_store<DT, FMT, P, true>), grid, dim3(kThreads), 0, st, p);
     else
         hipLaunchKernelGGL((k_store<DT, FMT, P, false>), grid, dim3(kThreads), 0, st, p);
@@ -1126,9 +1136,9 @@ kdn_status kdn_chunk_slice(const kdn_chunk *chunk, int32_t token_start, int32_t 
     return KDN_OK;
 }
 
-kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_table_dev,
-                           int32_t table_len, int32_t token_start, int32_t num_tokens,
-                           kdn_chunk *out, void *stream)
+static kdn_status store_impl(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                             int32_t table_len, int32_t token_start, int32_t num_tokens,
+                             const int32_t *tokens_dev, kdn_chunk *out, void *stream)
 {
     kdn_status st = check_cache(cache);
     if (st != KDN_OK)
@@ -1141,7 +1151,8 @@ kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_tab
         return KDN_EUNSUPPORTED;
     if (!aligned16(out->data))
         return KDN_EALIGN;
-    if ((int64_t)token_start + num_tokens > (int64_t)table_len * cache->block_size)
+    const int64_t limit = (int64_t)table_len * cache->block_size;
+    if (!tokens_dev && (int64_t)token_start + num_tokens > limit)
         return KDN_ERANGE;
     const uint64_t need = kdn_chunk_bytes(cache->num_layers, cache->num_kv_heads, cache->head_dim,
                                           num_tokens, out->fmt);
@@ -1153,6 +1164,10 @@ kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_tab
     p.out = static_cast<uint8_t *>(out->data);
     p.t0 = token_start;
     p.T = num_tokens;
+    p.tokens = tokens_dev;
+    p.limit = (int32_t)std::min<int64_t>(limit, 0x7fffffff);
+    if (tokens_dev)
+        p.c.G = 16; // list entries need no block alignment
     const int64_t groups = groups_spanned(token_start, num_tokens, p.c.G);
     if (groups * 2 * p.c.L > 0x7fffffff / kThreads)
         return KDN_ESIZE;
@@ -1174,6 +1189,22 @@ kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_tab
     out->token_start = 0;
     out->num_tokens = num_tokens;
     return KDN_OK;
+}
+
+kdn_status kdn_store_chunk(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                           int32_t table_len, int32_t token_start, int32_t num_tokens,
+                           kdn_chunk *out, void *stream)
+{
+    return store_impl(cache, block_table_dev, table_len, token_start, num_tokens, nullptr, out, stream);
+}
+
+kdn_status kdn_store_tokens(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                            int32_t table_len, const int32_t *tokens_dev, int32_t num_tokens,
+                            kdn_chunk *out, void *stream)
+{
+    if (!tokens_dev)
+        return KDN_EINVAL;
+    return store_impl(cache, block_table_dev, table_len, 0, num_tokens, tokens_dev, out, stream);
 }
 
 kdn_status kdn_load_chunk(const kdn_chunk *chunk, const kdn_cache_desc *cache,

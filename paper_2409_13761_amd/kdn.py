@@ -83,6 +83,8 @@ def lib() -> C.CDLL:
         L.kdn_chunk_slice.argtypes = [C.POINTER(ChunkDesc), i32, i32, C.POINTER(ChunkDesc)]
         L.kdn_store_chunk.restype = C.c_int
         L.kdn_store_chunk.argtypes = [C.POINTER(CacheDesc), vp, i32, i32, i32, C.POINTER(ChunkDesc), vp]
+        L.kdn_store_tokens.restype = C.c_int
+        L.kdn_store_tokens.argtypes = [C.POINTER(CacheDesc), vp, i32, vp, i32, C.POINTER(ChunkDesc), vp]
         L.kdn_load_chunk.restype = C.c_int
         L.kdn_load_chunk.argtypes = [C.POINTER(ChunkDesc), C.POINTER(CacheDesc), vp, i32, i32, vp]
         L.kdn_compose.restype = C.c_int
@@ -137,7 +139,7 @@ def lib() -> C.CDLL:
     return _lib
 
 
-EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk",
+EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk", "kdn_store_tokens",
            "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_rope",
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host",
            "kdn_staging_bytes", "kdn_rope_prepare",
@@ -277,6 +279,17 @@ def kdn_store_chunk(cache: PagedCache, block_table: torch.Tensor, token_start: i
     _check(lib().kdn_store_chunk(C.byref(cd), block_table.data_ptr(), block_table.numel(),
                                  token_start, num_tokens, C.byref(out.desc), _stream(stream)),
            "kdn_store_chunk")
+    return out
+
+
+def kdn_store_tokens(cache: PagedCache, block_table: torch.Tensor, tokens: torch.Tensor,
+                     out: Chunk, stream=None) -> Chunk:
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous()
+    assert tokens.dtype == torch.int32 and tokens.is_contiguous() and tokens.is_cuda
+    cd = cache.desc()
+    _check(lib().kdn_store_tokens(C.byref(cd), block_table.data_ptr(), block_table.numel(),
+                                  tokens.data_ptr(), tokens.numel(), C.byref(out.desc), _stream(stream)),
+           "kdn_store_tokens")
     return out
 
 

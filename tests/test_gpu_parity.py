@@ -495,3 +495,29 @@ def test_store_and_compose_replay_inside_a_hip_graph():
         assert_chunk_equal(out2, h2)
         assert_cache_equal(dc, fresh)
         _ = (dc.k.float().sum() + dc.v.float().sum()).item()   # unrelated eager work between replays
+
+
+# ------------------------------------------------------------------ token-list store
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("shape", [(2, 24, 16, 4, 64), (3, 40, 16, 8, 128), (1, 30, 8, 3, 96), (1, 64, 1, 2, 32)])
+def test_store_tokens_matches_oracle(fmt, shape):
+    L, nb, bs, H, D = shape
+    _say("store_tokens fmt=%d shape=%s" % (fmt, shape))
+    hc = host_cache(95 + D, L, nb, bs, H, D)
+    n_tab = min(nb - 2, 14)
+    bt = synth.disjoint_block_tables(95, nb, [n_tab])[0]
+    cap = n_tab * bs
+    tokens = np.sort(synth.permutation(96, cap)[:max(1, (cap * 2) // 3)]).astype(np.int32)   # a kept subset
+    want = O.store_tokens(hc, bt, tokens, fmt)
+    dc = dev_cache(hc)
+    out = kdn.alloc_chunk(dc, len(tokens), fmt)
+    out.data.fill_(0xCD)
+    kdn.kdn_store_tokens(dc, dev_table(bt), torch.from_numpy(tokens).cuda(), out)
+    assert_chunk_equal(out, want)
+    # the thinned chunk composes like any other
+    dst_bt = synth.disjoint_block_tables(97, nb, [n_tab])[0]
+    hd = host_cache(98, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose([want], [11], hd, dst_bt, 10000.0)
+    kdn.kdn_compose([out], [11], dd, dev_table(dst_bt), 10000.0)
+    assert_cache_equal(dd, hd)

@@ -664,3 +664,31 @@ def test_patch_rows_overwrites_exactly_the_named_tokens(oracle):
     assert np.array_equal(cache.v[:, ~touched], before.v[:, ~touched])
     with pytest.raises(ValueError):
         oracle.patch_rows(rows, np.array([3, 0, 17, 24, 9]), cache, bt)     # token 24 is past the table
+
+
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+def test_store_of_a_token_list(oracle, fmt):
+    """Row t of the chunk is request token tokens[t]: raw rows by brute force over a
+    tagged cache, quantised rows equal to the quantiser applied to those rows."""
+    L, nb, bs, H, D = 2, 40, 4, 3, 32
+    cache = _tagged_cache(oracle, L, nb, bs, H, D, False) if fmt == RAW else make_cache(oracle, 50, L, nb, bs, H, D)
+    bt = synth.disjoint_block_tables(50, nb, [9])[0]
+    tokens = np.array([35, 0, 7, 8, 22, 21, 3], dtype=np.int32)
+    ch = oracle.store_tokens(cache, bt, tokens, fmt)
+    assert ch.Tp == len(tokens)
+    for l in range(L):
+        for side, base in enumerate((cache.k, cache.v)):
+            for i, tok in enumerate(tokens):
+                row = base[l, int(bt[tok // bs]), tok % bs]            # [H][D]
+                for h in range(H):
+                    if fmt == RAW:
+                        assert np.array_equal(ch.raw()[l, side, i, h], row[h])
+                    elif fmt == INT8:
+                        q, s_ = oracle.quantise_row(row[h])
+                        assert np.array_equal(ch.codes()[l, side, i, h], q) and ch.scales()[l, side, i, h] == s_
+                    else:
+                        pk, s_ = oracle.quantise_row_int4(row[h])
+                        assert np.array_equal(ch.packed4()[l, side, i, h], pk)
+                        assert np.array_equal(ch.scales4()[l, side, i, h], s_)
+    with pytest.raises(ValueError):
+        oracle.store_tokens(cache, bt, np.array([1, 36]), fmt)          # 36 is past the table

@@ -44,14 +44,22 @@ FMT_IDS = {"raw": 0, "int8": 1, "int4": 2}
 # HBM bytes per k_place launch of the default workload from the FETCH_SIZE / WRITE_SIZE
 # counter runs summarised under profiles/, valid only for the kernel source they were
 # taken with.
-COUNTER_TRAFFIC = {"source_sha256_16": "4c7524f03ce35b12", "k_place_bytes_per_launch": 816471243}
+COUNTER_TRAFFIC = {"source_sha256_16": "6d384f7d8cd5d2b6", "k_place_bytes_per_launch": 816462875}
+
+
+def kernel_source_fingerprint():
+    """sha256 over the library's device and planner sources (csrc/kdn*.h, csrc/kdn.hip)."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2409_13761_amd", "csrc")
+    h = hashlib.sha256()
+    for name in ("kdn_kernels.h", "kdn_planner.h", "kdn.hip"):
+        h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:16]
 
 
 def counter_traffic():
-    import hashlib
-    src = os.path.join(ROOT, "paper_2409_13761_amd", "csrc", "kdn.hip")
-    sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
-    return COUNTER_TRAFFIC["k_place_bytes_per_launch"] if sha == COUNTER_TRAFFIC["source_sha256_16"] else None
+    same = kernel_source_fingerprint() == COUNTER_TRAFFIC["source_sha256_16"]
+    return COUNTER_TRAFFIC["k_place_bytes_per_launch"] if same else None
 
 
 def fill_normal(t, gen):

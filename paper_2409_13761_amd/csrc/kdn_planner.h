@@ -1,0 +1,496 @@
+// Host planner of the KDN library: argument checks, per-device tables (cos/sin rows,
+// segment tables, copy stream), kernel dispatch and the compose plan.  Included by
+// kdn.hip only.
+#ifndef KDN_PLANNER_H
+#define KDN_PLANNER_H
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <unordered_map>
+#include <vector>
+
+#include "kdn_kernels.h"
+
+namespace kdn_impl {
+
+// Resolved RoPE variant of one call: frequencies either derived from `base` or given.
+struct RopeSpec {
+    double base = 0.0;
+    std::vector<double> freq; // rot/2 explicit frequencies, empty: base^(-2j/rot)
+    int32_t rot = 0;
+    int32_t pairing = KDN_ROPE_HALF_SPLIT;
+};
+
+// cos/sin rows of one (frequencies, rot) pair, one row per offset seen so far
+struct RopeTable {
+    f32x2 *dev = nullptr;
+    double base = 0.0;
+    std::vector<double> freq;
+    int32_t rot = 0;
+    std::unordered_map<int32_t, int32_t> row_of;
+};
+
+struct DeviceState {
+    std::vector<RopeTable> rope;
+    uint8_t *seg_dev = nullptr;                   // kSegSlots * kSegSlotBytes
+    uint8_t *seg_host = nullptr;                  // pinned mirror
+    hipEvent_t seg_done[kSegSlots] = {};
+    bool seg_used[kSegSlots] = {};
+    int next_slot = 0;
+    // streaming of host-resident chunks: a copy stream and, per half of the caller's
+    // staging buffer, "filled" and "drained" events
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t filled[2] = {};
+    hipEvent_t drained[2] = {};
+    bool drained_valid[2] = {};
+};
+
+std::mutex g_mu;
+std::unordered_map<int, DeviceState> g_dev;
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+kdn_status check_shape(int32_t L, int32_t H, int32_t D)
+{
+    if (L <= 0 || H <= 0 || D <= 0 || L > 32767)
+        return KDN_EINVAL;
+    if (D % 16 != 0 || D > kMaxHeadDim)
+        return KDN_EUNSUPPORTED;
+    return KDN_OK;
+}
+
+kdn_status check_cache(const kdn_cache_desc *c)
+{
+    if (!c || !c->k_base || !c->v_base)
+        return KDN_EINVAL;
+    kdn_status st = check_shape(c->num_layers, c->num_kv_heads, c->head_dim);
+    if (st != KDN_OK)
+        return st;
+    if (c->block_size <= 0 || c->num_blocks <= 0)
+        return KDN_EINVAL;
+    if (c->head_stride < c->head_dim || c->token_stride < 0 || c->block_stride < 0
+        || c->layer_stride < 0)
+        return KDN_EINVAL;
+    if (!aligned16(c->k_base) || !aligned16(c->v_base) || c->head_stride % 8 || c->token_stride % 8
+        || c->block_stride % 8 || c->layer_stride % 8)
+        return KDN_EALIGN;
+    return KDN_OK;
+}
+
+bool known_format(int32_t fmt)
+{
+    return fmt == KDN_FMT_RAW_BF16 || fmt == KDN_FMT_INT8_ROWSCALE || fmt == KDN_FMT_INT4_GROUP32;
+}
+
+kdn_status check_chunk(const kdn_chunk *ch, const kdn_cache_desc *c)
+{
+    if (!ch || !ch->data)
+        return KDN_EINVAL;
+    if (!known_format(ch->fmt))
+        return KDN_EINVAL;
+    if (ch->fmt == KDN_FMT_INT4_GROUP32 && ch->head_dim % 32 != 0)
+        return KDN_EUNSUPPORTED;
+    if (ch->num_layers != c->num_layers || ch->num_kv_heads != c->num_kv_heads
+        || ch->head_dim != c->head_dim)
+        return KDN_EINVAL;
+    if (!aligned16(ch->data))
+        return KDN_EALIGN;
+    if (ch->parent_tokens <= 0 || ch->num_tokens <= 0 || ch->token_start < 0)
+        return KDN_EINVAL;
+    if ((int64_t)ch->token_start + ch->num_tokens > ch->parent_tokens)
+        return KDN_ERANGE;
+    if (ch->bytes < kdn_chunk_bytes(ch->num_layers, ch->num_kv_heads, ch->head_dim,
+                                    ch->parent_tokens, ch->fmt))
+        return KDN_ESIZE;
+    return KDN_OK;
+}
+
+CacheP make_cache_p(const kdn_cache_desc *c)
+{
+    CacheP p;
+    p.k = static_cast<uint16_t *>(c->k_base);
+    p.v = static_cast<uint16_t *>(c->v_base);
+    p.layer_stride = c->layer_stride;
+    p.block_stride = c->block_stride;
+    p.token_stride = c->token_stride;
+    p.head_stride = c->head_stride;
+    p.L = c->num_layers;
+    p.H = c->num_kv_heads;
+    p.D = c->head_dim;
+    p.bs = c->block_size;
+    // token group: a whole block when it is small, else 16-token pieces of it
+    p.G = (c->block_size > 16 && c->block_size % 16 == 0) ? 16 : c->block_size;
+    p.dense = (c->head_stride == c->head_dim
+               && c->token_stride == (int64_t)c->num_kv_heads * c->head_dim);
+    return p;
+}
+
+// number of token groups touched by tokens [s, s+t)
+int64_t groups_spanned(int64_t s, int64_t t, int32_t G) { return (s + t - 1) / G - s / G + 1; }
+
+kdn_status hip_status(hipError_t e) { return e == hipSuccess ? KDN_OK : KDN_EDEVICE; }
+
+DeviceState *device_state(int *dev_out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess)
+        return nullptr;
+    if (dev_out)
+        *dev_out = dev;
+    return &g_dev[dev];
+}
+
+// Validates a caller's RoPE variant for head_dim D.  NULL selects the default
+// (all of D rotary, half-split pairs, frequencies from `base`).
+kdn_status resolve_spec(const kdn_rope_spec *in, double base, int32_t D, RopeSpec &out)
+{
+    out = RopeSpec();
+    out.base = in ? in->base : base;
+    out.rot = in && in->rot_dim ? in->rot_dim : D;
+    out.pairing = in ? in->pairing : (int32_t)KDN_ROPE_HALF_SPLIT;
+    if (out.pairing != KDN_ROPE_HALF_SPLIT && out.pairing != KDN_ROPE_INTERLEAVED)
+        return KDN_EINVAL;
+    if (out.rot <= 0 || out.rot > D)
+        return KDN_EINVAL;
+    if (out.rot % 16 != 0) // a lane rotates 8 pairs
+        return KDN_EUNSUPPORTED;
+    if (in && in->inv_freq) {
+        out.freq.assign(in->inv_freq, in->inv_freq + out.rot / 2);
+        for (double f : out.freq)
+            if (!std::isfinite(f))
+                return KDN_EINVAL;
+    }
+    return KDN_OK;
+}
+
+// Returns the cos/sin table of the variant and fills rows[i] for offsets[i] (-1 for a
+// zero offset).  New rows are computed in double and uploaded before returning.
+kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t *offsets, int32_t n,
+                     int32_t *rows, const f32x2 **table)
+{
+    *table = nullptr;
+    bool any = false;
+    for (int32_t i = 0; i < n; ++i)
+        any = any || offsets[i] != 0;
+    if (!any) {
+        for (int32_t i = 0; i < n; ++i)
+            rows[i] = -1;
+        return KDN_OK;
+    }
+    if (spec.freq.empty() && (!(spec.base > 0.0) || !std::isfinite(spec.base)))
+        return KDN_EINVAL;
+    {
+        std::unordered_map<int32_t, int32_t> distinct;
+        for (int32_t i = 0; i < n; ++i)
+            if (offsets[i] != 0)
+                distinct.emplace(offsets[i], 0);
+        if ((int32_t)distinct.size() > kRopeRowsCap)
+            return KDN_ESIZE;
+    }
+    size_t ti = 0;
+    for (; ti < ds->rope.size(); ++ti) {
+        const RopeTable &t = ds->rope[ti];
+        if (t.rot == spec.rot && t.freq == spec.freq && (!spec.freq.empty() || t.base == spec.base))
+            break;
+    }
+    if (ti == ds->rope.size()) {
+        RopeTable t;
+        t.base = spec.base;
+        t.freq = spec.freq;
+        t.rot = spec.rot;
+        ds->rope.push_back(std::move(t));
+    }
+    RopeTable &rt = ds->rope[ti];
+    const int32_t half = spec.rot / 2;
+    if (!rt.dev
+        && hipMalloc(reinterpret_cast<void **>(&rt.dev), (size_t)kRopeRowsCap * half * sizeof(f32x2))
+               != hipSuccess)
+        return KDN_EDEVICE;
+    std::vector<float> row((size_t)half * 2);
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t d = offsets[i];
+        if (d == 0) {
+            rows[i] = -1;
+            continue;
+        }
+        auto it = rt.row_of.find(d);
+        if (it != rt.row_of.end()) {
+            rows[i] = it->second;
+            continue;
+        }
+        if ((int32_t)rt.row_of.size() >= kRopeRowsCap) {
+            // table full: wait until nothing can still read it, then start over
+            if (hipDeviceSynchronize() != hipSuccess)
+                return KDN_EDEVICE;
+            rt.row_of.clear();
+            for (int32_t k = 0; k < i; ++k) // rows handed out earlier in this call are gone
+                if (offsets[k] != 0)
+                    rows[k] = -2;
+        }
+        for (int32_t j = 0; j < half; ++j) {
+            const double theta = spec.freq.empty() ? std::pow(spec.base, -(double)(2 * j) / (double)spec.rot)
+                                                   : spec.freq[(size_t)j];
+            const double phi = (double)d * theta;
+            row[2 * j] = (float)std::cos(phi);
+            row[2 * j + 1] = (float)std::sin(phi);
+        }
+        const int32_t r = (int32_t)rt.row_of.size();
+        if (hipMemcpy(rt.dev + (size_t)r * half, row.data(), row.size() * sizeof(float),
+                      hipMemcpyHostToDevice)
+            != hipSuccess)
+            return KDN_EDEVICE;
+        rt.row_of.emplace(d, r);
+        rows[i] = r;
+    }
+    for (int32_t i = 0; i < n; ++i)
+        if (rows[i] == -2) // only after a table reset inside this call
+            return rope_rows(ds, spec, offsets, n, rows, table);
+    *table = rt.dev;
+    return KDN_OK;
+}
+
+template <int DT, int FMT, int P>
+void launch_store(const StoreP &p, dim3 grid, hipStream_t st)
+{
+    if (p.c.dense && !p.tokens)
+        hipLaunchKernelGGL((k_store<DT, FMT, P, true>), grid, dim3(kThreads), 0, st, p);
+    else
+        hipLaunchKernelGGL((k_store<DT, FMT, P, false>), grid, dim3(kThreads), 0, st, p);
+}
+
+template <int FMT>
+void launch_store_d(const StoreP &p, dim3 grid, hipStream_t st)
+{
+    switch (p.c.D) {
+    case 64: launch_store<64, FMT, 8>(p, grid, st); return;
+    case 128: launch_store<128, FMT, 16>(p, grid, st); return;
+    default: break;
+    }
+    switch (log2_ceil(p.c.D >> 3)) { // lane group: D/8 lanes rounded up to a power of two
+    case 1: launch_store<0, FMT, 2>(p, grid, st); break;
+    case 2: launch_store<0, FMT, 4>(p, grid, st); break;
+    case 3: launch_store<0, FMT, 8>(p, grid, st); break;
+    case 4: launch_store<0, FMT, 16>(p, grid, st); break;
+    case 5: launch_store<0, FMT, 32>(p, grid, st); break;
+    default: launch_store<0, FMT, 64>(p, grid, st); break;
+    }
+}
+
+template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE>
+void launch_place_v(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
+                    hipStream_t st)
+{
+    if (segs_dev) {
+        SegsDevice sd{segs_dev};
+        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, REUSE, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+    } else {
+        SegsInline si;
+        std::memset(&si, 0, sizeof si);
+        std::memcpy(si.s, segs, (size_t)n * sizeof(Seg));
+        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, REUSE, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+    }
+}
+
+template <int DT, int FMT>
+void launch_place(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
+                  hipStream_t st)
+{
+    const bool var = p.rot != p.c.D || p.pairing != KDN_ROPE_HALF_SPLIT;
+    // the cache-friendly load flavour exists for the common serving case only (dense
+    // layout, default RoPE variant); elsewhere shared rows are streamed like any other
+    if (p.c.dense) {
+        if (var)
+            launch_place_v<DT, FMT, true, true, false>(p, segs, n, segs_dev, grid, st);
+        else if (p.reuse)
+            launch_place_v<DT, FMT, true, false, true>(p, segs, n, segs_dev, grid, st);
+        else
+            launch_place_v<DT, FMT, true, false, false>(p, segs, n, segs_dev, grid, st);
+    } else {
+        if (var)
+            launch_place_v<DT, FMT, false, true, false>(p, segs, n, segs_dev, grid, st);
+        else
+            launch_place_v<DT, FMT, false, false, false>(p, segs, n, segs_dev, grid, st);
+    }
+}
+
+template <int FMT>
+void launch_place_d(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
+                    hipStream_t st)
+{
+    switch (p.c.D) {
+    case 64: launch_place<64, FMT>(p, segs, n, segs_dev, grid, st); break;
+    case 128: launch_place<128, FMT>(p, segs, n, segs_dev, grid, st); break;
+    default: launch_place<0, FMT>(p, segs, n, segs_dev, grid, st); break;
+    }
+}
+
+// Enqueue the placement of `segs` (all of one format).  Up to kMaxInlineSegs travel
+// in the kernel arguments; more go through a ring of device tables.
+kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const std::vector<Seg> &segs,
+                          hipStream_t st)
+{
+    if (segs.empty())
+        return KDN_OK;
+    if (segs.size() > 65535 || segs.size() * sizeof(Seg) > kSegSlotBytes)
+        return KDN_ESIZE;
+    int64_t max_groups = 0;
+    for (const Seg &s : segs)
+        max_groups = std::max(max_groups, groups_spanned(s.S, s.T, p.c.G));
+    if (max_groups * 2 * p.c.L > 0x7fffffff / kThreads)
+        return KDN_ESIZE;
+    dim3 grid((unsigned)(max_groups * 2 * p.c.L), (unsigned)segs.size(), 1);
+
+    const Seg *segs_dev = nullptr;
+    int slot = -1;
+    if ((int)segs.size() > kMaxInlineSegs) {
+        if (!ds->seg_dev) {
+            if (hipMalloc(reinterpret_cast<void **>(&ds->seg_dev), kSegSlots * kSegSlotBytes) != hipSuccess)
+                return KDN_EDEVICE;
+            if (hipHostMalloc(reinterpret_cast<void **>(&ds->seg_host), kSegSlots * kSegSlotBytes,
+                              hipHostMallocDefault)
+                != hipSuccess)
+                return KDN_EDEVICE;
+            for (int i = 0; i < kSegSlots; ++i)
+                if (hipEventCreateWithFlags(&ds->seg_done[i], hipEventDisableTiming) != hipSuccess)
+                    return KDN_EDEVICE;
+        }
+        slot = ds->next_slot;
+        ds->next_slot = (slot + 1) % kSegSlots;
+        if (ds->seg_used[slot] && hipEventSynchronize(ds->seg_done[slot]) != hipSuccess)
+            return KDN_EDEVICE;
+        uint8_t *h = ds->seg_host + (size_t)slot * kSegSlotBytes;
+        uint8_t *d = ds->seg_dev + (size_t)slot * kSegSlotBytes;
+        std::memcpy(h, segs.data(), segs.size() * sizeof(Seg));
+        if (hipMemcpyAsync(d, h, segs.size() * sizeof(Seg), hipMemcpyHostToDevice, st) != hipSuccess)
+            return KDN_EDEVICE;
+        segs_dev = reinterpret_cast<const Seg *>(d);
+    }
+    if (fmt == KDN_FMT_RAW_BF16)
+        launch_place_d<KDN_FMT_RAW_BF16>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
+    else if (fmt == KDN_FMT_INT8_ROWSCALE)
+        launch_place_d<KDN_FMT_INT8_ROWSCALE>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
+    else
+        launch_place_d<KDN_FMT_INT4_GROUP32>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
+    kdn_status rc = hip_status(hipGetLastError());
+    if (slot >= 0) {
+        if (hipEventRecord(ds->seg_done[slot], st) != hipSuccess)
+            return KDN_EDEVICE;
+        ds->seg_used[slot] = true;
+    }
+    return rc;
+}
+
+kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
+                        double rope_base, const kdn_rope_spec *variant, void *stream)
+{
+    if (!reqs || n_reqs <= 0)
+        return KDN_EINVAL;
+    kdn_status st = check_cache(cache);
+    if (st != KDN_OK)
+        return st;
+    RopeSpec spec;
+    st = resolve_spec(variant, rope_base, cache->head_dim, spec);
+    if (st != KDN_OK)
+        return st;
+    std::vector<int32_t> offs;
+    for (int32_t r = 0; r < n_reqs; ++r) {
+        const kdn_request &q = reqs[r];
+        if (!q.chunks || !q.offsets || q.n_chunks <= 0 || !q.block_table_dev || q.table_len <= 0
+            || q.dest_token_start < 0)
+            return KDN_EINVAL;
+        int64_t total = q.dest_token_start;
+        for (int32_t i = 0; i < q.n_chunks; ++i) {
+            st = check_chunk(&q.chunks[i], cache);
+            if (st != KDN_OK)
+                return st;
+            total += q.chunks[i].num_tokens;
+            offs.push_back(q.offsets[i]);
+        }
+        if (total > (int64_t)q.table_len * cache->block_size)
+            return KDN_ERANGE;
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *ds = device_state(nullptr);
+    if (!ds)
+        return KDN_EDEVICE;
+    PlaceP p;
+    p.c = make_cache_p(cache);
+    p.layer0 = 0;
+    p.rot = spec.rot;
+    p.pairing = spec.pairing;
+    std::vector<int32_t> rows(offs.size());
+    st = rope_rows(ds, spec, offs.data(), (int32_t)offs.size(), rows.data(), &p.rope);
+    if (st != KDN_OK)
+        return st;
+    std::vector<Seg> segs[3];
+    size_t k = 0;
+    for (int32_t r = 0; r < n_reqs; ++r) {
+        const kdn_request &q = reqs[r];
+        int32_t S = q.dest_token_start;
+        for (int32_t i = 0; i < q.n_chunks; ++i, ++k) {
+            const kdn_chunk &ch = q.chunks[i];
+            Seg s;
+            s.data = static_cast<const uint8_t *>(ch.data);
+            s.bt = q.block_table_dev;
+            s.Tp = ch.parent_tokens;
+            s.tok0 = ch.token_start;
+            s.T = ch.num_tokens;
+            s.S = S;
+            s.rope_row = rows[k];
+            s.pad = 0;
+            segs[ch.fmt].push_back(s);
+            S += ch.num_tokens;
+        }
+    }
+    for (int f = 0; f < 3; ++f) {
+        // Segments that read the same stored rows run back to back, so that a popular
+        // chunk is fetched from HBM once and from the last-level cache afterwards.
+        p.reuse = 0;
+        if (n_reqs > 1) {
+            std::stable_sort(segs[f].begin(), segs[f].end(), [](const Seg &a, const Seg &b) {
+                return a.data != b.data ? a.data < b.data : a.tok0 < b.tok0;
+            });
+            for (size_t i = 1; i < segs[f].size(); ++i) {
+                const Seg &a = segs[f][i - 1], &b = segs[f][i];
+                if (a.data == b.data && b.tok0 < a.tok0 + a.T)
+                    p.reuse = 1;
+            }
+        }
+        st = place_segments(ds, p, f, segs[f], static_cast<hipStream_t>(stream));
+        if (st != KDN_OK)
+            return st;
+    }
+    return KDN_OK;
+}
+
+// Views of the same host buffer are staged once: the token range [lo, hi) that the
+// views of one buffer span crosses the link as one copy per stage.
+struct HostParent {
+    const uint8_t *data;
+    int32_t fmt, L, H, D, Tp, lo, hi;
+};
+
+void plan_host_parents(const kdn_chunk *chunks, int32_t n, std::vector<HostParent> &parents,
+                       std::vector<int32_t> &parent_of)
+{
+    parents.clear();
+    parent_of.assign((size_t)n, 0);
+    for (int32_t i = 0; i < n; ++i) {
+        const kdn_chunk &ch = chunks[i];
+        size_t k = 0;
+        for (; k < parents.size(); ++k)
+            if (parents[k].data == ch.data && parents[k].fmt == ch.fmt && parents[k].Tp == ch.parent_tokens)
+                break;
+        if (k == parents.size())
+            parents.push_back({static_cast<const uint8_t *>(ch.data), ch.fmt, ch.num_layers, ch.num_kv_heads,
+                               ch.head_dim, ch.parent_tokens, ch.token_start, ch.token_start + ch.num_tokens});
+        parents[k].lo = std::min(parents[k].lo, ch.token_start);
+        parents[k].hi = std::max(parents[k].hi, ch.token_start + ch.num_tokens);
+        parent_of[(size_t)i] = (int32_t)k;
+    }
+}
+
+} // namespace kdn_impl
+#endif // KDN_PLANNER_H

@@ -521,3 +521,65 @@ def test_store_tokens_matches_oracle(fmt, shape):
     O.compose([want], [11], hd, dst_bt, 10000.0)
     kdn.kdn_compose([out], [11], dd, dev_table(dst_bt), 10000.0)
     assert_cache_equal(dd, hd)
+
+
+# ------------------------------------------------------------------ planner state under load
+def test_cos_sin_table_refills_after_it_overflows():
+    """More distinct offsets than the resident table holds: the table is drained and
+    refilled, and composes before and after still match the oracle."""
+    L, nb, bs, H, D = 1, 16, 16, 1, 32
+    src = host_cache(111, L, nb, bs, H, D)
+    a, b = synth.disjoint_block_tables(111, nb, [2, 4])
+    ch = O.store(src, a, 0, 32, INT8)
+    dch = chunk_to_dev(ch)
+    base = 12345.0                                 # a table of its own
+    for start in (1, 3000, 6000):                  # 9000 distinct offsets in all, capacity is 4096
+        kdn.kdn_rope_prepare(base, D, list(range(start, start + 3000)))
+        d = start + 1500
+        hd = host_cache(112, L, nb, bs, H, D)
+        dd = dev_cache(hd)
+        O.compose([ch, ch], [d, 7], hd, b, base)
+        kdn.kdn_compose([dch, dch], [d, 7], dd, dev_table(b), base)
+        assert_cache_equal(dd, hd)
+    with pytest.raises(kdn.KdnError) as e:          # more distinct offsets in ONE call than the table holds
+        kdn.kdn_rope_prepare(base, D, list(range(1, 5000)))
+    assert e.value.status == kdn.ESIZE
+
+
+def test_two_streams_and_two_host_threads():
+    """Independent composes issued from two host threads on two streams into disjoint
+    tables of one cache."""
+    import threading
+    L, nb, bs, H, D = 2, 96, 16, 2, 128
+    src = host_cache(121, L, nb, bs, H, D)
+    tabs = synth.disjoint_block_tables(121, nb, [6, 6, 20, 20])
+    c1, c2 = O.store(src, tabs[0], 0, 96, INT8), O.store(src, tabs[1], 0, 96, INT4)
+    d1, d2 = chunk_to_dev(c1), chunk_to_dev(c2)
+    hd = host_cache(122, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    bt = [dev_table(tabs[2]), dev_table(tabs[3])]
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    errors = []
+
+    def worker(i):
+        try:
+            with torch.cuda.stream(streams[i]):
+                for rep in range(20):
+                    kdn.kdn_compose([d1, d2, d1], [rep + 1, -(rep + 1), 100 * i], dd, bt[i], 500000.0,
+                                    stream=streams[i])
+                    kdn.kdn_load_chunk(d2, dd, bt[i], 220, stream=streams[i])
+        except Exception as exc:                    # surfaced in the main thread
+            errors.append(exc)
+
+    th = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in th:
+        t.start()
+    for t in th:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(2):
+        O.compose([c1, c2, c1], [20, -20, 100 * i], hd, tabs[2 + i], 500000.0)
+        O.load(c2, hd, tabs[2 + i], 220)
+    assert_cache_equal(dd, hd)

@@ -105,6 +105,28 @@ class Timed:
         return wall, ms
 
 
+def copy_ceiling(dev):
+    """A plain device copy as the box's own yardstick: 1 GiB read + 1 GiB written per
+    copy, over 3 rotating buffer pairs so that the last-level cache serves nothing."""
+    import torch
+    n = 1 << 29
+    bufs = [(torch.empty(n, dtype=torch.bfloat16, device=dev).normal_(),
+             torch.empty(n, dtype=torch.bfloat16, device=dev)) for _ in range(3)]
+    for a, b in bufs:
+        b.copy_(a)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 12
+    e0.record()
+    for i in range(reps):
+        a, b = bufs[i % 3]
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    return 2.0 * n * 2 / (ms * 1e-3) / 1e9
+
+
 def workload_8b(args, dev):
     import torch
     from paper_2409_13761_amd import kdn, synth
@@ -530,6 +552,12 @@ def main() -> int:
             "traffic": res["traffic"],
         },
     }
+    if args.workload == "8b":
+        ceiling = copy_ceiling(dev)
+        out["device_copy_ceiling"] = {
+            "GBps": ceiling, "what": "torch copy of 1 GiB bf16 buffers (1 GiB read + 1 GiB written), "
+                                     "3 rotating pairs, HIP events",
+            "frac_of_ceiling": {n: gbps[n] / ceiling for n in ms}}
     if "extra" in res:
         out["config"].update(res["extra"])
     if "cpu_baseline" in res:

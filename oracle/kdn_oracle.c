@@ -29,7 +29,7 @@
 #include <stdint.h>
 #include <string.h>
 
-enum { KDNO_FMT_RAW_BF16 = 0, KDNO_FMT_INT8_ROWSCALE = 1, KDNO_FMT_INT4_GROUP32 = 2 };
+enum { KDNO_FMT_RAW_BF16 = 0, KDNO_FMT_INT8_ROWSCALE = 1, KDNO_FMT_INT4_GROUP32 = 2, KDNO_FMT_FP8_ROWSCALE = 3 };
 enum { KDNO_GROUP = 32 };
 
 /* Engine paged KV memory (Sec. 3.2, "paged memory" of the serving engine).
@@ -82,6 +82,8 @@ void kdno_f32_to_bf16_array(const float *in, uint16_t *out, int64_t n)
  *                                   nibble, 2k+1 in the high nibble, two's
  *                                   complement), then
  *          fp32  [L][2][Tp][H][D/32] one scale per group of 32 elements.
+ *   fp8  : uint8 [L][2][Tp][H][D]   e4m3 codes, then fp32 [L][2][Tp][H] row scales
+ *                                   (the int8 layout with other codes).
  * Tokens stay sliceable: a view is (Tp, tok_start, T). */
 int64_t kdno_chunk_bytes(int32_t L, int32_t H, int32_t D, int32_t Tp, int32_t fmt)
 {
@@ -192,6 +194,76 @@ void kdno_dequantise_row_int4(const uint8_t *packed, const float *scales, int32_
     }
 }
 
+/* ---- fp8 (e4m3) with a row scale ------------------------------------------------
+ * READING: the 8-bit float with 4 exponent bits (bias 7), 3 mantissa bits, no
+ * infinities, all-ones = NaN, largest finite value 448, subnormals below 2^-6 in steps
+ * of 2^-9.  Conversion rounds to nearest, ties to the even code, and saturates at 448.
+ * Per row: amax < 2^-119 (448/amax would not be a finite fp32) gives scale 0 and codes
+ * 0; otherwise scale = amax/448, inv = 448/amax, code_j = e4m3(x_j * inv); the
+ * dequantised value is e4m3_value(code_j) * scale, one fp32 multiply. */
+uint8_t kdno_f32_to_e4m3(float f)
+{
+    uint8_t sign = signbit(f) ? 0x80 : 0;
+    float a = fabsf(f);
+    if (a != a)
+        return (uint8_t)(sign | 0x7f);
+    if (a >= 448.0f)
+        return (uint8_t)(sign | 0x7e);
+    if (a < 0x1p-6f) {                         /* subnormal range: multiples of 2^-9 */
+        int q = (int)rintf(a * 0x1p9f);        /* 0..8; 8 is the smallest normal's code */
+        return (uint8_t)(sign | q);
+    }
+    int e;
+    float m = frexpf(a, &e);                   /* a = m * 2^e, m in [0.5, 1) */
+    m *= 2.0f;
+    e -= 1;                                    /* a = m * 2^e, m in [1, 2) */
+    int q = (int)rintf((m - 1.0f) * 8.0f);     /* 0..8 */
+    if (q == 8) {
+        q = 0;
+        e += 1;
+    }
+    return (uint8_t)(sign | ((e + 7) << 3) | q);
+}
+
+float kdno_e4m3_to_f32(uint8_t c)
+{
+    int e = (c >> 3) & 0xf, q = c & 7;
+    float v;
+    if (e == 0xf && q == 7)
+        v = NAN;
+    else if (e == 0)
+        v = ldexpf((float)q, -9);
+    else
+        v = ldexpf(1.0f + (float)q / 8.0f, e - 7);
+    return (c & 0x80) ? -v : v;
+}
+
+void kdno_quantise_row_fp8(const uint16_t *x, int32_t D, uint8_t *q, float *scale)
+{
+    float amax = 0.0f;
+    for (int32_t j = 0; j < D; ++j) {
+        float a = fabsf(kdno_bf16_to_f32(x[j]));
+        if (a > amax)
+            amax = a;
+    }
+    if (amax < 0x1p-119f) {
+        *scale = 0.0f;
+        for (int32_t j = 0; j < D; ++j)
+            q[j] = 0;
+        return;
+    }
+    *scale = amax / 448.0f;
+    float inv = 448.0f / amax;
+    for (int32_t j = 0; j < D; ++j)
+        q[j] = kdno_f32_to_e4m3(kdno_bf16_to_f32(x[j]) * inv);
+}
+
+void kdno_dequantise_row_fp8(const uint8_t *q, float scale, int32_t D, float *y)
+{
+    for (int32_t j = 0; j < D; ++j)
+        y[j] = kdno_e4m3_to_f32(q[j]) * scale;
+}
+
 /* ---- RoPE shift -------------------------------------------------------------
  * READING (reuse of a chunk "at different positions", Sec. 3.2 blending): keys
  * carry rotary position embedding; moving a chunk by d positions multiplies
@@ -295,6 +367,8 @@ int kdno_store(const kdno_cache *c, const int32_t *bt, int32_t table_len,
                         memcpy(raw + r * D, src, (size_t)D * 2);
                     else if (fmt == KDNO_FMT_INT4_GROUP32)
                         kdno_quantise_row_int4(src, D, codes4 + r * (D / 2), scales4 + r * (D / KDNO_GROUP));
+                    else if (fmt == KDNO_FMT_FP8_ROWSCALE)
+                        kdno_quantise_row_fp8(src, D, (uint8_t *)codes + r * D, scales + r);
                     else
                         kdno_quantise_row(src, D, codes + r * D, scales + r);
                 }
@@ -330,6 +404,9 @@ int kdno_store_tokens(const kdno_cache *c, const int32_t *bt, int32_t table_len,
                     else if (fmt == KDNO_FMT_INT4_GROUP32)
                         kdno_quantise_row_int4(src, D, (uint8_t *)out + r * (D / 2),
                                                (float *)((char *)out + n_rows * (D / 2)) + r * (D / KDNO_GROUP));
+                    else if (fmt == KDNO_FMT_FP8_ROWSCALE)
+                        kdno_quantise_row_fp8(src, D, (uint8_t *)out + r * D,
+                                              (float *)((char *)out + n_rows * D) + r);
                     else
                         kdno_quantise_row(src, D, (int8_t *)out + r * D,
                                           (float *)((char *)out + n_rows * D) + r);
@@ -378,6 +455,8 @@ static int place(const void *data, int32_t fmt, int32_t Tp, int32_t tok_start,
                             y[j] = kdno_bf16_to_f32(raw[r * D + j]);
                     } else if (fmt == KDNO_FMT_INT4_GROUP32) {
                         kdno_dequantise_row_int4(codes4 + r * (D / 2), scales4 + r * (D / KDNO_GROUP), D, y);
+                    } else if (fmt == KDNO_FMT_FP8_ROWSCALE) {
+                        kdno_dequantise_row_fp8((const uint8_t *)codes + r * D, scales[r], D, y);
                     } else {
                         kdno_dequantise_row(codes + r * D, scales[r], D, y);
                     }

@@ -20,6 +20,7 @@ _LIB = os.path.join(_HERE, "libkdn_oracle.so")
 FMT_RAW_BF16 = 0
 FMT_INT8_ROWSCALE = 1
 FMT_INT4_GROUP32 = 2
+FMT_FP8_ROWSCALE = 3
 GROUP = 32
 PAIR_HALF_SPLIT = 0
 PAIR_INTERLEAVED = 1
@@ -68,6 +69,14 @@ def lib():
             L.kdno_quantise_row_int4.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
             L.kdno_dequantise_row_int4.restype = None
             L.kdno_dequantise_row_int4.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+            L.kdno_f32_to_e4m3.restype = C.c_uint8
+            L.kdno_f32_to_e4m3.argtypes = [C.c_float]
+            L.kdno_e4m3_to_f32.restype = C.c_float
+            L.kdno_e4m3_to_f32.argtypes = [C.c_uint8]
+            L.kdno_quantise_row_fp8.restype = None
+            L.kdno_quantise_row_fp8.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+            L.kdno_dequantise_row_fp8.restype = None
+            L.kdno_dequantise_row_fp8.argtypes = [C.c_void_p, C.c_float, C.c_int32, C.c_void_p]
             L.kdno_dequantise_row.restype = None
             L.kdno_dequantise_row.argtypes = [C.c_void_p, C.c_float, C.c_int32, C.c_void_p]
             L.kdno_rope_table.restype = None
@@ -150,12 +159,13 @@ class Chunk:
 
     # typed views of the parent buffer, for tests
     def codes(self) -> np.ndarray:
-        assert self.fmt == FMT_INT8_ROWSCALE
+        assert self.fmt in (FMT_INT8_ROWSCALE, FMT_FP8_ROWSCALE)
         n = self.L * 2 * self.Tp * self.H * self.D
-        return self.data[:n].view(np.int8).reshape(self.L, 2, self.Tp, self.H, self.D)
+        dt = np.int8 if self.fmt == FMT_INT8_ROWSCALE else np.uint8
+        return self.data[:n].view(dt).reshape(self.L, 2, self.Tp, self.H, self.D)
 
     def scales(self) -> np.ndarray:
-        assert self.fmt == FMT_INT8_ROWSCALE
+        assert self.fmt in (FMT_INT8_ROWSCALE, FMT_FP8_ROWSCALE)
         n = self.L * 2 * self.Tp * self.H * self.D
         return self.data[n:].view(np.float32).reshape(self.L, 2, self.Tp, self.H)
 
@@ -219,6 +229,33 @@ def dequantise_row_int4(packed: np.ndarray, scales: np.ndarray) -> np.ndarray:
     scales = np.ascontiguousarray(scales, dtype=np.float32)
     y = np.empty(packed.size * 2, dtype=np.float32)
     lib().kdno_dequantise_row_int4(_ptr(packed), _ptr(scales), y.size, _ptr(y))
+    return y
+
+
+def f32_to_e4m3(x: np.ndarray) -> np.ndarray:
+    f = lib().kdno_f32_to_e4m3
+    flat = np.ascontiguousarray(x, dtype=np.float32).ravel()
+    return np.array([f(float(v)) for v in flat], dtype=np.uint8).reshape(np.shape(x))
+
+
+def e4m3_to_f32(c: np.ndarray) -> np.ndarray:
+    f = lib().kdno_e4m3_to_f32
+    flat = np.ascontiguousarray(c, dtype=np.uint8).ravel()
+    return np.array([f(int(v)) for v in flat], dtype=np.float32).reshape(np.shape(c))
+
+
+def quantise_row_fp8(x_bf16: np.ndarray):
+    x = np.ascontiguousarray(x_bf16, dtype=np.uint16)
+    q = np.empty(x.size, dtype=np.uint8)
+    s = np.empty(1, dtype=np.float32)
+    lib().kdno_quantise_row_fp8(_ptr(x), x.size, _ptr(q), _ptr(s))
+    return q, np.float32(s[0])
+
+
+def dequantise_row_fp8(q: np.ndarray, scale) -> np.ndarray:
+    q = np.ascontiguousarray(q, dtype=np.uint8)
+    y = np.empty(q.size, dtype=np.float32)
+    lib().kdno_dequantise_row_fp8(_ptr(q), C.c_float(float(scale)), q.size, _ptr(y))
     return y
 
 

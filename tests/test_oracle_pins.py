@@ -12,7 +12,7 @@ import torch
 
 from paper_2409_13761_amd import synth
 
-RAW, INT8, INT4 = 0, 1, 2
+RAW, INT8, INT4, FP8 = 0, 1, 2, 3
 
 
 def bf16_bits_to_f64(b):
@@ -357,6 +357,62 @@ def test_int4_every_bf16_value_against_mathematical_rounding(oracle):
     assert n_slop < 500
 
 
+# ------------------------------------------------------------------- fp8 (e4m3), row scale
+def test_e4m3_decode_of_every_code_matches_torch(oracle):
+    codes = np.arange(256, dtype=np.uint8)
+    got = oracle.e4m3_to_f32(codes)
+    want = torch.from_numpy(codes).view(torch.float8_e4m3fn).float().numpy()
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(got[~np.isnan(got)].view(np.uint32), want[~np.isnan(want)].view(np.uint32))
+    assert got[0x7E] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6
+
+
+def test_e4m3_encode_matches_torch_below_saturation(oracle):
+    """torch's CPU cast to float8_e4m3fn is the independent reference inside the finite
+    range; above it torch gives NaN where this format saturates (never reached by the
+    quantiser, whose products stay below 448(1 + 2^-24))."""
+    rng = np.random.default_rng(31)
+    grid = oracle.e4m3_to_f32(np.arange(0, 0x7F, dtype=np.uint8)).astype(np.float64)
+    mids = (grid[:-1] + grid[1:]) / 2                       # every tie
+    x = np.concatenate([grid, mids, np.nextafter(mids.astype(np.float32), np.float32(0)),
+                        np.nextafter(mids.astype(np.float32), np.float32(1000)),
+                        rng.uniform(-448, 448, 20000), rng.standard_normal(20000) * 0.01,
+                        [448.0, 448.00003, -448.00003, 2.0 ** -10, 2.0 ** -10 * 1.0001, 0.0, -0.0]]).astype(np.float32)
+    x = np.concatenate([x, -x])
+    got = oracle.f32_to_e4m3(x)
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    inside = np.abs(x) <= 448.0
+    assert np.array_equal(got[inside], want[inside])
+    assert np.all((got[~inside] & 0x7F) == 0x7E)
+    assert oracle.f32_to_e4m3(np.array([464.0, 1e9, -1e9], dtype=np.float32)).tolist() == [0x7E, 0x7E, 0xFE]
+
+
+def test_fp8_rows(oracle):
+    D = 128
+    rows = _rows(38, 300, D)
+    for r in rows:
+        x = bf16_bits_to_f64(r)
+        q, s = oracle.quantise_row_fp8(r)
+        amax = np.max(np.abs(x))
+        assert np.float32(s) == np.float32(amax / 448.0)
+        assert (q[np.argmax(np.abs(x))] & 0x7F) == 0x7E                 # the peak maps to +-448
+        y = oracle.dequantise_row_fp8(q, s).astype(np.float64)
+        # relative error of a 3-bit mantissa: half a step of 1/8 at most, plus the subnormal floor
+        assert np.all(np.abs(x - y) <= np.abs(x) * (1 / 16 + 1e-3) + float(s) * 2.0 ** -10 * 1.01)
+        # codes are the torch cast of the fp32 products
+        inv = np.float32(448.0) / np.float32(amax)
+        prod = (bf16_bits_to_f32(r) * inv).astype(np.float32)
+        want = torch.from_numpy(np.minimum(np.abs(prod), 448.0) * np.sign(prod)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        assert np.array_equal(q, want)
+    z = np.zeros(D, dtype=np.uint16)
+    z[3] = 0x0400                        # 2^-119 * ... below? 0x0400 = 2^-119: kept
+    q, s = oracle.quantise_row_fp8(z)
+    assert s > 0 and (q[3] & 0x7F) == 0x7E
+    z[3] = 0x03FF                        # just under 2^-119: flushed
+    q, s = oracle.quantise_row_fp8(z)
+    assert s == 0 and not q.any()
+
+
 # --------------------------------------------------------------------- rotation
 def test_rope_table_values(oracle):
     for base, D, d in ((10000.0, 64, 256), (500000.0, 128, 24576), (10000.0, 128, -777)):
@@ -442,7 +498,7 @@ def _setup_compose(oracle, fmt, seed=41):
     return src, chunks, dst_bt
 
 
-@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
 def test_zero_offset_compose_is_concatenation(oracle, fmt):
     src, chunks, dst_bt = _setup_compose(oracle, fmt)
     a = make_cache(oracle, 77, src.L, src.nb, src.bs, src.H, src.D)
@@ -462,6 +518,8 @@ def test_zero_offset_compose_is_concatenation(oracle, fmt):
         else:
             if fmt == INT8:
                 y = c.codes().astype(np.float32) * c.scales()[..., None]
+            elif fmt == FP8:
+                y = torch.from_numpy(c.codes().copy()).view(torch.float8_e4m3fn).float().numpy() * c.scales()[..., None]
             else:
                 y = unpack_nibbles(c.packed4()).astype(np.float32) * np.repeat(c.scales4(), 32, axis=-1)
             rows = torch.from_numpy(y).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
@@ -472,7 +530,7 @@ def test_zero_offset_compose_is_concatenation(oracle, fmt):
         S += c.T
 
 
-@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
 def test_compose_equals_independent_single_chunk_composes(oracle, fmt):
     src, chunks, dst_bt = _setup_compose(oracle, fmt, seed=42)
     offs = [0, 29, -7]

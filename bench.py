@@ -39,12 +39,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 METRIC = "KV tokens composed/sec (store+load+RoPE shift) and achieved HBM GB/s"
-FMT_IDS = {"raw": 0, "int8": 1, "int4": 2}
+FMT_IDS = {"raw": 0, "int8": 1, "int4": 2, "fp8": 3}
 
 # HBM bytes per k_place launch of the default workload from the FETCH_SIZE / WRITE_SIZE
 # counter runs summarised under profiles/, valid only for the kernel source they were
 # taken with.
-COUNTER_TRAFFIC = {"source_sha256_16": "6d384f7d8cd5d2b6", "k_place_bytes_per_launch": 816462875}
+COUNTER_TRAFFIC = {"source_sha256_16": "7d94f219cb404c51", "k_place_bytes_per_launch": 816450597}
 
 
 def kernel_source_fingerprint():
@@ -470,7 +470,7 @@ def main() -> int:
     ap.add_argument("--workload", choices=("8b", "70b_long", "batched_reuse", "host_stream_int8", "host_stream_raw",
                              "pool_trace"),
                     default="8b")
-    ap.add_argument("--fmt", choices=("int8", "int4", "raw"), default="int8",
+    ap.add_argument("--fmt", choices=("int8", "int4", "fp8", "raw"), default="int8",
                     help="stored form used by the 8b and 70b_long workloads")
     ap.add_argument("--layout", choices=("planes", "kv_pair", "block_major"), default="planes",
                     help="paged cache layout of the 8b workload, all expressed through the "
@@ -533,7 +533,8 @@ def main() -> int:
         "dtype": "bf16 KV, %s stored form, fp32 arithmetic" % (
             "int8 codes + fp32 row scales" if args.fmt == "int8" or args.workload == "batched_reuse"
             or args.workload == "host_stream_int8" else
-            "int4 codes + fp32 group scales" if args.fmt == "int4" else "raw bf16"),
+            "int4 codes + fp32 group scales" if args.fmt == "int4" else
+            "fp8 e4m3 codes + fp32 row scales" if args.fmt == "fp8" else "raw bf16"),
         "data": "synthetic N(0,1) bf16 KV, seeded; random disjoint block tables",
         "config": {
             "workload": res["workload"],

@@ -56,6 +56,12 @@
  * codes per byte as two's-complement nibbles, the even element in the low nibble;
  * dequantisation (float)code_j * scale_group.  5 bits per element instead of 8.25: a
  * tighter form toward the footprint reductions of Sec. 3.2, "KV-cache delivery".
+ *   KDN_FMT_FP8_ROWSCALE   the int8 layout with e4m3 codes (4 exponent bits, bias 7, 3
+ *                          mantissa bits, no infinities, largest finite value 448):
+ *                          amax < 2^-119 gives scale 0, codes 0; otherwise scale =
+ *                          amax/448, inv = 448/amax, code_j = e4m3(x_j*inv) rounded to
+ *                          nearest even; dequantisation value(code_j) * scale.  Same
+ *                          footprint as int8, relative instead of absolute precision.
  *
  * RoPE shift.  Keys carry rotary position embedding with half-split pairing:
  * element j pairs with j + D/2, j in [0, D/2), at frequency
@@ -90,7 +96,8 @@ typedef enum {
 typedef enum {
     KDN_FMT_RAW_BF16 = 0,
     KDN_FMT_INT8_ROWSCALE = 1,
-    KDN_FMT_INT4_GROUP32 = 2
+    KDN_FMT_INT4_GROUP32 = 2,
+    KDN_FMT_FP8_ROWSCALE = 3
 } kdn_format;
 
 /* The engine's paged KV memory.  k_base, v_base: [device] bf16, 16-byte aligned;
@@ -148,7 +155,7 @@ typedef struct {
 } kdn_request;
 
 /* Bytes of a stored chunk of num_tokens tokens: L*2*T*H*D*2 (raw), L*2*T*H*(D+4)
- * (int8) or L*2*T*H*(D/2 + D/8) (int4).  Returns 0 on invalid arguments. */
+ * (int8, fp8) or L*2*T*H*(D/2 + D/8) (int4).  Returns 0 on invalid arguments. */
 uint64_t kdn_chunk_bytes(int32_t num_layers, int32_t num_kv_heads, int32_t head_dim,
                          int32_t num_tokens, int32_t fmt);
 

@@ -19,7 +19,7 @@ uint64_t kdn_chunk_bytes(int32_t L, int32_t H, int32_t D, int32_t T, int32_t fmt
     const uint64_t rows = (uint64_t)L * 2 * (uint64_t)T * (uint64_t)H;
     if (fmt == KDN_FMT_RAW_BF16)
         return rows * (uint64_t)D * 2;
-    if (fmt == KDN_FMT_INT8_ROWSCALE)
+    if (fmt == KDN_FMT_INT8_ROWSCALE || fmt == KDN_FMT_FP8_ROWSCALE)
         return rows * ((uint64_t)D + 4);
     if (fmt == KDN_FMT_INT4_GROUP32 && D % 32 == 0)
         return rows * ((uint64_t)D / 2 + (uint64_t)D / 32 * 4);
@@ -109,6 +109,8 @@ static kdn_status store_impl(const kdn_cache_desc *cache, const int32_t *block_t
         launch_store_d<KDN_FMT_RAW_BF16>(p, grid, hs);
     else if (out->fmt == KDN_FMT_INT8_ROWSCALE)
         launch_store_d<KDN_FMT_INT8_ROWSCALE>(p, grid, hs);
+    else if (out->fmt == KDN_FMT_FP8_ROWSCALE)
+        launch_store_d<KDN_FMT_FP8_ROWSCALE>(p, grid, hs);
     else
         launch_store_d<KDN_FMT_INT4_GROUP32>(p, grid, hs);
     st = hip_status(hipGetLastError());
@@ -321,7 +323,7 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
                                      hipMemcpyHostToDevice, ds->copy_stream);
             if (e != hipSuccess)
                 return KDN_EDEVICE;
-            if (hp.fmt == KDN_FMT_INT8_ROWSCALE) {
+            if (hp.fmt == KDN_FMT_INT8_ROWSCALE || hp.fmt == KDN_FMT_FP8_ROWSCALE) {
                 const uint64_t w_sc = (uint64_t)Tu * H * 4, pitch_sc = (uint64_t)Tp * H * 4;
                 const uint8_t *src_sc = hp.data + (uint64_t)L * 2 * Tp * H * D
                                         + ((uint64_t)l0 * 2 * Tp + hp.lo) * H * 4;
@@ -337,7 +339,7 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
             const uint64_t bytes = kdn_chunk_bytes(Lg, H, D, Tu, hp.fmt);
             at += (bytes + 255) & ~(uint64_t)255;
         }
-        std::vector<Seg> segs[3];
+        std::vector<Seg> segs[kFormats];
         int32_t S = dest_token_start;
         for (int32_t i = 0; i < n_chunks; ++i) {
             const kdn_chunk &ch = chunks[i];
@@ -359,7 +361,7 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
             return KDN_EDEVICE;
         p.c.L = Lg;
         p.layer0 = l0;
-        for (int f = 0; f < 3; ++f) {
+        for (int f = 0; f < kFormats; ++f) {
             st = place_segments(ds, p, f, segs[f], user);
             if (st != KDN_OK)
                 return st;

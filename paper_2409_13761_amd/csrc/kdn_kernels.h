@@ -95,6 +95,17 @@ __device__ __forceinline__ float code_f32(uint32_t w, int byte)
     return (float)(int8_t)(w >> (8 * byte));
 }
 
+// value of the e4m3 code in byte `byte` of w (exact)
+__device__ __forceinline__ float fp8_f32(uint32_t w, int byte)
+{
+    switch (byte) {
+    case 0: return __builtin_amdgcn_cvt_f32_fp8((int)w, 0);
+    case 1: return __builtin_amdgcn_cvt_f32_fp8((int)w, 1);
+    case 2: return __builtin_amdgcn_cvt_f32_fp8((int)w, 2);
+    default: return __builtin_amdgcn_cvt_f32_fp8((int)w, 3);
+    }
+}
+
 constexpr __host__ __device__ int log2_ceil(int x)
 {
     int l = 0;
@@ -160,6 +171,15 @@ __device__ __forceinline__ uint32_t quantise4(uint32_t w0, uint32_t w1, float in
     return p01 | p23;
 }
 
+// e4m3 codes of 4 values: the hardware conversion rounds to nearest even; the products
+// never leave the finite range (|x*inv| <= 448(1 + 2^-24), which still rounds to 448).
+__device__ __forceinline__ uint32_t quantise4_fp8(uint32_t w0, uint32_t w1, float inv)
+{
+    int v = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(w0) * inv, bf16_hi(w0) * inv, 0, false);
+    v = __builtin_amdgcn_cvt_pk_fp8_f32(bf16_lo(w1) * inv, bf16_hi(w1) * inv, v, true);
+    return (uint32_t)v;
+}
+
 template <int DT, int FMT, int P, bool DENSE>
 __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 {
@@ -168,6 +188,9 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     // with at least 8 lanes per row the 2*U divisions of a batch are spread over the
     // lanes of the row's group (one division sequence per batch instead of 2*U)
     constexpr bool SPREAD = P >= 8 && U == 4;
+    // largest code magnitude, and the smallest amax whose reciprocal scale is finite
+    constexpr float QMAX = FMT == KDN_FMT_FP8_ROWSCALE ? 448.0f : 127.0f;
+    constexpr float TINY = FMT == KDN_FMT_FP8_ROWSCALE ? 0x1p-119f : 0x1p-121f;
     const int D = DT ? DT : p.c.D;
     const int R = D >> 3;
     const int H = p.c.H, G = p.c.G, bs = p.c.bs;
@@ -189,7 +212,7 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     const int64_t row_base = ((int64_t)ls * p.T + (tok_lo - p.t0)) * H;
     const int n_items = ((tok_hi - tok_lo) * H) << LOGP;
     const int64_t total_rows = (int64_t)p.c.L * 2 * p.T * H;
-    constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT8_ROWSCALE ? 2 : 1; // words per 8 stored elements
+    constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT4_GROUP32 ? 1 : 2; // words per 8 stored elements
     const int spr = FMT == KDN_FMT_INT4_GROUP32 ? D >> 5 : 1;                              // scales per row
     uint8_t *codes = p.out + ((row_base * D * W) >> 1);
     float *scales = reinterpret_cast<float *>(p.out + ((total_rows * D * W) >> 1)) + row_base * spr;
@@ -285,8 +308,8 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
             const uint32_t msel = us == 0 ? m[0] : us == 1 ? m[1] : us == 2 ? m[2] : m[U - 1];
             const float amax = __uint_as_float(msel << 16);
             const bool is_scale = (sub & 4) != 0;
-            const float q = (is_scale ? amax : 127.0f) / (is_scale ? 127.0f : amax);
-            const float quot = amax >= 0x1p-121f ? q : 0.0f;
+            const float q = (is_scale ? amax : QMAX) / (is_scale ? QMAX : amax);
+            const float quot = amax >= TINY ? q : 0.0f;
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 inv[u] = __int_as_float(__builtin_amdgcn_ds_bpermute(grp_addr + 4 * u, __float_as_int(quot)));
@@ -297,11 +320,11 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const float amax = __uint_as_float(m[u] << 16);
-                const bool keep = amax >= 0x1p-121f;
-                inv[u] = keep ? 127.0f / amax : 0.0f;
+                const bool keep = amax >= TINY;
+                inv[u] = keep ? QMAX / amax : 0.0f;
                 const int it = base + u * kThreads + threadIdx.x;
                 if (sub == 0 && it < n_items)
-                    scales[it >> LOGP] = keep ? amax / 127.0f : 0.0f;
+                    scales[it >> LOGP] = keep ? amax / QMAX : 0.0f;
             }
         }
 #pragma unroll
@@ -309,7 +332,15 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
             const int it = base + u * kThreads + threadIdx.x;
             const int r = it >> LOGP;
             if (it < n_items && sub < R) {
-                const u32x2 q = {quantise4(w[u][0], w[u][1], inv[u]), quantise4(w[u][2], w[u][3], inv[u])};
+                u32x2 q;
+                if (FMT == KDN_FMT_FP8_ROWSCALE) {
+                    // a flushed row (inv == 0) stores code 0, not the -0 code of a negative element
+                    const uint32_t live = inv[u] != 0.0f ? 0xffffffffu : 0u;
+                    q = u32x2{quantise4_fp8(w[u][0], w[u][1], inv[u]) & live,
+                              quantise4_fp8(w[u][2], w[u][3], inv[u]) & live};
+                } else {
+                    q = u32x2{quantise4(w[u][0], w[u][1], inv[u]), quantise4(w[u][2], w[u][3], inv[u])};
+                }
                 __builtin_nontemporal_store(q, reinterpret_cast<u32x2 *>(codes + (uint32_t)(r * D + sub * 8)));
             }
         }
@@ -346,7 +377,7 @@ template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 {
     constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 2 : 4;
-    constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT8_ROWSCALE ? 2 : 1; // 32-bit words per 8 stored elements
+    constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT4_GROUP32 ? 1 : 2; // 32-bit words per 8 stored elements
     constexpr int NS = FMT == KDN_FMT_INT4_GROUP32 ? 2 : 1;                                // scales per item
     const int D = DT ? DT : p.c.D;
     const int half = D >> 1;
@@ -485,6 +516,12 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                     for (int e = 0; e < 8; ++e) {
                         a[e] = (float)((int32_t)(lo[u][0] << (28 - 4 * e)) >> 28) * sc[u][0];
                         b[e] = (float)((int32_t)(hi[u][0] << (28 - 4 * e)) >> 28) * sc[u][NS - 1];
+                    }
+                } else if (FMT == KDN_FMT_FP8_ROWSCALE) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        a[e] = fp8_f32(lo[u][(e >> 2) % W], e & 3) * sc[u][0];
+                        b[e] = fp8_f32(hi[u][(e >> 2) % W], e & 3) * sc[u][0];
                     }
                 } else {
 #pragma unroll

@@ -16,6 +16,8 @@
 namespace kdn_impl {
 
 // Resolved RoPE variant of one call: frequencies either derived from `base` or given.
+constexpr int kFormats = 4; // kdn_format values
+
 struct RopeSpec {
     double base = 0.0;
     std::vector<double> freq; // rot/2 explicit frequencies, empty: base^(-2j/rot)
@@ -81,7 +83,8 @@ kdn_status check_cache(const kdn_cache_desc *c)
 
 bool known_format(int32_t fmt)
 {
-    return fmt == KDN_FMT_RAW_BF16 || fmt == KDN_FMT_INT8_ROWSCALE || fmt == KDN_FMT_INT4_GROUP32;
+    return fmt == KDN_FMT_RAW_BF16 || fmt == KDN_FMT_INT8_ROWSCALE || fmt == KDN_FMT_INT4_GROUP32
+           || fmt == KDN_FMT_FP8_ROWSCALE;
 }
 
 kdn_status check_chunk(const kdn_chunk *ch, const kdn_cache_desc *c)
@@ -371,6 +374,8 @@ kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const s
         launch_place_d<KDN_FMT_RAW_BF16>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
     else if (fmt == KDN_FMT_INT8_ROWSCALE)
         launch_place_d<KDN_FMT_INT8_ROWSCALE>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
+    else if (fmt == KDN_FMT_FP8_ROWSCALE)
+        launch_place_d<KDN_FMT_FP8_ROWSCALE>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
     else
         launch_place_d<KDN_FMT_INT4_GROUP32>(p, segs.data(), (int32_t)segs.size(), segs_dev, grid, st);
     kdn_status rc = hip_status(hipGetLastError());
@@ -424,7 +429,7 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
     st = rope_rows(ds, spec, offs.data(), (int32_t)offs.size(), rows.data(), &p.rope);
     if (st != KDN_OK)
         return st;
-    std::vector<Seg> segs[3];
+    std::vector<Seg> segs[kFormats];
     size_t k = 0;
     for (int32_t r = 0; r < n_reqs; ++r) {
         const kdn_request &q = reqs[r];
@@ -444,7 +449,7 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
             S += ch.num_tokens;
         }
     }
-    for (int f = 0; f < 3; ++f) {
+    for (int f = 0; f < kFormats; ++f) {
         // Segments that read the same stored rows run back to back, so that a popular
         // chunk is fetched from HBM once and from the last-level cache afterwards.
         p.reuse = 0;

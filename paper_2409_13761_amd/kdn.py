@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_PKG, "libkdn.so")
 FMT_RAW_BF16 = 0
 FMT_INT8_ROWSCALE = 1
 FMT_INT4_GROUP32 = 2
+FMT_FP8_ROWSCALE = 3
 
 OK, EINVAL, EALIGN, ERANGE, ESIZE, EDEVICE, EUNSUPPORTED, ENOTFOUND = 0, -1, -2, -3, -4, -5, -6, -7
 
@@ -212,13 +213,13 @@ class Chunk:
 
     def codes(self) -> torch.Tensor:
         d, n = self._split()
-        assert d.fmt == FMT_INT8_ROWSCALE
-        return self.data[:n].view(torch.int8).view(d.num_layers, 2, d.parent_tokens,
+        assert d.fmt in (FMT_INT8_ROWSCALE, FMT_FP8_ROWSCALE)
+        return self.data[:n].view(torch.int8 if d.fmt == FMT_INT8_ROWSCALE else torch.uint8).view(d.num_layers, 2, d.parent_tokens,
                                                    d.num_kv_heads, d.head_dim)
 
     def scales(self) -> torch.Tensor:
         d, n = self._split()
-        assert d.fmt == FMT_INT8_ROWSCALE
+        assert d.fmt in (FMT_INT8_ROWSCALE, FMT_FP8_ROWSCALE)
         return self.data[n:n + n // d.head_dim * 4].view(torch.float32).view(
             d.num_layers, 2, d.parent_tokens, d.num_kv_heads)
 

@@ -90,7 +90,7 @@ class KVShape:
 
     def stored_bytes_per_token(self, fmt_name: str) -> int:
         return {"raw": self.paged_bytes_per_token, "int8": self.int8_bytes_per_token,
-                "int4": self.int4_bytes_per_token}[fmt_name]
+                "fp8": self.int8_bytes_per_token, "int4": self.int4_bytes_per_token}[fmt_name]
 
 
 @dataclass(frozen=True)

@@ -6,7 +6,7 @@ import torch
 from oracle import kdn_oracle as O
 from paper_2409_13761_amd import kdn, synth
 
-RAW, INT8, INT4 = 0, 1, 2
+RAW, INT8, INT4, FP8 = 0, 1, 2, 3
 K_TOL = 1e-2        # absolute tolerance on RoPE-shifted bf16 keys for N(0,1) inputs
 
 

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 import torch
 
-from helpers import (INT4, INT8, RAW, assert_cache_equal, assert_chunk_equal, bits_of, chunk_to_dev,
+from helpers import (FP8, INT4, INT8, RAW, assert_cache_equal, assert_chunk_equal, bits_of, chunk_to_dev,
                      dev_cache, dev_table, host_cache, to_dev_bf16)
 from oracle import kdn_oracle as O
 from paper_2409_13761_amd import kdn, synth
@@ -21,7 +21,7 @@ def _say(msg):
 
 
 # ------------------------------------------------------------------ store
-@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
 @pytest.mark.parametrize("shape", [
     # L, nb, bs, H, D, t0, T
     (2, 24, 16, 4, 64, 0, 128),        # block aligned, several tiles
@@ -117,7 +117,7 @@ def test_store_strided_cache():
 
 
 # ------------------------------------------------------------------ load / compose
-@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
 @pytest.mark.parametrize("shape", [
     # L, nb, bs, H, D, dest, T
     (2, 24, 16, 4, 64, 0, 128),
@@ -152,7 +152,7 @@ def test_load_matches_oracle_and_touches_nothing_else(fmt, shape):
     assert_cache_equal(dd, hd)
 
 
-@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
 @pytest.mark.parametrize("D,base", [(64, 10000.0), (128, 500000.0), (96, 10000.0), (16, 10000.0), (256, 1e6),
                                     (32, 10000.0), (512, 10000.0)])
 def test_compose_ragged_chunks_with_offsets(fmt, D, base):
@@ -176,19 +176,67 @@ def test_compose_ragged_chunks_with_offsets(fmt, D, base):
 def test_compose_mixed_formats_and_slices():
     L, nb, bs, H, D = 2, 48, 16, 4, 64
     src = host_cache(21, L, nb, bs, H, D)
-    a, b, dst_bt = synth.disjoint_block_tables(21, nb, [10, 6, 14])
+    a, b, dst_bt = synth.disjoint_block_tables(21, nb, [10, 6, 18])
     whole = O.store(src, a, 0, 160, INT8)
     rawc = O.store(src, b, 3, 90, RAW)
     four = O.store(src, a, 16, 70, INT4)
-    chunks = [whole.slice(100, 50), rawc.slice(10, 33), whole.slice(0, 64), rawc.slice(0, 10), four.slice(5, 60)]
-    offsets = [7, 0, 50, -90, 33]
+    eight = O.store(src, b, 0, 40, FP8)
+    chunks = [whole.slice(100, 50), rawc.slice(10, 33), whole.slice(0, 64), rawc.slice(0, 10), four.slice(5, 60),
+              eight.slice(3, 30)]
+    offsets = [7, 0, 50, -90, 33, -5]
     hd = host_cache(22, L, nb, bs, H, D)
     dd = dev_cache(hd)
     O.compose(chunks, offsets, hd, dst_bt, 10000.0, dest=1)
-    dw, dr, d4 = chunk_to_dev(whole), chunk_to_dev(rawc), chunk_to_dev(four)
-    dchunks = [dw.slice(100, 50), dr.slice(10, 33), dw.slice(0, 64), dr.slice(0, 10), d4.slice(5, 60)]
+    dw, dr, d4, d8 = chunk_to_dev(whole), chunk_to_dev(rawc), chunk_to_dev(four), chunk_to_dev(eight)
+    dchunks = [dw.slice(100, 50), dr.slice(10, 33), dw.slice(0, 64), dr.slice(0, 10), d4.slice(5, 60),
+               d8.slice(3, 30)]
     kdn.kdn_compose(dchunks, offsets, dd, dev_table(dst_bt), 10000.0, dest_token_start=1)
     assert_cache_equal(dd, hd)
+
+
+def test_fp8_special_rows_and_every_amax():
+    """Every positive finite bf16 as a row's amax with companions at ratios that land on
+    and next to e4m3 ties and in its subnormal range; zero and under-threshold rows."""
+    L, nb, bs, H, D = 1, 2100, 16, 1, 32
+    k = np.zeros((L, nb, bs, H, D), dtype=np.uint16)
+    rows = k.reshape(-1, D)
+    amax_bits = np.arange(1, 0x7F80, dtype=np.uint16)
+    n = amax_bits.size
+    rows[:n, 0] = amax_bits
+    f = (amax_bits.astype(np.uint32) << 16).view(np.float32)
+    ratios = (0.5, -0.25, 0.96875, -0.9375, 0.53125, 0.03515625, -0.001953125, 0.0009765625, 0.00048828125,
+              0.000244140625, -0.0001, 0.3333, -0.0117, 0.99, 0.0021, -0.0033, 0.07, 0.6, -0.8, 0.15)
+    for j, ratio in enumerate(ratios, start=1):
+        rows[:n, j] = bits_of(torch.from_numpy((f * np.float32(ratio)).astype(np.float32)).to(torch.bfloat16))
+    rows[n, 3] = 0x8000
+    rows[n + 1, :] = 0x03FF                               # under 2^-119 everywhere
+    rows[n + 2, :4] = [0x0400, 0x8400, 0x0380, 0x0001]    # exactly 2^-119
+    hc = O.PagedCache(k, synth.normal_bf16(8, k.shape))
+    T = nb * bs
+    bt = np.arange(nb, dtype=np.int32)
+    want = O.store(hc, bt, 0, T, FP8)
+    dc = dev_cache(hc)
+    out = kdn.alloc_chunk(dc, T, FP8)
+    kdn.kdn_store_chunk(dc, dev_table(bt), 0, T, out)
+    assert_chunk_equal(out, want)
+    hd = O.PagedCache(np.zeros_like(hc.k), np.zeros_like(hc.v))
+    O.load(want, hd, bt, 0)
+    dd = dev_cache(O.PagedCache(np.zeros_like(hc.k), np.zeros_like(hc.v)))
+    kdn.kdn_load_chunk(out, dd, dev_table(bt), 0)
+    assert_cache_equal(dd, hd)
+    # every e4m3 code decodes on the device as the oracle says
+    codes = np.tile(np.arange(256, dtype=np.uint8), 4)                      # one row of 1024... as 32 rows of 32
+    codes[codes == 0x7F] = 0
+    codes[codes == 0xFF] = 0x80
+    chunk = O.Chunk(np.zeros(O.chunk_bytes(1, 1, 32, 32, FP8), dtype=np.uint8), FP8, 1, 1, 32, 32)
+    chunk.codes()[0, 0] = codes.reshape(32, 1, 32)
+    chunk.codes()[0, 1] = codes.reshape(32, 1, 32)
+    chunk.scales()[:] = np.float32(0.37)
+    hd2 = O.PagedCache(np.zeros((1, 2, 16, 1, 32), dtype=np.uint16), np.zeros((1, 2, 16, 1, 32), dtype=np.uint16))
+    O.load(chunk, hd2, np.array([1, 0], dtype=np.int32), 0)
+    dd2 = dev_cache(O.PagedCache(np.zeros_like(hd2.k), np.zeros_like(hd2.v)))
+    kdn.kdn_load_chunk(chunk_to_dev(chunk), dd2, dev_table(np.array([1, 0], dtype=np.int32)), 0)
+    assert_cache_equal(dd2, hd2)
 
 
 def test_int4_special_groups():
@@ -361,7 +409,7 @@ def test_compose_from_pinned_host_chunks_equals_compose(layers_per_stage):
 
 
 # ------------------------------------------------------------------ RoPE variants, patching
-@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
 @pytest.mark.parametrize("variant", [
     # D, rot_dim, pairing, explicit frequencies?
     (128, 0, 1, False),        # interleaved pairs, whole row
@@ -498,7 +546,7 @@ def test_store_and_compose_replay_inside_a_hip_graph():
 
 
 # ------------------------------------------------------------------ token-list store
-@pytest.mark.parametrize("fmt", [RAW, INT8, INT4])
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
 @pytest.mark.parametrize("shape", [(2, 24, 16, 4, 64), (3, 40, 16, 8, 128), (1, 30, 8, 3, 96), (1, 64, 1, 2, 32)])
 def test_store_tokens_matches_oracle(fmt, shape):
     L, nb, bs, H, D = shape

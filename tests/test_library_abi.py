@@ -45,6 +45,7 @@ def test_chunk_bytes(lib):
     assert kdn.kdn_chunk_bytes(2, 4, 64, 4, 7) == 0
     assert kdn.kdn_chunk_bytes(32, 8, 128, 1, 2) == 40960        # int4: 5 bits per element
     assert kdn.kdn_chunk_bytes(2, 4, 48, 4, 2) == 0              # int4 needs head_dim % 32 == 0
+    assert kdn.kdn_chunk_bytes(32, 8, 128, 1, 3) == 67584        # fp8: the int8 footprint
     # 32768 tokens of the 80-layer shape need more than 32 bits
     assert kdn.kdn_chunk_bytes(80, 8, 128, 32768, 1) == 32768 * 168960
 

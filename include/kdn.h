@@ -31,6 +31,15 @@
  *     id outside [0, num_blocks) or a destination block listed twice is undefined
  *     behaviour.  kdn_validate_block_table() is the opt-in check.
  *   - KV values must be finite.
+ *   - HIP graph capture: kdn_store_chunk, kdn_store_tokens, kdn_load_chunk,
+ *     kdn_patch_rows, and kdn_compose / kdn_compose_rope with at most 64 chunks whose
+ *     cos/sin rows are resident (kdn_rope_prepare) enqueue kernels only and may be
+ *     captured.  Composes with more chunks (their segment table is copied from pinned
+ *     memory and guarded by events), kdn_compose_from_host and
+ *     kdn_validate_block_table must not be captured.
+ *   - Calls may come from several host threads and target several streams; the
+ *     library serialises its own bookkeeping.  Two calls that write the same
+ *     destination blocks race like any two kernels would.
  *
  * Paged cache layout (kdn_cache_desc).  For layer l, side K or V, physical block b,
  * slot s (token within the block), kv-head h and dimension j the bf16 element is

@@ -1,0 +1,95 @@
+"""Seeded random parity sweep: shapes, block sizes, formats, ragged token ranges, chunk
+views, RoPE variants and patches drawn at random, every result compared with the oracle
+bit for bit.  Complements the hand-picked cases of test_gpu_parity.py."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import (FP8, INT4, INT8, RAW, assert_cache_equal, assert_chunk_equal, chunk_to_dev,
+                     dev_cache, dev_table, host_cache, to_dev_bf16)
+from oracle import kdn_oracle as O
+from paper_2409_13761_amd import kdn, synth
+
+pytestmark = pytest.mark.gpu
+
+DIMS = (16, 32, 48, 64, 80, 96, 128, 192, 256)
+BLOCKS = (1, 2, 4, 8, 16, 24, 32, 48)
+
+
+def _case(seed):
+    rng = np.random.default_rng(seed)
+    L, H = int(rng.integers(1, 4)), int(rng.integers(1, 6))
+    D, bs = int(rng.choice(DIMS)), int(rng.choice(BLOCKS))
+    fmts = [f for f in (RAW, INT8, INT4, FP8) if f != INT4 or D % 32 == 0]
+    tokens_cap = int(rng.integers(40, 200))
+    n_tab = (tokens_cap + bs - 1) // bs
+    nb = 3 * n_tab + 5
+    return rng, L, H, D, bs, fmts, n_tab, nb
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_store_compose_patch(seed):
+    rng, L, H, D, bs, fmts, n_tab, nb = _case(1000 + seed)
+    cap = n_tab * bs
+    print("[case] seed=%d L=%d H=%d D=%d bs=%d cap=%d" % (seed, L, H, D, bs, cap), flush=True)
+    src = host_cache(2000 + seed, L, nb, bs, H, D)
+    t_a, t_b, dst_bt = synth.disjoint_block_tables(seed, nb, [n_tab, n_tab, n_tab])
+    dsrc = dev_cache(src)
+
+    # two stored chunks of random ranges and formats, checked as stored
+    hch, dch = [], []
+    for tab in (t_a, t_b):
+        fmt = int(rng.choice(fmts))
+        t0 = int(rng.integers(0, cap // 2))
+        T = int(rng.integers(1, cap - t0 + 1))
+        h = O.store(src, tab, t0, T, fmt)
+        out = kdn.alloc_chunk(dsrc, T, fmt)
+        kdn.kdn_store_chunk(dsrc, dev_table(tab), t0, T, out)
+        assert_chunk_equal(out, h)
+        hch.append(h)
+        dch.append(out)
+
+    # random views of them, composed with a random RoPE variant into a third table
+    views_h, views_d, offsets, total = [], [], [], 0
+    dest = int(rng.integers(0, bs + 1))
+    for _ in range(int(rng.integers(1, 6))):
+        i = int(rng.integers(0, 2))
+        ts = int(rng.integers(0, hch[i].T))
+        Tv = int(rng.integers(1, hch[i].T - ts + 1))
+        if dest + total + Tv > cap:
+            break
+        views_h.append(hch[i].slice(ts, Tv))
+        views_d.append(dch[i].slice(ts, Tv))
+        offsets.append(int(rng.integers(-5000, 5000)) if rng.random() < 0.8 else 0)
+        total += Tv
+    if not views_h:
+        views_h, views_d, offsets = [hch[0].slice(0, 1)], [dch[0].slice(0, 1)], [3]
+        dest, total = 0, 1
+    rot = int(rng.choice([0] + [r for r in range(16, D + 1, 16)]))
+    pairing = int(rng.integers(0, 2))
+    base = float(rng.choice([10000.0, 500000.0]))
+    inv_freq = None
+    if rng.random() < 0.3:
+        r = rot or D
+        inv_freq = base ** (-2.0 * np.arange(r // 2) / r) * rng.uniform(0.1, 1.0, size=r // 2)
+    hd = host_cache(3000 + seed, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose_spec(views_h, offsets, hd, dst_bt, base, inv_freq=inv_freq, rot_dim=rot, pairing=pairing, dest=dest)
+    kdn.kdn_compose_rope(views_d, offsets, dd, dev_table(dst_bt), kdn.rope_spec(base, inv_freq, rot, pairing),
+                         dest_token_start=dest)
+    assert_cache_equal(dd, hd)
+
+    # a kept-token store from the composed request, and a patch over a few of its tokens
+    n_keep = int(rng.integers(1, dest + total + 1))
+    keep = np.sort(rng.choice(dest + total, size=n_keep, replace=False)).astype(np.int32)
+    fmt = int(rng.choice(fmts))
+    want = O.store_tokens(hd, dst_bt, keep, fmt)
+    out = kdn.alloc_chunk(dd, n_keep, fmt)
+    kdn.kdn_store_tokens(dd, dev_table(dst_bt), torch.from_numpy(keep).cuda(), out)
+    assert_chunk_equal(out, want)
+    n_patch = int(rng.integers(1, min(8, cap) + 1))
+    tok = rng.choice(cap, size=n_patch, replace=False).astype(np.int32)
+    rows = synth.normal_bf16(4000 + seed, (L, 2, n_patch, H, D))
+    O.patch_rows(rows, tok, hd, dst_bt)
+    kdn.kdn_patch_rows(to_dev_bf16(rows), torch.from_numpy(tok).cuda(), dd, dev_table(dst_bt))
+    assert_cache_equal(dd, hd)

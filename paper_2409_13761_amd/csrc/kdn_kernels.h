@@ -119,7 +119,7 @@ constexpr __host__ __device__ int log2_ceil(int x)
 // Lane group: D/8 lanes own one row, 8 consecutive elements (one 16-byte load) each;
 // the group is padded to a power of two so the row reduction is a butterfly of
 // cross-lane moves (DPP within 16 lanes, wavefront shuffles beyond).
-// Grid: x = group * 2L + (layer, side).
+// Grid: x = (layer, side) * groups + group.
 
 // max over the P lanes of a row's lane group; every lane of the group gets the result
 template <int P>
@@ -196,8 +196,10 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     const int H = p.c.H, G = p.c.G, bs = p.c.bs;
     const int L2 = 2 * p.c.L;
 
-    const int piece = blockIdx.x / L2;
-    const int ls = blockIdx.x - piece * L2;
+    // group-fastest order: neighbouring workgroups write neighbouring rows of the chunk
+    const int n_groups = gridDim.x / L2;
+    const int ls = blockIdx.x / n_groups;
+    const int piece = blockIdx.x - ls * n_groups;
     const int gi = p.t0 / G + piece;
     const int tok_lo = max(p.t0, gi * G);
     const int tok_hi = min(p.t0 + p.T, (gi + 1) * G);

@@ -12,7 +12,7 @@ Inputs are resident in HBM before the timed region.  Four disjoint buffer sets a
 cycled, and a step reads chunks that were stored two or three steps earlier, so that
 the 256 MB last-level cache cannot serve a repeat or a just-written chunk.
 
-Other workloads (--workload): "70b_long" (80 layers, 32768 tokens: one store, one
+Other workloads (--workload): "toy" (latency bound), "70b_long" (80 layers, 32768 tokens: one store, one
 compose of four 8192-token slices) and "batched_reuse" (64 requests x 4 chunks of
 1024 tokens drawn by Zipf popularity from a resident pool of 256 chunks, one batched
 compose per step).
@@ -190,6 +190,43 @@ def workload_8b(args, dev):
         res["cpu_baseline"] = cpu_baseline(cache, sets[0][0], order, offsets, w.rope_base, T, n_slices,
                                            args.cpu_steps)
     return res
+
+
+def workload_toy(args, dev):
+    """The toy workload: 2 layers, 4 KV heads, head_dim 64, 128 blocks; two 256-token chunks
+    stored, then composed at offsets 0 and 256.  About 1.5 MB per call: launch latency, not
+    bandwidth, is what this measures."""
+    import torch
+    from paper_2409_13761_amd import kdn, synth
+
+    w = synth.WORKLOADS["toy"]
+    sh, nb = w.shape, 128
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+    v = torch.empty_like(k)
+    fill_normal(k, g)
+    fill_normal(v, g)
+    cache = kdn.PagedCache(k, v)
+    t1, t2, dst = (torch.from_numpy(t).to(dev) for t in synth.disjoint_block_tables(w.seed, nb, [16, 16, 32]))
+    c1 = kdn.alloc_chunk(cache, 256, FMT_IDS[args.fmt])
+    c2 = kdn.alloc_chunk(cache, 256, FMT_IDS[args.fmt])
+    offsets = list(w.offsets)
+    kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
+
+    def step(i, rec):
+        rec("store", lambda: (kdn.kdn_store_chunk(cache, t1, 0, 256, c1), kdn.kdn_store_chunk(cache, t2, 0, 256, c2)))
+        rec("compose", lambda: kdn.kdn_compose([c1, c2], offsets, cache, dst, w.rope_base))
+
+    wall, ms = Timed(("store", "compose"), args.steps).run(step, args.warmup)
+    bytes_call = 512 * (sh.paged_bytes_per_token + sh.stored_bytes_per_token(args.fmt))
+    return {
+        "tokens_per_step": 512, "wall": wall, "ms": ms, "bytes": {n: bytes_call for n in ms},
+        "place_calls": ("compose",),
+        "workload": "toy KV (L2 H4 D64 bs16, 128 blocks): per step store two 256-token chunks to %s "
+                    "(two calls) and compose them at offsets 0 and 256, base 10000; latency bound" % args.fmt,
+        "traffic": None,
+    }
 
 
 def workload_70b(args, dev):
@@ -467,8 +504,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=("8b", "70b_long", "batched_reuse", "host_stream_int8", "host_stream_raw",
-                             "pool_trace"),
+    ap.add_argument("--workload", choices=("8b", "toy", "70b_long", "batched_reuse", "host_stream_int8",
+                             "host_stream_raw", "pool_trace"),
                     default="8b")
     ap.add_argument("--fmt", choices=("int8", "int4", "fp8", "raw"), default="int8",
                     help="stored form used by the 8b and 70b_long workloads")
@@ -486,7 +523,7 @@ def main() -> int:
         print("bench.py: this build runs on one GPU only; the path shards without any exchange "
               "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
         return 2
-    defaults = {"8b": (40, 8), "70b_long": (10, 3), "batched_reuse": (10, 3),
+    defaults = {"8b": (40, 8), "toy": (200, 20), "70b_long": (10, 3), "batched_reuse": (10, 3),
                 "host_stream_int8": (10, 3), "host_stream_raw": (10, 3), "pool_trace": (400, 100)}[args.workload]
     args.steps = defaults[0] if args.steps is None else args.steps
     args.warmup = defaults[1] if args.warmup is None else args.warmup
@@ -501,7 +538,7 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
-    res = {"8b": workload_8b, "70b_long": workload_70b, "batched_reuse": workload_batched,
+    res = {"8b": workload_8b, "toy": workload_toy, "70b_long": workload_70b, "batched_reuse": workload_batched,
            "host_stream_int8": lambda a, d: workload_host_stream(a, d, "int8"),
            "host_stream_raw": lambda a, d: workload_host_stream(a, d, "raw"),
            "pool_trace": workload_pool_trace}[args.workload](args, dev)

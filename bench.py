@@ -520,7 +520,7 @@ def main() -> int:
                          "scaling hardware byte counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only; the path shards without any exchange "
+        print("bench.py: this library runs on one GPU only; the path shards without any exchange "
               "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
         return 2
     defaults = {"8b": (40, 8), "toy": (200, 20), "70b_long": (10, 3), "batched_reuse": (10, 3),

@@ -269,6 +269,10 @@ uint64_t kdn_staging_bytes(const kdn_chunk *chunks, int32_t n_chunks, int32_t la
 kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *offsets,
                             int32_t n);
 
+/* The same for a RoPE variant (rope: [host], not NULL). */
+kdn_status kdn_rope_prepare_spec(const kdn_rope_spec *rope, int32_t head_dim, const int32_t *offsets,
+                                 int32_t n);
+
 /* Debug check, synchronous: KDN_ERANGE if any of the table_len entries of
  * block_table_dev [device] is outside [0, num_blocks) or occurs twice. */
 kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t table_len,

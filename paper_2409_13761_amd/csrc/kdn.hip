@@ -84,8 +84,8 @@ static kdn_status store_impl(const kdn_cache_desc *cache, const int32_t *block_t
     if (!aligned16(out->data))
         return KDN_EALIGN;
     const int64_t limit = (int64_t)table_len * cache->block_size;
-    if (!tokens_dev && (int64_t)token_start + num_tokens > limit)
-        return KDN_ERANGE;
+    if (!tokens_dev && ((int64_t)token_start + num_tokens > limit || (int64_t)token_start + num_tokens > 0x7fffffff))
+        return KDN_ERANGE; // token indices are 32-bit in the kernels
     const uint64_t need = kdn_chunk_bytes(cache->num_layers, cache->num_kv_heads, cache->head_dim,
                                           num_tokens, out->fmt);
     if (out->bytes < need)
@@ -256,8 +256,8 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
             return KDN_EINVAL;
         total += chunks[i].num_tokens;
     }
-    if (total > (int64_t)table_len * cache->block_size)
-        return KDN_ERANGE;
+    if (total > (int64_t)table_len * cache->block_size || total > 0x7fffffff)
+        return KDN_ERANGE; // token indices are 32-bit in the kernels
     const uint64_t need = kdn_staging_bytes(chunks, n_chunks, layers_per_stage);
     if (need == 0 || staging_bytes < need)
         return KDN_ESIZE;
@@ -373,11 +373,16 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
     return KDN_OK;
 }
 
-kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *offsets, int32_t n)
+static kdn_status rope_prepare_impl(const kdn_rope_spec *variant, double rope_base, int32_t head_dim,
+                                    const int32_t *offsets, int32_t n)
 {
     if (!offsets || n <= 0)
         return KDN_EINVAL;
     kdn_status st = check_shape(1, 1, head_dim);
+    if (st != KDN_OK)
+        return st;
+    RopeSpec spec;
+    st = resolve_spec(variant, rope_base, head_dim, spec);
     if (st != KDN_OK)
         return st;
     std::lock_guard<std::mutex> lock(g_mu);
@@ -386,11 +391,20 @@ kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *o
         return KDN_EDEVICE;
     std::vector<int32_t> rows((size_t)n);
     const f32x2 *table;
-    RopeSpec spec;
-    st = resolve_spec(nullptr, rope_base, head_dim, spec);
-    if (st != KDN_OK)
-        return st;
     return rope_rows(ds, spec, offsets, n, rows.data(), &table);
+}
+
+kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *offsets, int32_t n)
+{
+    return rope_prepare_impl(nullptr, rope_base, head_dim, offsets, n);
+}
+
+kdn_status kdn_rope_prepare_spec(const kdn_rope_spec *rope, int32_t head_dim, const int32_t *offsets,
+                                 int32_t n)
+{
+    if (!rope)
+        return KDN_EINVAL;
+    return rope_prepare_impl(rope, rope->base, head_dim, offsets, n);
 }
 
 kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t table_len,

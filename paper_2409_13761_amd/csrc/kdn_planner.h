@@ -413,8 +413,8 @@ kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache
             total += q.chunks[i].num_tokens;
             offs.push_back(q.offsets[i]);
         }
-        if (total > (int64_t)q.table_len * cache->block_size)
-            return KDN_ERANGE;
+        if (total > (int64_t)q.table_len * cache->block_size || total > 0x7fffffff)
+            return KDN_ERANGE; // token indices are 32-bit in the kernels
     }
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *ds = device_state(nullptr);

@@ -125,6 +125,8 @@ def lib() -> C.CDLL:
         L.kdn_staging_bytes.argtypes = [C.POINTER(ChunkDesc), i32, i32]
         L.kdn_rope_prepare.restype = C.c_int
         L.kdn_rope_prepare.argtypes = [C.c_double, i32, C.POINTER(i32), i32]
+        L.kdn_rope_prepare_spec.restype = C.c_int
+        L.kdn_rope_prepare_spec.argtypes = [C.POINTER(RopeSpecDesc), i32, C.POINTER(i32), i32]
         L.kdn_validate_block_table.restype = C.c_int
         L.kdn_validate_block_table.argtypes = [vp, i32, i32, vp]
         L.kdn_f32_to_bf16.restype = C.c_int
@@ -143,7 +145,7 @@ def lib() -> C.CDLL:
 EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk", "kdn_store_tokens",
            "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_rope",
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host",
-           "kdn_staging_bytes", "kdn_rope_prepare",
+           "kdn_staging_bytes", "kdn_rope_prepare", "kdn_rope_prepare_spec",
            "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version", "kdn_pool_create", "kdn_pool_destroy", "kdn_pool_hash", "kdn_pool_lookup",
            "kdn_pool_insert", "kdn_pool_remove", "kdn_pool_get_stats"]
@@ -421,6 +423,12 @@ def kdn_compose_from_host(chunks, offsets, cache: PagedCache, block_table: torch
 def kdn_rope_prepare(rope_base: float, head_dim: int, offsets) -> None:
     off = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
     _check(lib().kdn_rope_prepare(float(rope_base), head_dim, off, len(offsets)), "kdn_rope_prepare")
+
+
+def kdn_rope_prepare_spec(spec, head_dim: int, offsets) -> None:
+    """spec: the pair returned by rope_spec()."""
+    off = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
+    _check(lib().kdn_rope_prepare_spec(C.byref(spec[0]), head_dim, off, len(offsets)), "kdn_rope_prepare_spec")
 
 
 def kdn_validate_block_table(block_table: torch.Tensor, num_blocks: int, stream=None) -> int:

@@ -453,6 +453,7 @@ def test_compose_rope_default_spec_is_compose():
     O.compose([ch], [33], hd, b, 10000.0, dest=4)
     kdn.kdn_compose_rope([chunk_to_dev(ch)], [33], dd, dev_table(b), kdn.rope_spec(10000.0), dest_token_start=4)
     assert_cache_equal(dd, hd)
+    kdn.kdn_rope_prepare_spec(kdn.rope_spec(10000.0, None, 32, 1), D, [1, 2, 3])
     bad = kdn.rope_spec(10000.0, None, 24, 0)                 # rot_dim not a multiple of 16
     with pytest.raises(kdn.KdnError) as e:
         kdn.kdn_compose_rope([chunk_to_dev(ch)], [33], dd, dev_table(b), bad)

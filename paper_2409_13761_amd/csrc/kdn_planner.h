@@ -15,9 +15,9 @@
 
 namespace kdn_impl {
 
-// Resolved RoPE variant of one call: frequencies either derived from `base` or given.
 constexpr int kFormats = 4; // kdn_format values
 
+// Resolved RoPE variant of one call: frequencies either derived from `base` or given.
 struct RopeSpec {
     double base = 0.0;
     std::vector<double> freq; // rot/2 explicit frequencies, empty: base^(-2j/rot)
@@ -49,12 +49,12 @@ struct DeviceState {
     bool drained_valid[2] = {};
 };
 
-std::mutex g_mu;
-std::unordered_map<int, DeviceState> g_dev;
+inline std::mutex g_mu; // guards g_dev and everything in it
+inline std::unordered_map<int, DeviceState> g_dev;
 
-bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-kdn_status check_shape(int32_t L, int32_t H, int32_t D)
+inline kdn_status check_shape(int32_t L, int32_t H, int32_t D)
 {
     if (L <= 0 || H <= 0 || D <= 0 || L > 32767)
         return KDN_EINVAL;
@@ -63,7 +63,7 @@ kdn_status check_shape(int32_t L, int32_t H, int32_t D)
     return KDN_OK;
 }
 
-kdn_status check_cache(const kdn_cache_desc *c)
+inline kdn_status check_cache(const kdn_cache_desc *c)
 {
     if (!c || !c->k_base || !c->v_base)
         return KDN_EINVAL;
@@ -81,13 +81,13 @@ kdn_status check_cache(const kdn_cache_desc *c)
     return KDN_OK;
 }
 
-bool known_format(int32_t fmt)
+inline bool known_format(int32_t fmt)
 {
     return fmt == KDN_FMT_RAW_BF16 || fmt == KDN_FMT_INT8_ROWSCALE || fmt == KDN_FMT_INT4_GROUP32
            || fmt == KDN_FMT_FP8_ROWSCALE;
 }
 
-kdn_status check_chunk(const kdn_chunk *ch, const kdn_cache_desc *c)
+inline kdn_status check_chunk(const kdn_chunk *ch, const kdn_cache_desc *c)
 {
     if (!ch || !ch->data)
         return KDN_EINVAL;
@@ -110,7 +110,7 @@ kdn_status check_chunk(const kdn_chunk *ch, const kdn_cache_desc *c)
     return KDN_OK;
 }
 
-CacheP make_cache_p(const kdn_cache_desc *c)
+inline CacheP make_cache_p(const kdn_cache_desc *c)
 {
     CacheP p;
     p.k = static_cast<uint16_t *>(c->k_base);
@@ -131,11 +131,11 @@ CacheP make_cache_p(const kdn_cache_desc *c)
 }
 
 // number of token groups touched by tokens [s, s+t)
-int64_t groups_spanned(int64_t s, int64_t t, int32_t G) { return (s + t - 1) / G - s / G + 1; }
+inline int64_t groups_spanned(int64_t s, int64_t t, int32_t G) { return (s + t - 1) / G - s / G + 1; }
 
-kdn_status hip_status(hipError_t e) { return e == hipSuccess ? KDN_OK : KDN_EDEVICE; }
+inline kdn_status hip_status(hipError_t e) { return e == hipSuccess ? KDN_OK : KDN_EDEVICE; }
 
-DeviceState *device_state(int *dev_out)
+inline DeviceState *device_state(int *dev_out)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess)
@@ -147,7 +147,7 @@ DeviceState *device_state(int *dev_out)
 
 // Validates a caller's RoPE variant for head_dim D.  NULL selects the default
 // (all of D rotary, half-split pairs, frequencies from `base`).
-kdn_status resolve_spec(const kdn_rope_spec *in, double base, int32_t D, RopeSpec &out)
+inline kdn_status resolve_spec(const kdn_rope_spec *in, double base, int32_t D, RopeSpec &out)
 {
     out = RopeSpec();
     out.base = in ? in->base : base;
@@ -170,8 +170,8 @@ kdn_status resolve_spec(const kdn_rope_spec *in, double base, int32_t D, RopeSpe
 
 // Returns the cos/sin table of the variant and fills rows[i] for offsets[i] (-1 for a
 // zero offset).  New rows are computed in double and uploaded before returning.
-kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t *offsets, int32_t n,
-                     int32_t *rows, const f32x2 **table)
+inline kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t *offsets, int32_t n,
+                            int32_t *rows, const f32x2 **table)
 {
     *table = nullptr;
     bool any = false;
@@ -331,8 +331,8 @@ void launch_place_d(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs
 
 // Enqueue the placement of `segs` (all of one format).  Up to kMaxInlineSegs travel
 // in the kernel arguments; more go through a ring of device tables.
-kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const std::vector<Seg> &segs,
-                          hipStream_t st)
+inline kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const std::vector<Seg> &segs,
+                                 hipStream_t st)
 {
     if (segs.empty())
         return KDN_OK;
@@ -387,8 +387,8 @@ kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const s
     return rc;
 }
 
-kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
-                        double rope_base, const kdn_rope_spec *variant, void *stream)
+inline kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
+                               double rope_base, const kdn_rope_spec *variant, void *stream)
 {
     if (!reqs || n_reqs <= 0)
         return KDN_EINVAL;
@@ -477,8 +477,8 @@ struct HostParent {
     int32_t fmt, L, H, D, Tp, lo, hi;
 };
 
-void plan_host_parents(const kdn_chunk *chunks, int32_t n, std::vector<HostParent> &parents,
-                       std::vector<int32_t> &parent_of)
+inline void plan_host_parents(const kdn_chunk *chunks, int32_t n, std::vector<HostParent> &parents,
+                              std::vector<int32_t> &parent_of)
 {
     parents.clear();
     parent_of.assign((size_t)n, 0);

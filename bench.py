@@ -187,7 +187,7 @@ def workload_8b(args, dev):
         "traffic": counter_traffic() if args.fmt == "int8" else None,
     }
     if not args.no_cpu_baseline and args.fmt == "int8":
-        res["cpu_baseline"] = cpu_baseline(cache, sets[0][0], order, offsets, w.rope_base, T, n_slices,
+        res["cpu_baseline"] = cpu_baseline(kdn, cache, sets[0], order, offsets, w.rope_base, T, n_slices,
                                            args.cpu_steps)
     return res
 
@@ -456,14 +456,17 @@ def workload_pool_trace(args, dev):
     }
 
 
-def cpu_baseline(cache, src, order, offsets, base, T, n_slices, steps):  # noqa: C901
+def cpu_baseline(kdn, cache, buf_set, order, offsets, base, T, n_slices, steps):
     """The oracle as it stands, on the host cores: the same step (store, load, compose
-    of one 4096-token context, all layers), layers split over threads."""
+    of one 4096-token context, all layers), layers split over threads; once more on one
+    thread; and, untimed, a comparison of one coherent GPU pass (store -> load -> compose
+    of this buffer set) with what the oracle computed from the same source blocks."""
     import numpy as np
     import torch
     from oracle import kdn_oracle as O
 
     L, nb, bs, H, D = cache.shape
+    src, dst_a, dst_b, gpu_chunk, gpu_slices = buf_set
     blocks = T // bs
     # host copy of the source blocks only; destination blocks start as zeros
     hk = np.zeros((L, 3 * blocks, bs, H, D), dtype=np.uint16)
@@ -477,7 +480,6 @@ def cpu_baseline(cache, src, order, offsets, base, T, n_slices, steps):  # noqa:
     chunk = O.Chunk(np.zeros(O.chunk_bytes(L, H, D, T, O.FMT_INT8_ROWSCALE), dtype=np.uint8),
                     O.FMT_INT8_ROWSCALE, L, H, D, T)
     cores = max(1, min(len(os.sched_getaffinity(0)), 16, L))
-    bounds = [(L * i // cores, L * (i + 1) // cores) for i in range(cores)]
     slices = [chunk.slice(int(i) * (T // n_slices), T // n_slices) for i in order]
 
     def work(lr):
@@ -485,18 +487,46 @@ def cpu_baseline(cache, src, order, offsets, base, T, n_slices, steps):  # noqa:
         O.load(chunk, host, t_a, 0, layers=lr)
         O.compose(slices, offsets, host, t_b, base, layers=lr)
 
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        th = [threading.Thread(target=work, args=(b,)) for b in bounds]
-        for t in th:
-            t.start()
-        for t in th:
-            t.join()
-    dt = time.perf_counter() - t0
+    def run(n_threads, n_steps):
+        bounds = [(L * i // n_threads, L * (i + 1) // n_threads) for i in range(n_threads)]
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            th = [threading.Thread(target=work, args=(b,)) for b in bounds]
+            for t in th:
+                t.start()
+            for t in th:
+                t.join()
+        return time.perf_counter() - t0
+
+    dt = run(cores, steps)
+    dt1 = run(1, 1)
+
+    # one coherent pass of the HIP path on the same buffer set, compared with the oracle's result
+    kdn.kdn_store_chunk(cache, src, 0, T, gpu_chunk)
+    kdn.kdn_load_chunk(gpu_chunk, cache, dst_a, 0)
+    kdn.kdn_compose(gpu_slices, offsets, cache, dst_b, base)
+    torch.cuda.synchronize()
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    def f64(b):
+        return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+    parity = {"stored_chunk_equal": bool(np.array_equal(gpu_chunk.data.cpu().numpy(), chunk.data))}
+    gk_a, gv_a = bits(cache.k[:, dst_a.long()]), bits(cache.v[:, dst_a.long()])
+    gk_b, gv_b = bits(cache.k[:, dst_b.long()]), bits(cache.v[:, dst_b.long()])
+    parity["load_equal"] = bool(np.array_equal(gk_a, hk[:, blocks:2 * blocks])
+                                and np.array_equal(gv_a, hv[:, blocks:2 * blocks]))
+    parity["compose_v_equal"] = bool(np.array_equal(gv_b, hv[:, 2 * blocks:]))
+    want_k = hk[:, 2 * blocks:]
+    parity["compose_k_differing_elements"] = int(np.count_nonzero(gk_b != want_k))
+    parity["compose_k_max_abs_diff"] = float(np.max(np.abs(f64(gk_b) - f64(want_k))))
     return {"value": T * steps / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "sample": "%d full steps of the same workload (store+load+compose of 4096 tokens, "
                       "all %d layers), layers split over %d threads" % (steps, L, cores),
-            "seconds": dt}
+            "seconds": dt, "single_thread_value": T / dt1,
+            "parity_of_one_gpu_pass": parity}
 
 
 def main() -> int:

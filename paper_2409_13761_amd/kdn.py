@@ -75,7 +75,7 @@ def lib() -> C.CDLL:
             raise ImportError("libkdn.so is not built: run `python -m paper_2409_13761_amd.build` "
                               "(there is no fallback path)")
         L = C.CDLL(LIB_PATH)
-        vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
+        vp, i32, u64 = C.c_void_p, C.c_int32, C.c_uint64
         L.kdn_chunk_bytes.restype = u64
         L.kdn_chunk_bytes.argtypes = [i32, i32, i32, i32, i32]
         L.kdn_chunk_init.restype = C.c_int
@@ -137,7 +137,6 @@ def lib() -> C.CDLL:
         L.kdn_status_str.argtypes = [C.c_int]
         L.kdn_version.restype = C.c_char_p
         L.kdn_version.argtypes = []
-        _ = i64
         _lib = L
     return _lib
 

@@ -330,9 +330,10 @@ def workload_batched(args, dev):
 
 
 def workload_host_stream(args, dev, fmt_name):
-    """A 4096-token chunk that lives in pinned host memory is composed as 8 shifted slices:
-    the stored rows cross PCIe in their compact form, 4 layers per stage, while the previous
-    stage is dequantised and scattered.  The rate is link bound (PCIe-inclusive)."""
+    """A 4096-token context is stored into pinned host memory and composed back from there as
+    8 shifted slices: in both directions the stored rows cross PCIe in their compact form,
+    4 layers per stage, while the neighbouring stage is quantised (store) or dequantised and
+    scattered (compose).  The rates are link bound (PCIe-inclusive)."""
     import torch
     from paper_2409_13761_amd import kdn, synth
 
@@ -359,25 +360,29 @@ def workload_host_stream(args, dev, fmt_name):
     slices = [host.slice(int(i) * (T // n_slices), T // n_slices) for i in order]
     offsets = [int(j * (T // n_slices)) for j in range(n_slices)]
     lps = 4
-    staging = torch.empty(kdn.kdn_staging_bytes(slices, lps), dtype=torch.uint8, device=dev)
+    staging = torch.empty(max(kdn.kdn_staging_bytes(slices, lps), kdn.kdn_store_staging_bytes(cache, T, fmt, lps)),
+                          dtype=torch.uint8, device=dev)
     kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
     dsts = (dst_a, dst_b)
 
     def step(i, rec):
+        # the host chunk is rewritten with the same bytes it already holds
+        rec("store_to_host", lambda: kdn.kdn_store_to_host(cache, src, 0, T, host, staging, lps))
         rec("compose_from_host", lambda: kdn.kdn_compose_from_host(
             slices, offsets, cache, dsts[i % 2], w.rope_base, staging, lps))
 
-    wall, ms = Timed(("compose_from_host",), args.steps).run(step, args.warmup)
+    wall, ms = Timed(("store_to_host", "compose_from_host"), args.steps).run(step, args.warmup)
     stored = T * (sh.int8_bytes_per_token if fmt_name == "int8" else sh.paged_bytes_per_token)
+    moved = stored + T * sh.paged_bytes_per_token
     return {
         "tokens_per_step": T, "wall": wall, "ms": ms,
-        "bytes": {"compose_from_host": stored + T * sh.paged_bytes_per_token},
+        "bytes": {"store_to_host": moved, "compose_from_host": moved},
         "place_calls": ("compose_from_host",),
-        "workload": "Llama-3-8B-shaped KV: one 4096-token %s chunk in pinned host memory composed as "
-                    "8x512-token shifted slices, %d layers per stage (PCIe-inclusive, link bound)"
-                    % (fmt_name, lps),
-        "extra": {"stored_bytes_over_link": stored,
-                  "link_GBps": stored / (ms["compose_from_host"] * 1e-3) / 1e9},
+        "workload": "Llama-3-8B-shaped KV: 4096 tokens stored as one %s chunk into pinned host memory and "
+                    "composed back from there as 8x512-token shifted slices, %d layers per stage "
+                    "(PCIe-inclusive, link bound)" % (fmt_name, lps),
+        "extra": {"stored_bytes_over_link_each_way": stored,
+                  "link_GBps": {n: stored / (ms[n] * 1e-3) / 1e9 for n in ms}},
         "traffic": None,
     }
 

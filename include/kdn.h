@@ -196,6 +196,24 @@ kdn_status kdn_store_tokens(const kdn_cache_desc *cache, const int32_t *block_ta
                             int32_t table_len, const int32_t *tokens_dev, int32_t num_tokens,
                             kdn_chunk *out, void *stream);
 
+/* Store into pinned HOST memory: the way out of the engine toward the storage device
+ * (Sec. 3.1, storage module; CPU memory as the KV store, Sec. 3 "Limited storage").
+ * out_host->data: [host], allocated with hipHostMalloc (or a pinned torch tensor), at
+ * least kdn_chunk_bytes(...) bytes; in: data, bytes, fmt; out: the other fields.  The
+ * kernels write layers_per_stage layers at a time, already in the stored form, into
+ * staging_dev [device, 16-byte aligned, kdn_store_staging_bytes(...) bytes], and a copy
+ * stream the library owns moves each stage to the host while the next is produced.  The
+ * host chunk is complete once `stream` has been synchronised.  Same bytes as
+ * kdn_store_chunk followed by a device-to-host copy. */
+kdn_status kdn_store_to_host(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                             int32_t table_len, int32_t token_start, int32_t num_tokens,
+                             kdn_chunk *out_host, void *staging_dev, uint64_t staging_bytes,
+                             int32_t layers_per_stage, void *stream);
+
+/* Staging bytes kdn_store_to_host needs (two stages); 0 on invalid arguments. */
+uint64_t kdn_store_staging_bytes(const kdn_cache_desc *cache, int32_t num_tokens, int32_t fmt,
+                                 int32_t layers_per_stage);
+
 /* Load (Sec. 3.2, interface (ii); decompression on the GPU, Sec. 3.1).  Writes the
  * chunk view's tokens to request tokens [dest_token_start, dest_token_start +
  * chunk->num_tokens) of the paged cache.  No rotation.  Slots and blocks outside
@@ -262,6 +280,27 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
  * copy of the token range they span; each copy is padded to 256 bytes.  0 on invalid
  * arguments.  chunks: [host] array; the data they point to is not read. */
 uint64_t kdn_staging_bytes(const kdn_chunk *chunks, int32_t n_chunks, int32_t layers_per_stage);
+
+/* The link transfers of one stage of kdn_compose_from_host, for callers that account for
+ * link bytes or want to check a plan before running it.  Host only: no device is touched
+ * and the chunks' data is not read (any non-null pointer serves).  Stage s covers layers
+ * [s*layers_per_stage, min(L, (s+1)*layers_per_stage)).  One kdn_stage_copy is `rows` runs
+ * of `width` bytes that lie `src_pitch` apart starting `src_offset` bytes into the data of
+ * chunks[chunk] (the first view of that host buffer), packed back to back from
+ * `dst_offset` of the stage's staging half.  The staged image of a host buffer is a stored
+ * chunk of the stage's layers and the token range its views span; view_offsets[i] ([host]
+ * array of n_chunks, may be null) is where the image that chunks[i] reads starts.
+ * copies_out: [host] array of `cap` records; *n_copies receives the count (cap 0 asks for
+ * the count alone).  KDN_ERANGE when the stage is past the last layer, KDN_ESIZE when cap
+ * is too small or a chunk's bytes do not cover its layout. */
+typedef struct kdn_stage_copy {
+    int32_t chunk;
+    int32_t rows;
+    uint64_t src_offset, src_pitch, width, dst_offset;
+} kdn_stage_copy;
+kdn_status kdn_host_stage_plan(const kdn_chunk *chunks, int32_t n_chunks, int32_t layers_per_stage,
+                               int32_t stage, kdn_stage_copy *copies_out, int32_t cap, int32_t *n_copies,
+                               uint64_t *view_offsets);
 
 /* Make the cos/sin rows of the given offsets resident so that later composes with
  * them enqueue no copy (needed before capturing composes into a HIP graph).

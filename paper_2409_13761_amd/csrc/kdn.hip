@@ -68,9 +68,10 @@ kdn_status kdn_chunk_slice(const kdn_chunk *chunk, int32_t token_start, int32_t 
     return KDN_OK;
 }
 
-static kdn_status store_impl(const kdn_cache_desc *cache, const int32_t *block_table_dev,
-                             int32_t table_len, int32_t token_start, int32_t num_tokens,
-                             const int32_t *tokens_dev, kdn_chunk *out, void *stream)
+// Validates a store request (shared by the device and host destinations).
+static kdn_status store_check(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                              int32_t table_len, int32_t token_start, int32_t num_tokens,
+                              const int32_t *tokens_dev, const kdn_chunk *out)
 {
     kdn_status st = check_cache(cache);
     if (st != KDN_OK)
@@ -90,38 +91,65 @@ static kdn_status store_impl(const kdn_cache_desc *cache, const int32_t *block_t
                                           num_tokens, out->fmt);
     if (out->bytes < need)
         return KDN_ESIZE;
+    return KDN_OK;
+}
+
+// Enqueues the store of layers [layer0, layer0 + n_layers) into `dst`, laid out as a chunk
+// of n_layers layers.
+static kdn_status store_launch(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                               int32_t table_len, int32_t token_start, int32_t num_tokens,
+                               const int32_t *tokens_dev, int32_t fmt, void *dst, int32_t layer0,
+                               int32_t n_layers, hipStream_t hs)
+{
     StoreP p;
     p.c = make_cache_p(cache);
+    p.c.L = n_layers;
+    p.layer0 = layer0;
     p.bt = block_table_dev;
-    p.out = static_cast<uint8_t *>(out->data);
+    p.out = static_cast<uint8_t *>(dst);
     p.t0 = token_start;
     p.T = num_tokens;
     p.tokens = tokens_dev;
-    p.limit = (int32_t)std::min<int64_t>(limit, 0x7fffffff);
+    p.limit = (int32_t)std::min<int64_t>((int64_t)table_len * cache->block_size, 0x7fffffff);
     if (tokens_dev)
         p.c.G = 16; // list entries need no block alignment
     const int64_t groups = groups_spanned(token_start, num_tokens, p.c.G);
     if (groups * 2 * p.c.L > 0x7fffffff / kThreads)
         return KDN_ESIZE;
     dim3 grid((unsigned)(groups * 2 * p.c.L), 1, 1);
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    if (out->fmt == KDN_FMT_RAW_BF16)
+    if (fmt == KDN_FMT_RAW_BF16)
         launch_store_d<KDN_FMT_RAW_BF16>(p, grid, hs);
-    else if (out->fmt == KDN_FMT_INT8_ROWSCALE)
+    else if (fmt == KDN_FMT_INT8_ROWSCALE)
         launch_store_d<KDN_FMT_INT8_ROWSCALE>(p, grid, hs);
-    else if (out->fmt == KDN_FMT_FP8_ROWSCALE)
+    else if (fmt == KDN_FMT_FP8_ROWSCALE)
         launch_store_d<KDN_FMT_FP8_ROWSCALE>(p, grid, hs);
     else
         launch_store_d<KDN_FMT_INT4_GROUP32>(p, grid, hs);
-    st = hip_status(hipGetLastError());
-    if (st != KDN_OK)
-        return st;
+    return hip_status(hipGetLastError());
+}
+
+static void describe_stored(const kdn_cache_desc *cache, int32_t num_tokens, kdn_chunk *out)
+{
     out->num_layers = cache->num_layers;
     out->num_kv_heads = cache->num_kv_heads;
     out->head_dim = cache->head_dim;
     out->parent_tokens = num_tokens;
     out->token_start = 0;
     out->num_tokens = num_tokens;
+}
+
+static kdn_status store_impl(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                             int32_t table_len, int32_t token_start, int32_t num_tokens,
+                             const int32_t *tokens_dev, kdn_chunk *out, void *stream)
+{
+    kdn_status st = store_check(cache, block_table_dev, table_len, token_start, num_tokens, tokens_dev, out);
+    if (st != KDN_OK)
+        return st;
+    st = store_launch(cache, block_table_dev, table_len, token_start, num_tokens, tokens_dev, out->fmt,
+                      out->data, 0, cache->num_layers, static_cast<hipStream_t>(stream));
+    if (st != KDN_OK)
+        return st;
+    describe_stored(cache, num_tokens, out);
     return KDN_OK;
 }
 
@@ -139,6 +167,95 @@ kdn_status kdn_store_tokens(const kdn_cache_desc *cache, const int32_t *block_ta
     if (!tokens_dev)
         return KDN_EINVAL;
     return store_impl(cache, block_table_dev, table_len, 0, num_tokens, tokens_dev, out, stream);
+}
+
+uint64_t kdn_store_staging_bytes(const kdn_cache_desc *cache, int32_t num_tokens, int32_t fmt,
+                                 int32_t layers_per_stage)
+{
+    if (!cache || layers_per_stage <= 0)
+        return 0;
+    const uint64_t b = kdn_chunk_bytes(std::min(layers_per_stage, cache->num_layers), cache->num_kv_heads,
+                                       cache->head_dim, num_tokens, fmt);
+    return b ? 2 * ((b + 255) & ~(uint64_t)255) : 0;
+}
+
+kdn_status kdn_store_to_host(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                             int32_t table_len, int32_t token_start, int32_t num_tokens,
+                             kdn_chunk *out_host, void *staging_dev, uint64_t staging_bytes,
+                             int32_t layers_per_stage, void *stream)
+{
+    kdn_status st = store_check(cache, block_table_dev, table_len, token_start, num_tokens, nullptr, out_host);
+    if (st != KDN_OK)
+        return st;
+    if (!staging_dev || layers_per_stage <= 0)
+        return KDN_EINVAL;
+    if (!aligned16(staging_dev))
+        return KDN_EALIGN;
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, out_host->data) != hipSuccess) {
+        (void)hipGetLastError();
+        return KDN_EINVAL; // ordinary pageable memory
+    }
+    if (attr.type != hipMemoryTypeHost)
+        return KDN_EINVAL;
+    const uint64_t need = kdn_store_staging_bytes(cache, num_tokens, out_host->fmt, layers_per_stage);
+    if (need == 0 || staging_bytes < need)
+        return KDN_ESIZE;
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *ds = device_state(nullptr);
+    if (!ds)
+        return KDN_EDEVICE;
+    st = ensure_copy_stream(ds);
+    if (st != KDN_OK)
+        return st;
+    hipStream_t user = static_cast<hipStream_t>(stream);
+    const int32_t L = cache->num_layers, H = cache->num_kv_heads, D = cache->head_dim, T = num_tokens;
+    const int32_t fmt = out_host->fmt;
+    // bytes of one layer's codes (K and V) and scales in the stored form
+    const uint64_t codes_l = (uint64_t)2 * T * H * row_code_bytes(fmt, D);
+    const uint64_t scales_l = (uint64_t)2 * T * H * row_scale_bytes(fmt, D);
+    const bool scaled = scales_l != 0;
+    uint8_t *staging = static_cast<uint8_t *>(staging_dev);
+    uint8_t *host = static_cast<uint8_t *>(out_host->data);
+    const uint64_t half_bytes = need / 2;
+    int stage_no = 0;
+    for (int32_t l0 = 0; l0 < L; l0 += layers_per_stage, ++stage_no) {
+        const int32_t Lg = std::min(layers_per_stage, L - l0);
+        const int b = stage_no & 1;
+        uint8_t *buf = staging + (uint64_t)b * half_bytes;
+        // the kernel may overwrite this half only after the copy that last read it
+        if (ds->drained_valid[b] && hipStreamWaitEvent(user, ds->drained[b], 0) != hipSuccess)
+            return KDN_EDEVICE;
+        if ((uint64_t)Lg * (codes_l + scales_l) > half_bytes
+            || (uint64_t)L * codes_l + (uint64_t)(l0 + Lg) * scales_l > out_host->bytes)
+            return KDN_ESIZE; // nothing may leave the staging half or the host buffer
+        st = store_launch(cache, block_table_dev, table_len, token_start, T, nullptr, fmt, buf, l0, Lg, user);
+        if (st != KDN_OK)
+            return st;
+        if (hipEventRecord(ds->filled[b], user) != hipSuccess
+            || hipStreamWaitEvent(ds->copy_stream, ds->filled[b], 0) != hipSuccess)
+            return KDN_EDEVICE;
+        // staged: codes of Lg layers, then their scales; both are contiguous runs of the host chunk
+        if (hipMemcpyAsync(host + (uint64_t)l0 * codes_l, buf, (uint64_t)Lg * codes_l, hipMemcpyDeviceToHost,
+                           ds->copy_stream)
+            != hipSuccess)
+            return KDN_EDEVICE;
+        if (scaled
+            && hipMemcpyAsync(host + (uint64_t)L * codes_l + (uint64_t)l0 * scales_l, buf + (uint64_t)Lg * codes_l,
+                              (uint64_t)Lg * scales_l, hipMemcpyDeviceToHost, ds->copy_stream)
+                   != hipSuccess)
+            return KDN_EDEVICE;
+        if (hipEventRecord(ds->drained[b], ds->copy_stream) != hipSuccess)
+            return KDN_EDEVICE;
+        ds->drained_valid[b] = true;
+    }
+    // the caller's stream completes only when the last copies have landed
+    for (int b = 0; b < 2; ++b)
+        if (ds->drained_valid[b] && hipStreamWaitEvent(user, ds->drained[b], 0) != hipSuccess)
+            return KDN_EDEVICE;
+    describe_stored(cache, num_tokens, out_host);
+    return KDN_OK;
 }
 
 kdn_status kdn_load_chunk(const kdn_chunk *chunk, const kdn_cache_desc *cache,
@@ -228,6 +345,58 @@ uint64_t kdn_staging_bytes(const kdn_chunk *chunks, int32_t n_chunks, int32_t la
     return 2 * stage;
 }
 
+kdn_status kdn_host_stage_plan(const kdn_chunk *chunks, int32_t n_chunks, int32_t layers_per_stage,
+                               int32_t stage, kdn_stage_copy *copies_out, int32_t cap, int32_t *n_copies,
+                               uint64_t *view_offsets)
+{
+    if (!chunks || n_chunks <= 0 || layers_per_stage <= 0 || stage < 0 || !n_copies || cap < 0
+        || (cap > 0 && !copies_out))
+        return KDN_EINVAL;
+    for (int32_t i = 0; i < n_chunks; ++i) {
+        const kdn_chunk &ch = chunks[i];
+        if (!ch.data || check_shape(ch.num_layers, ch.num_kv_heads, ch.head_dim) != KDN_OK || !known_format(ch.fmt)
+            || ch.num_layers != chunks[0].num_layers || ch.num_kv_heads != chunks[0].num_kv_heads
+            || ch.head_dim != chunks[0].head_dim)
+            return KDN_EINVAL;
+        if (ch.token_start < 0 || ch.num_tokens <= 0 || ch.parent_tokens <= 0
+            || (int64_t)ch.token_start + ch.num_tokens > ch.parent_tokens)
+            return KDN_ERANGE;
+        if (ch.bytes < kdn_chunk_bytes(ch.num_layers, ch.num_kv_heads, ch.head_dim, ch.parent_tokens, ch.fmt))
+            return KDN_ESIZE;
+    }
+    const int32_t L = chunks[0].num_layers;
+    const int64_t l0 = (int64_t)stage * layers_per_stage;
+    if (l0 >= L)
+        return KDN_ERANGE;
+    const uint64_t need = kdn_staging_bytes(chunks, n_chunks, layers_per_stage);
+    if (need == 0)
+        return KDN_ESIZE;
+    std::vector<HostParent> parents;
+    std::vector<int32_t> parent_of;
+    plan_host_parents(chunks, n_chunks, parents, parent_of);
+    std::vector<StageCopy> copies;
+    std::vector<uint64_t> staged_at;
+    kdn_status st = plan_stage_copies(parents, (int32_t)l0, std::min<int32_t>(layers_per_stage, L - (int32_t)l0),
+                                      need / 2, copies, staged_at);
+    if (st != KDN_OK)
+        return st;
+    *n_copies = (int32_t)copies.size();
+    if ((int32_t)copies.size() > cap)
+        return cap == 0 ? KDN_OK : KDN_ESIZE; // cap 0 asks for the count only
+    for (size_t c = 0; c < copies.size(); ++c) {
+        // name the first chunk that views the host buffer
+        int32_t first = 0;
+        while (parent_of[(size_t)first] != copies[c].parent)
+            ++first;
+        copies_out[c] = {first, (int32_t)copies[c].rows, copies[c].src_off, copies[c].src_pitch,
+                         copies[c].width, copies[c].dst_off};
+    }
+    if (view_offsets)
+        for (int32_t i = 0; i < n_chunks; ++i)
+            view_offsets[i] = staged_at[(size_t)parent_of[(size_t)i]];
+    return KDN_OK;
+}
+
 kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
                                  const kdn_cache_desc *cache, const int32_t *block_table_dev,
                                  int32_t table_len, int32_t dest_token_start, double rope_base,
@@ -269,14 +438,9 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
     DeviceState *ds = device_state(nullptr);
     if (!ds)
         return KDN_EDEVICE;
-    if (!ds->copy_stream) {
-        if (hipStreamCreateWithFlags(&ds->copy_stream, hipStreamNonBlocking) != hipSuccess)
-            return KDN_EDEVICE;
-        for (int b = 0; b < 2; ++b)
-            if (hipEventCreateWithFlags(&ds->filled[b], hipEventDisableTiming) != hipSuccess
-                || hipEventCreateWithFlags(&ds->drained[b], hipEventDisableTiming) != hipSuccess)
-                return KDN_EDEVICE;
-    }
+    st = ensure_copy_stream(ds);
+    if (st != KDN_OK)
+        return st;
     hipStream_t user = static_cast<hipStream_t>(stream);
     PlaceP p;
     p.c = make_cache_p(cache);
@@ -295,7 +459,8 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
     const int32_t L = cache->num_layers, H = cache->num_kv_heads, D = cache->head_dim;
     uint8_t *staging = static_cast<uint8_t *>(staging_dev);
     const uint64_t half_bytes = need / 2;
-    std::vector<uint8_t *> staged(parents.size());
+    std::vector<StageCopy> copies;
+    std::vector<uint64_t> staged_at;
     int stage_no = 0;
     for (int32_t l0 = 0; l0 < L; l0 += layers_per_stage, ++stage_no) {
         const int32_t Lg = std::min(layers_per_stage, L - l0);
@@ -304,40 +469,19 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
         // the copy may overwrite this half only after the kernel that last read it
         if (ds->drained_valid[b] && hipStreamWaitEvent(ds->copy_stream, ds->drained[b], 0) != hipSuccess)
             return KDN_EDEVICE;
-        uint64_t at = 0;
-        for (size_t k = 0; k < parents.size(); ++k) {
-            const HostParent &hp = parents[k];
-            const int32_t Tu = hp.hi - hp.lo, Tp = hp.Tp;
-            const uint64_t esz = hp.fmt == KDN_FMT_RAW_BF16 ? 2 : 1;
-            uint8_t *dst = buf + at;
-            staged[k] = dst;
-            // rows of layers [l0, l0+Lg), both sides, tokens [lo, hi) of this host buffer:
-            // 2*Lg planes of Tu*H*D elements, Tp*H*D apart
-            const uint64_t w_codes = (uint64_t)Tu * H * D * esz, pitch_codes = (uint64_t)Tp * H * D * esz;
-            const uint8_t *src_codes = hp.data + ((uint64_t)l0 * 2 * Tp + hp.lo) * H * D * esz;
+        st = plan_stage_copies(parents, l0, Lg, half_bytes, copies, staged_at);
+        if (st != KDN_OK)
+            return st;
+        for (const StageCopy &c : copies) {
+            const uint8_t *from = parents[(size_t)c.parent].data + c.src_off;
             hipError_t e;
-            if (Tu == Tp)
-                e = hipMemcpyAsync(dst, src_codes, w_codes * 2 * Lg, hipMemcpyHostToDevice, ds->copy_stream);
+            if (c.width == c.src_pitch) // whole chunk: the planes adjoin
+                e = hipMemcpyAsync(buf + c.dst_off, from, c.width * c.rows, hipMemcpyHostToDevice, ds->copy_stream);
             else
-                e = hipMemcpy2DAsync(dst, w_codes, src_codes, pitch_codes, w_codes, (size_t)2 * Lg,
+                e = hipMemcpy2DAsync(buf + c.dst_off, c.width, from, c.src_pitch, c.width, (size_t)c.rows,
                                      hipMemcpyHostToDevice, ds->copy_stream);
             if (e != hipSuccess)
                 return KDN_EDEVICE;
-            if (hp.fmt == KDN_FMT_INT8_ROWSCALE || hp.fmt == KDN_FMT_FP8_ROWSCALE) {
-                const uint64_t w_sc = (uint64_t)Tu * H * 4, pitch_sc = (uint64_t)Tp * H * 4;
-                const uint8_t *src_sc = hp.data + (uint64_t)L * 2 * Tp * H * D
-                                        + ((uint64_t)l0 * 2 * Tp + hp.lo) * H * 4;
-                uint8_t *dst_sc = dst + w_codes * 2 * Lg;
-                if (Tu == Tp)
-                    e = hipMemcpyAsync(dst_sc, src_sc, w_sc * 2 * Lg, hipMemcpyHostToDevice, ds->copy_stream);
-                else
-                    e = hipMemcpy2DAsync(dst_sc, w_sc, src_sc, pitch_sc, w_sc, (size_t)2 * Lg,
-                                         hipMemcpyHostToDevice, ds->copy_stream);
-                if (e != hipSuccess)
-                    return KDN_EDEVICE;
-            }
-            const uint64_t bytes = kdn_chunk_bytes(Lg, H, D, Tu, hp.fmt);
-            at += (bytes + 255) & ~(uint64_t)255;
         }
         std::vector<Seg> segs[kFormats];
         int32_t S = dest_token_start;
@@ -345,7 +489,7 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
             const kdn_chunk &ch = chunks[i];
             const HostParent &hp = parents[parent_of[i]];
             Seg s;
-            s.data = staged[parent_of[i]];
+            s.data = buf + staged_at[(size_t)parent_of[i]];
             s.bt = block_table_dev;
             s.Tp = hp.hi - hp.lo;
             s.tok0 = ch.token_start - hp.lo;

@@ -70,6 +70,7 @@ struct StoreP {
     int32_t t0, T;
     const int32_t *tokens; // token-list store: row t holds request token tokens[t]; else NULL
     int32_t limit;         // request tokens the block table covers (list entries are clamped to it)
+    int32_t layer0;        // cache layer that stored layer 0 comes from (c.L layers are stored)
 };
 
 struct PlaceP {
@@ -207,7 +208,7 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
         return;
     // a token list (strided instantiation only) resolves every row's token by itself
     const bool listed = !DENSE && p.tokens != nullptr;
-    const uint16_t *plane = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(ls >> 1) * p.c.layer_stride;
+    const uint16_t *plane = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(p.layer0 + (ls >> 1)) * p.c.layer_stride;
     const int blk = listed ? 0 : p.bt[tok_lo / bs];
     const int slot0 = listed ? 0 : tok_lo % bs;
     const uint16_t *tile = plane + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;

@@ -145,6 +145,20 @@ inline DeviceState *device_state(int *dev_out)
     return &g_dev[dev];
 }
 
+// The stream and events behind the host-memory paths, created on first use.
+inline kdn_status ensure_copy_stream(DeviceState *ds)
+{
+    if (ds->copy_stream)
+        return KDN_OK;
+    if (hipStreamCreateWithFlags(&ds->copy_stream, hipStreamNonBlocking) != hipSuccess)
+        return KDN_EDEVICE;
+    for (int b = 0; b < 2; ++b)
+        if (hipEventCreateWithFlags(&ds->filled[b], hipEventDisableTiming) != hipSuccess
+            || hipEventCreateWithFlags(&ds->drained[b], hipEventDisableTiming) != hipSuccess)
+            return KDN_EDEVICE;
+    return KDN_OK;
+}
+
 // Validates a caller's RoPE variant for head_dim D.  NULL selects the default
 // (all of D rotary, half-split pairs, frequencies from `base`).
 inline kdn_status resolve_spec(const kdn_rope_spec *in, double base, int32_t D, RopeSpec &out)
@@ -470,10 +484,21 @@ inline kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kd
     return KDN_OK;
 }
 
+// bytes of one stored row's codes, and of its scales, per format
+inline uint64_t row_code_bytes(int32_t fmt, int32_t D)
+{
+    return fmt == KDN_FMT_RAW_BF16 ? (uint64_t)D * 2 : fmt == KDN_FMT_INT4_GROUP32 ? (uint64_t)D / 2 : (uint64_t)D;
+}
+inline uint64_t row_scale_bytes(int32_t fmt, int32_t D)
+{
+    return fmt == KDN_FMT_RAW_BF16 ? 0 : fmt == KDN_FMT_INT4_GROUP32 ? (uint64_t)(D / 32) * 4 : 4;
+}
+
 // Views of the same host buffer are staged once: the token range [lo, hi) that the
 // views of one buffer span crosses the link as one copy per stage.
 struct HostParent {
     const uint8_t *data;
+    uint64_t bytes; // size of the host buffer
     int32_t fmt, L, H, D, Tp, lo, hi;
 };
 
@@ -489,12 +514,55 @@ inline void plan_host_parents(const kdn_chunk *chunks, int32_t n, std::vector<Ho
             if (parents[k].data == ch.data && parents[k].fmt == ch.fmt && parents[k].Tp == ch.parent_tokens)
                 break;
         if (k == parents.size())
-            parents.push_back({static_cast<const uint8_t *>(ch.data), ch.fmt, ch.num_layers, ch.num_kv_heads,
-                               ch.head_dim, ch.parent_tokens, ch.token_start, ch.token_start + ch.num_tokens});
+            parents.push_back({static_cast<const uint8_t *>(ch.data), ch.bytes, ch.fmt, ch.num_layers,
+                               ch.num_kv_heads, ch.head_dim, ch.parent_tokens, ch.token_start,
+                               ch.token_start + ch.num_tokens});
+        parents[k].bytes = std::min<uint64_t>(parents[k].bytes, ch.bytes);
         parents[k].lo = std::min(parents[k].lo, ch.token_start);
         parents[k].hi = std::max(parents[k].hi, ch.token_start + ch.num_tokens);
         parent_of[(size_t)i] = (int32_t)k;
     }
+}
+
+// The copies of one stage (cache layers [l0, l0+Lg)) of a compose from host memory.  Per host
+// buffer: 2*Lg planes of Tu*H rows, Tp*H rows apart, once for the codes and (if the form has
+// any) once for the scales, packed back to back; the staged image is a chunk of Lg layers and
+// Tu tokens.  `staged_at[k]` is where buffer k's image starts within the staging half.  Every
+// copy is checked to stay inside its host buffer and inside `half_bytes` of staging.
+struct StageCopy {
+    int32_t parent;
+    uint64_t rows, src_off, src_pitch, width, dst_off;
+};
+
+inline kdn_status plan_stage_copies(const std::vector<HostParent> &parents, int32_t l0, int32_t Lg,
+                                    uint64_t half_bytes, std::vector<StageCopy> &copies,
+                                    std::vector<uint64_t> &staged_at)
+{
+    copies.clear();
+    staged_at.assign(parents.size(), 0);
+    uint64_t at = 0;
+    for (size_t k = 0; k < parents.size(); ++k) {
+        const HostParent &hp = parents[k];
+        if (l0 < 0 || Lg <= 0 || l0 + Lg > hp.L || hp.lo < 0 || hp.hi <= hp.lo || hp.hi > hp.Tp)
+            return KDN_ERANGE;
+        const uint64_t Tu = (uint64_t)(hp.hi - hp.lo), Tp = (uint64_t)hp.Tp, H = (uint64_t)hp.H;
+        const uint64_t cb = row_code_bytes(hp.fmt, hp.D), sb = row_scale_bytes(hp.fmt, hp.D);
+        const uint64_t planes = (uint64_t)2 * Lg;
+        const uint64_t first_row = (uint64_t)l0 * 2 * Tp + (uint64_t)hp.lo; // in units of H rows
+        staged_at[k] = at;
+        StageCopy c = {(int32_t)k, planes, first_row * H * cb, Tp * H * cb, Tu * H * cb, at};
+        StageCopy s = {(int32_t)k, planes, (uint64_t)hp.L * 2 * Tp * H * cb + first_row * H * sb, Tp * H * sb,
+                       Tu * H * sb, at + planes * c.width};
+        if (s.dst_off + planes * s.width > half_bytes
+            || c.src_off + (planes - 1) * c.src_pitch + c.width > hp.bytes
+            || (sb && s.src_off + (planes - 1) * s.src_pitch + s.width > hp.bytes))
+            return KDN_ESIZE;
+        copies.push_back(c);
+        if (sb)
+            copies.push_back(s);
+        at += (planes * (c.width + s.width) + 255) & ~(uint64_t)255;
+    }
+    return KDN_OK;
 }
 
 } // namespace kdn_impl

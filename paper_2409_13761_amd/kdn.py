@@ -86,6 +86,11 @@ def lib() -> C.CDLL:
         L.kdn_store_chunk.argtypes = [C.POINTER(CacheDesc), vp, i32, i32, i32, C.POINTER(ChunkDesc), vp]
         L.kdn_store_tokens.restype = C.c_int
         L.kdn_store_tokens.argtypes = [C.POINTER(CacheDesc), vp, i32, vp, i32, C.POINTER(ChunkDesc), vp]
+        L.kdn_store_to_host.restype = C.c_int
+        L.kdn_store_to_host.argtypes = [C.POINTER(CacheDesc), vp, i32, i32, i32, C.POINTER(ChunkDesc),
+                                        vp, u64, i32, vp]
+        L.kdn_store_staging_bytes.restype = u64
+        L.kdn_store_staging_bytes.argtypes = [C.POINTER(CacheDesc), i32, i32, i32]
         L.kdn_load_chunk.restype = C.c_int
         L.kdn_load_chunk.argtypes = [C.POINTER(ChunkDesc), C.POINTER(CacheDesc), vp, i32, i32, vp]
         L.kdn_compose.restype = C.c_int
@@ -123,6 +128,8 @@ def lib() -> C.CDLL:
                                             vp, u64, i32, vp]
         L.kdn_staging_bytes.restype = u64
         L.kdn_staging_bytes.argtypes = [C.POINTER(ChunkDesc), i32, i32]
+        L.kdn_host_stage_plan.restype = C.c_int
+        L.kdn_host_stage_plan.argtypes = [C.POINTER(ChunkDesc), i32, i32, i32, vp, i32, C.POINTER(i32), vp]
         L.kdn_rope_prepare.restype = C.c_int
         L.kdn_rope_prepare.argtypes = [C.c_double, i32, C.POINTER(i32), i32]
         L.kdn_rope_prepare_spec.restype = C.c_int
@@ -142,9 +149,10 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk", "kdn_store_tokens",
+           "kdn_store_to_host", "kdn_store_staging_bytes",
            "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_rope",
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host",
-           "kdn_staging_bytes", "kdn_rope_prepare", "kdn_rope_prepare_spec",
+           "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec",
            "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version", "kdn_pool_create", "kdn_pool_destroy", "kdn_pool_hash", "kdn_pool_lookup",
            "kdn_pool_insert", "kdn_pool_remove", "kdn_pool_get_stats"]
@@ -295,6 +303,35 @@ def kdn_store_tokens(cache: PagedCache, block_table: torch.Tensor, tokens: torch
     return out
 
 
+def alloc_host_chunk(cache: PagedCache, num_tokens: int, fmt: int) -> Chunk:
+    """A chunk buffer in pinned host memory (a pinned torch tensor)."""
+    L, _, _, H, D = cache.shape
+    n = kdn_chunk_bytes(L, H, D, num_tokens, fmt)
+    if n == 0:
+        raise KdnError(EINVAL, "kdn_chunk_bytes")
+    data = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    d = ChunkDesc()
+    _check(lib().kdn_chunk_init(C.byref(d), data.data_ptr(), n, fmt, L, H, D, num_tokens), "kdn_chunk_init")
+    return Chunk(data, d)
+
+
+def kdn_store_staging_bytes(cache: PagedCache, num_tokens: int, fmt: int, layers_per_stage: int) -> int:
+    cd = cache.desc()
+    return int(lib().kdn_store_staging_bytes(C.byref(cd), num_tokens, fmt, layers_per_stage))
+
+
+def kdn_store_to_host(cache: PagedCache, block_table: torch.Tensor, token_start: int, num_tokens: int,
+                      out_host: Chunk, staging: torch.Tensor, layers_per_stage: int, stream=None) -> Chunk:
+    assert block_table.dtype == torch.int32 and block_table.is_contiguous()
+    assert staging.is_cuda and staging.is_contiguous() and not out_host.data.is_cuda
+    cd = cache.desc()
+    _check(lib().kdn_store_to_host(C.byref(cd), block_table.data_ptr(), block_table.numel(), token_start,
+                                   num_tokens, C.byref(out_host.desc), staging.data_ptr(),
+                                   staging.numel() * staging.element_size(), layers_per_stage,
+                                   _stream(stream)), "kdn_store_to_host")
+    return out_host
+
+
 def kdn_load_chunk(chunk: Chunk, cache: PagedCache, block_table: torch.Tensor,
                    dest_token_start: int = 0, stream=None) -> None:
     assert block_table.dtype == torch.int32 and block_table.is_contiguous()
@@ -403,6 +440,24 @@ def pinned_host_copy(chunk: Chunk) -> Chunk:
 
 def kdn_staging_bytes(chunks, layers_per_stage: int) -> int:
     return int(lib().kdn_staging_bytes(_chunk_array(chunks), len(chunks), layers_per_stage))
+
+
+class StageCopyDesc(C.Structure):
+    _fields_ = [("chunk", C.c_int32), ("rows", C.c_int32), ("src_offset", C.c_uint64),
+                ("src_pitch", C.c_uint64), ("width", C.c_uint64), ("dst_offset", C.c_uint64)]
+
+
+def kdn_host_stage_plan(chunks, layers_per_stage: int, stage: int):
+    """(copies, view_offsets): the link transfers of one stage and where each view's staged
+    image starts; each copy is a dict of the C record's fields."""
+    arr, n = _chunk_array(chunks), C.c_int32(0)
+    _check(lib().kdn_host_stage_plan(arr, len(chunks), layers_per_stage, stage, None, 0, C.byref(n), None),
+           "kdn_host_stage_plan")
+    out = (StageCopyDesc * n.value)()
+    views = (C.c_uint64 * len(chunks))()
+    _check(lib().kdn_host_stage_plan(arr, len(chunks), layers_per_stage, stage, out, n.value, C.byref(n), views),
+           "kdn_host_stage_plan")
+    return ([{f: getattr(c, f) for f, _ in StageCopyDesc._fields_} for c in out], list(views))
 
 
 def kdn_compose_from_host(chunks, offsets, cache: PagedCache, block_table: torch.Tensor,

@@ -376,22 +376,23 @@ def test_rope_prepare_then_compose_and_shutdown_are_repeatable():
 # ------------------------------------------------------------------ chunks streamed from host memory
 @pytest.mark.parametrize("layers_per_stage", [1, 2, 3, 8])
 def test_compose_from_pinned_host_chunks_equals_compose(layers_per_stage):
-    """Stored chunks (int8 and raw, whole and sliced) that live in pinned host memory are
+    """Stored chunks (every format, whole and sliced) that live in pinned host memory are
     streamed in stages of layers; the result is the oracle's compose."""
     L, nb, bs, H, D = 5, 64, 16, 2, 64
     _say("compose_from_host layers_per_stage=%d" % layers_per_stage)
     src = host_cache(71, L, nb, bs, H, D)
-    t1, t2, t3, dst_bt = synth.disjoint_block_tables(71, nb, [6, 5, 4, 20])
+    t1, t2, t3, t4, dst_bt = synth.disjoint_block_tables(71, nb, [6, 5, 4, 4, 24])
     a = O.store(src, t1, 0, 90, INT8)
     b = O.store(src, t2, 3, 70, RAW)
-    c = O.store(src, t3, 0, 64, INT8)
-    chunks = [a.slice(10, 75), b, c, a.slice(0, 10), b.slice(20, 31)]
-    offsets = [0, 75, -12, 300, 7]
+    c = O.store(src, t3, 0, 64, INT4)
+    d = O.store(src, t4, 1, 50, FP8)
+    chunks = [a.slice(10, 75), b, c, a.slice(0, 10), b.slice(20, 31), d.slice(5, 40), c.slice(33, 20)]
+    offsets = [0, 75, -12, 300, 7, 1000, 55]
     hd = host_cache(72, L, nb, bs, H, D)
     dd = dev_cache(hd)
     O.compose(chunks, offsets, hd, dst_bt, 10000.0, dest=5)
-    ha, hb, hc = (kdn.pinned_host_copy(chunk_to_dev(x)) for x in (a, b, c))
-    hchunks = [ha.slice(10, 75), hb, hc, ha.slice(0, 10), hb.slice(20, 31)]
+    ha, hb, hc, hdd = (kdn.pinned_host_copy(chunk_to_dev(x)) for x in (a, b, c, d))
+    hchunks = [ha.slice(10, 75), hb, hc, ha.slice(0, 10), hb.slice(20, 31), hdd.slice(5, 40), hc.slice(33, 20)]
     need = kdn.kdn_staging_bytes(hchunks, layers_per_stage)
     assert need > 0
     staging = torch.empty(need, dtype=torch.uint8, device="cuda")
@@ -632,3 +633,45 @@ def test_two_streams_and_two_host_threads():
         O.compose([c1, c2, c1], [20, -20, 100 * i], hd, tabs[2 + i], 500000.0)
         O.load(c2, hd, tabs[2 + i], 220)
     assert_cache_equal(dd, hd)
+
+
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
+@pytest.mark.parametrize("layers_per_stage", [1, 2, 5])
+def test_store_to_pinned_host_memory_and_back(fmt, layers_per_stage):
+    """The staged store lands the oracle's chunk bytes in host memory; streamed back through
+    kdn_compose_from_host they give the oracle's compose."""
+    L, nb, bs, H, D = 5, 48, 16, 2, 64
+    _say("store_to_host fmt=%d layers_per_stage=%d" % (fmt, layers_per_stage))
+    src = host_cache(131, L, nb, bs, H, D)
+    a, b = synth.disjoint_block_tables(131, nb, [8, 10])
+    want = O.store(src, a, 5, 110, fmt)
+    dc = dev_cache(src)
+    out = kdn.alloc_host_chunk(dc, 110, fmt)
+    out.data.fill_(0xEE)
+    staging = torch.empty(kdn.kdn_store_staging_bytes(dc, 110, fmt, layers_per_stage), dtype=torch.uint8, device="cuda")
+    for _ in range(2):
+        kdn.kdn_store_to_host(dc, dev_table(a), 5, 110, out, staging, layers_per_stage)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.data.numpy(), want.data)
+    assert (out.desc.parent_tokens, out.desc.num_tokens) == (110, 110)
+    hd = host_cache(132, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose([want.slice(10, 90)], [64], hd, b, 10000.0, dest=3)
+    view = out.slice(10, 90)
+    st2 = torch.empty(kdn.kdn_staging_bytes([view], layers_per_stage), dtype=torch.uint8, device="cuda")
+    kdn.kdn_compose_from_host([view], [64], dd, dev_table(b), 10000.0, st2, layers_per_stage, dest_token_start=3)
+    assert_cache_equal(dd, hd)
+    with pytest.raises(kdn.KdnError) as e:                      # a device buffer is not a host destination
+        lib_store_to_host_with_device_chunk(dc, a, fmt, staging, layers_per_stage)
+    assert e.value.status == kdn.EINVAL
+
+
+def lib_store_to_host_with_device_chunk(dc, a, fmt, staging, layers_per_stage):
+    import ctypes as C
+    dev_chunk = kdn.alloc_chunk(dc, 110, fmt)
+    cd = dc.desc()
+    bt = dev_table(a)
+    st = kdn.lib().kdn_store_to_host(C.byref(cd), bt.data_ptr(), bt.numel(), 5, 110, C.byref(dev_chunk.desc),
+                                     staging.data_ptr(), staging.numel(), layers_per_stage, None)
+    if st != kdn.OK:
+        raise kdn.KdnError(st, "kdn_store_to_host")

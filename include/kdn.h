@@ -120,7 +120,14 @@ typedef struct {
 
 /* A stored chunk, or a token view of one.  data: [device], 16-byte aligned, at
  * least kdn_chunk_bytes(..., parent_tokens, fmt) bytes.  A view covers tokens
- * [token_start, token_start + num_tokens) of the parent_tokens the buffer holds. */
+ * [token_start, token_start + num_tokens) of the parent_tokens the buffer holds.
+ * For kdn_store_chunk, kdn_store_tokens, kdn_load_chunk and the kdn_compose* calls,
+ * data may instead be pinned host memory that the device can address (hipHostMalloc,
+ * a pinned torch tensor): the kernels then read or write the stored rows across the
+ * link themselves, with no staging buffer and no copy, at the link's rate and with
+ * the same results; only the compact form crosses (Sec. 3.1, delivery module).  The
+ * staged calls (kdn_store_to_host, kdn_compose_from_host) move the same bytes with
+ * the copy engines instead and leave the compute units free meanwhile. */
 typedef struct {
     void *data;
     uint64_t bytes;

@@ -206,7 +206,8 @@ kdn_status kdn_store_to_host(const kdn_cache_desc *cache, const int32_t *block_t
     DeviceState *ds = device_state(nullptr);
     if (!ds)
         return KDN_EDEVICE;
-    st = ensure_copy_stream(ds);
+    LinkDir &ln = ds->to_host;
+    st = ensure_link(ln);
     if (st != KDN_OK)
         return st;
     hipStream_t user = static_cast<hipStream_t>(stream);
@@ -219,13 +220,18 @@ kdn_status kdn_store_to_host(const kdn_cache_desc *cache, const int32_t *block_t
     uint8_t *staging = static_cast<uint8_t *>(staging_dev);
     uint8_t *host = static_cast<uint8_t *>(out_host->data);
     const uint64_t half_bytes = need / 2;
+    st = wait_for_other_direction(ds->to_device, staging, staging + need, user);
+    if (st != KDN_OK)
+        return st;
+    ln.last_lo = staging;
+    ln.last_hi = staging + need;
     int stage_no = 0;
     for (int32_t l0 = 0; l0 < L; l0 += layers_per_stage, ++stage_no) {
         const int32_t Lg = std::min(layers_per_stage, L - l0);
         const int b = stage_no & 1;
         uint8_t *buf = staging + (uint64_t)b * half_bytes;
         // the kernel may overwrite this half only after the copy that last read it
-        if (ds->drained_valid[b] && hipStreamWaitEvent(user, ds->drained[b], 0) != hipSuccess)
+        if (ln.drained_valid[b] && hipStreamWaitEvent(user, ln.drained[b], 0) != hipSuccess)
             return KDN_EDEVICE;
         if ((uint64_t)Lg * (codes_l + scales_l) > half_bytes
             || (uint64_t)L * codes_l + (uint64_t)(l0 + Lg) * scales_l > out_host->bytes)
@@ -233,26 +239,26 @@ kdn_status kdn_store_to_host(const kdn_cache_desc *cache, const int32_t *block_t
         st = store_launch(cache, block_table_dev, table_len, token_start, T, nullptr, fmt, buf, l0, Lg, user);
         if (st != KDN_OK)
             return st;
-        if (hipEventRecord(ds->filled[b], user) != hipSuccess
-            || hipStreamWaitEvent(ds->copy_stream, ds->filled[b], 0) != hipSuccess)
+        if (hipEventRecord(ln.filled[b], user) != hipSuccess
+            || hipStreamWaitEvent(ln.stream, ln.filled[b], 0) != hipSuccess)
             return KDN_EDEVICE;
         // staged: codes of Lg layers, then their scales; both are contiguous runs of the host chunk
         if (hipMemcpyAsync(host + (uint64_t)l0 * codes_l, buf, (uint64_t)Lg * codes_l, hipMemcpyDeviceToHost,
-                           ds->copy_stream)
+                           ln.stream)
             != hipSuccess)
             return KDN_EDEVICE;
         if (scaled
             && hipMemcpyAsync(host + (uint64_t)L * codes_l + (uint64_t)l0 * scales_l, buf + (uint64_t)Lg * codes_l,
-                              (uint64_t)Lg * scales_l, hipMemcpyDeviceToHost, ds->copy_stream)
+                              (uint64_t)Lg * scales_l, hipMemcpyDeviceToHost, ln.stream)
                    != hipSuccess)
             return KDN_EDEVICE;
-        if (hipEventRecord(ds->drained[b], ds->copy_stream) != hipSuccess)
+        if (hipEventRecord(ln.drained[b], ln.stream) != hipSuccess)
             return KDN_EDEVICE;
-        ds->drained_valid[b] = true;
+        ln.drained_valid[b] = true;
     }
     // the caller's stream completes only when the last copies have landed
     for (int b = 0; b < 2; ++b)
-        if (ds->drained_valid[b] && hipStreamWaitEvent(user, ds->drained[b], 0) != hipSuccess)
+        if (ln.drained_valid[b] && hipStreamWaitEvent(user, ln.drained[b], 0) != hipSuccess)
             return KDN_EDEVICE;
     describe_stored(cache, num_tokens, out_host);
     return KDN_OK;
@@ -438,7 +444,8 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
     DeviceState *ds = device_state(nullptr);
     if (!ds)
         return KDN_EDEVICE;
-    st = ensure_copy_stream(ds);
+    LinkDir &ln = ds->to_device;
+    st = ensure_link(ln);
     if (st != KDN_OK)
         return st;
     hipStream_t user = static_cast<hipStream_t>(stream);
@@ -461,13 +468,18 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
     const uint64_t half_bytes = need / 2;
     std::vector<StageCopy> copies;
     std::vector<uint64_t> staged_at;
+    st = wait_for_other_direction(ds->to_host, staging, staging + need, ln.stream);
+    if (st != KDN_OK)
+        return st;
+    ln.last_lo = staging;
+    ln.last_hi = staging + need;
     int stage_no = 0;
     for (int32_t l0 = 0; l0 < L; l0 += layers_per_stage, ++stage_no) {
         const int32_t Lg = std::min(layers_per_stage, L - l0);
         const int b = stage_no & 1;
         uint8_t *buf = staging + (uint64_t)b * half_bytes;
         // the copy may overwrite this half only after the kernel that last read it
-        if (ds->drained_valid[b] && hipStreamWaitEvent(ds->copy_stream, ds->drained[b], 0) != hipSuccess)
+        if (ln.drained_valid[b] && hipStreamWaitEvent(ln.stream, ln.drained[b], 0) != hipSuccess)
             return KDN_EDEVICE;
         st = plan_stage_copies(parents, l0, Lg, half_bytes, copies, staged_at);
         if (st != KDN_OK)
@@ -476,10 +488,10 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
             const uint8_t *from = parents[(size_t)c.parent].data + c.src_off;
             hipError_t e;
             if (c.width == c.src_pitch) // whole chunk: the planes adjoin
-                e = hipMemcpyAsync(buf + c.dst_off, from, c.width * c.rows, hipMemcpyHostToDevice, ds->copy_stream);
+                e = hipMemcpyAsync(buf + c.dst_off, from, c.width * c.rows, hipMemcpyHostToDevice, ln.stream);
             else
                 e = hipMemcpy2DAsync(buf + c.dst_off, c.width, from, c.src_pitch, c.width, (size_t)c.rows,
-                                     hipMemcpyHostToDevice, ds->copy_stream);
+                                     hipMemcpyHostToDevice, ln.stream);
             if (e != hipSuccess)
                 return KDN_EDEVICE;
         }
@@ -500,8 +512,8 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
             segs[ch.fmt].push_back(s);
             S += ch.num_tokens;
         }
-        if (hipEventRecord(ds->filled[b], ds->copy_stream) != hipSuccess
-            || hipStreamWaitEvent(user, ds->filled[b], 0) != hipSuccess)
+        if (hipEventRecord(ln.filled[b], ln.stream) != hipSuccess
+            || hipStreamWaitEvent(user, ln.filled[b], 0) != hipSuccess)
             return KDN_EDEVICE;
         p.c.L = Lg;
         p.layer0 = l0;
@@ -510,9 +522,9 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
             if (st != KDN_OK)
                 return st;
         }
-        if (hipEventRecord(ds->drained[b], user) != hipSuccess)
+        if (hipEventRecord(ln.drained[b], user) != hipSuccess)
             return KDN_EDEVICE;
-        ds->drained_valid[b] = true;
+        ln.drained_valid[b] = true;
     }
     return KDN_OK;
 }
@@ -616,13 +628,8 @@ kdn_status kdn_shutdown(void)
         for (int i = 0; i < kSegSlots; ++i)
             if (ds.seg_done[i])
                 (void)hipEventDestroy(ds.seg_done[i]);
-        if (ds.copy_stream) {
-            (void)hipStreamDestroy(ds.copy_stream);
-            for (int b = 0; b < 2; ++b) {
-                (void)hipEventDestroy(ds.filled[b]);
-                (void)hipEventDestroy(ds.drained[b]);
-            }
-        }
+        destroy_link(ds.to_device);
+        destroy_link(ds.to_host);
     }
     g_dev.clear();
     (void)hipSetDevice(cur);

@@ -34,6 +34,17 @@ struct RopeTable {
     std::unordered_map<int32_t, int32_t> row_of;
 };
 
+// One direction of the host link: a copy stream and, per half of the caller's staging
+// buffer, a "filled" and a "drained" event; the staging range of the direction's last call,
+// so that a call in the other direction that reuses the memory can wait for it.
+struct LinkDir {
+    hipStream_t stream = nullptr;
+    hipEvent_t filled[2] = {};
+    hipEvent_t drained[2] = {};
+    bool drained_valid[2] = {};
+    const uint8_t *last_lo = nullptr, *last_hi = nullptr;
+};
+
 struct DeviceState {
     std::vector<RopeTable> rope;
     uint8_t *seg_dev = nullptr;                   // kSegSlots * kSegSlotBytes
@@ -41,12 +52,7 @@ struct DeviceState {
     hipEvent_t seg_done[kSegSlots] = {};
     bool seg_used[kSegSlots] = {};
     int next_slot = 0;
-    // streaming of host-resident chunks: a copy stream and, per half of the caller's
-    // staging buffer, "filled" and "drained" events
-    hipStream_t copy_stream = nullptr;
-    hipEvent_t filled[2] = {};
-    hipEvent_t drained[2] = {};
-    bool drained_valid[2] = {};
+    LinkDir to_device, to_host; // the link is full duplex: the directions do not share a stream
 };
 
 inline std::mutex g_mu; // guards g_dev and everything in it
@@ -145,18 +151,45 @@ inline DeviceState *device_state(int *dev_out)
     return &g_dev[dev];
 }
 
-// The stream and events behind the host-memory paths, created on first use.
-inline kdn_status ensure_copy_stream(DeviceState *ds)
+// The stream and events of one link direction, created on first use.
+inline kdn_status ensure_link(LinkDir &ln)
 {
-    if (ds->copy_stream)
+    if (ln.stream)
         return KDN_OK;
-    if (hipStreamCreateWithFlags(&ds->copy_stream, hipStreamNonBlocking) != hipSuccess)
+    if (hipStreamCreateWithFlags(&ln.stream, hipStreamNonBlocking) != hipSuccess)
         return KDN_EDEVICE;
     for (int b = 0; b < 2; ++b)
-        if (hipEventCreateWithFlags(&ds->filled[b], hipEventDisableTiming) != hipSuccess
-            || hipEventCreateWithFlags(&ds->drained[b], hipEventDisableTiming) != hipSuccess)
+        if (hipEventCreateWithFlags(&ln.filled[b], hipEventDisableTiming) != hipSuccess
+            || hipEventCreateWithFlags(&ln.drained[b], hipEventDisableTiming) != hipSuccess)
             return KDN_EDEVICE;
     return KDN_OK;
+}
+
+// Before a call writes staging memory [lo, hi): if the other direction's last call used
+// memory that overlaps it, `first_writer` waits until that call has let go of both halves.
+inline kdn_status wait_for_other_direction(const LinkDir &other, const uint8_t *lo, const uint8_t *hi,
+                                           hipStream_t first_writer)
+{
+    if (!other.last_lo || hi <= other.last_lo || other.last_hi <= lo)
+        return KDN_OK;
+    for (int b = 0; b < 2; ++b)
+        if (other.drained_valid[b] && hipStreamWaitEvent(first_writer, other.drained[b], 0) != hipSuccess)
+            return KDN_EDEVICE;
+    return KDN_OK;
+}
+
+inline void destroy_link(LinkDir &ln)
+{
+    if (!ln.stream)
+        return;
+    (void)hipStreamDestroy(ln.stream);
+    for (int b = 0; b < 2; ++b) {
+        if (ln.filled[b])
+            (void)hipEventDestroy(ln.filled[b]);
+        if (ln.drained[b])
+            (void)hipEventDestroy(ln.drained[b]);
+    }
+    ln = LinkDir();
 }
 
 // Validates a caller's RoPE variant for head_dim D.  NULL selects the default

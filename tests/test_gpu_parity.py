@@ -666,6 +666,40 @@ def test_store_to_pinned_host_memory_and_back(fmt, layers_per_stage):
     assert e.value.status == kdn.EINVAL
 
 
+@pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
+def test_kernels_on_chunks_in_pinned_host_memory(fmt):
+    """Store, load and compose with the chunk itself in pinned host memory (no staging, the
+    kernels cross the link): the oracle's bytes land in host memory, and views of the host
+    chunk compose to the oracle's result."""
+    L, nb, bs, H, D = 3, 64, 16, 2, 128
+    _say("direct host chunk fmt=%d" % fmt)
+    src = host_cache(141, L, nb, bs, H, D)
+    a, b, c = synth.disjoint_block_tables(141, nb, [9, 12, 8])
+    want = O.store(src, a, 7, 130, fmt)
+    dc = dev_cache(src)
+    out = kdn.alloc_host_chunk(dc, 130, fmt)
+    out.data.fill_(0xEE)
+    kdn.kdn_store_chunk(dc, dev_table(a), 7, 130, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.data.numpy(), want.data)
+    keep = synth.permutation(141, 130)[:40].astype(np.int32) + 7
+    want_t = O.store_tokens(src, a, keep, fmt)
+    out_t = kdn.alloc_host_chunk(dc, 40, fmt)
+    kdn.kdn_store_tokens(dc, dev_table(a), torch.from_numpy(keep).cuda(), out_t)
+    torch.cuda.synchronize()
+    assert np.array_equal(out_t.data.numpy(), want_t.data)
+    hd = host_cache(142, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    views = [want.slice(100, 30), want_t, want.slice(0, 64), want.slice(50, 37)]
+    offsets = [0, 30, -20, 4000]
+    O.compose(views, offsets, hd, b, 500000.0, dest=9)
+    O.load(want.slice(3, 100), hd, c, 11)
+    hviews = [out.slice(100, 30), out_t, out.slice(0, 64), out.slice(50, 37)]
+    kdn.kdn_compose(hviews, offsets, dd, dev_table(b), 500000.0, dest_token_start=9)
+    kdn.kdn_load_chunk(out.slice(3, 100), dd, dev_table(c), 11)
+    assert_cache_equal(dd, hd)
+
+
 def lib_store_to_host_with_device_chunk(dc, a, fmt, staging, layers_per_stage):
     import ctypes as C
     dev_chunk = kdn.alloc_chunk(dc, 110, fmt)

@@ -255,6 +255,29 @@ kdn_status kdn_compose_rope(const kdn_chunk *chunks, const int32_t *offsets, int
 kdn_status kdn_compose_batch_rope(const kdn_request *requests, int32_t n_requests,
                                   const kdn_cache_desc *cache, const kdn_rope_spec *rope, void *stream);
 
+/* The bookkeeping of kdn_compose_batch without the launch, for callers that want to
+ * inspect or log a plan (host only: no device is touched, no pointer is dereferenced
+ * beyond the request and chunk records).  One record per chunk view, in the order the
+ * kernels take them: grouped by stored form (one launch per form present, `launch`
+ * counts them), and, when there is more than one request, views of the same stored rows
+ * next to each other.  dest_token is the request token that receives the view's first
+ * row: dest_token_start plus the token counts of the views before it in its request.
+ * shares_rows is 1 when some stored rows are read by more than one view of that launch
+ * (the kernels then keep them in the cache hierarchy).  Argument checks and status
+ * codes are those of kdn_compose_batch.  out: [host] array of `cap` records; *n_out
+ * receives the count (cap 0 asks for the count alone); KDN_ESIZE if cap is too small. */
+typedef struct kdn_placement {
+    int32_t request, chunk; /* indices into requests[] and its chunks[] */
+    int32_t fmt;
+    int32_t launch;
+    int32_t dest_token;
+    int32_t num_tokens;
+    int32_t offset;         /* RoPE position delta of the view */
+    int32_t shares_rows;
+} kdn_placement;
+kdn_status kdn_compose_plan(const kdn_request *requests, int32_t n_requests, const kdn_cache_desc *cache,
+                            kdn_placement *out, int32_t cap, int32_t *n_out);
+
 /* Patch: the write-back half of selective recompute after a blend (Sec. 3.2, "KV-cache
  * blending": recomputing a small part of the composed KV).  rows_dev [device, 16-byte
  * aligned]: bf16 [L][2][n_tokens][H][D] recomputed K and V rows; row i replaces request

@@ -289,6 +289,35 @@ kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
     return compose_impl(requests, n_requests, cache, rope_base, nullptr, stream);
 }
 
+kdn_status kdn_compose_plan(const kdn_request *requests, int32_t n_requests, const kdn_cache_desc *cache,
+                            kdn_placement *out, int32_t cap, int32_t *n_out)
+{
+    if (!n_out || cap < 0 || (cap > 0 && !out))
+        return KDN_EINVAL;
+    ComposePlan plan;
+    kdn_status st = plan_compose(requests, n_requests, cache, plan);
+    if (st != KDN_OK)
+        return st;
+    size_t n = 0;
+    for (int f = 0; f < kFormats; ++f)
+        n += plan.segs[f].size();
+    if (n > 0x7fffffff)
+        return KDN_ESIZE;
+    *n_out = (int32_t)n;
+    if (cap == 0)
+        return KDN_OK; // the count alone
+    if ((size_t)cap < n)
+        return KDN_ESIZE;
+    size_t k = 0;
+    int32_t launch = 0;
+    for (int f = 0; f < kFormats; ++f) {
+        for (const PlannedSeg &ps : plan.segs[f])
+            out[k++] = {ps.request, ps.chunk, f, launch, ps.seg.S, ps.seg.T, ps.offset, plan.reuse[f]};
+        launch += plan.segs[f].empty() ? 0 : 1;
+    }
+    return KDN_OK;
+}
+
 kdn_status kdn_compose_rope(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
                             const kdn_cache_desc *cache, const int32_t *block_table_dev,
                             int32_t table_len, int32_t dest_token_start, const kdn_rope_spec *rope,

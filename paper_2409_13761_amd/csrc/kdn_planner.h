@@ -434,19 +434,27 @@ inline kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, 
     return rc;
 }
 
-inline kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
-                               double rope_base, const kdn_rope_spec *variant, void *stream)
+// The bookkeeping of a (batched) compose, host only: every chunk view becomes one segment
+// placed at the running sum of the token counts before it in its request; segments are
+// grouped by stored form (one launch each).  `request`, `chunk` and `offset` say where a
+// segment came from; its cos/sin row is filled in later.
+struct PlannedSeg {
+    Seg seg;
+    int32_t request, chunk, offset;
+};
+struct ComposePlan {
+    std::vector<PlannedSeg> segs[kFormats];
+    int32_t reuse[kFormats] = {};
+};
+
+inline kdn_status plan_compose(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
+                               ComposePlan &plan)
 {
     if (!reqs || n_reqs <= 0)
         return KDN_EINVAL;
     kdn_status st = check_cache(cache);
     if (st != KDN_OK)
         return st;
-    RopeSpec spec;
-    st = resolve_spec(variant, rope_base, cache->head_dim, spec);
-    if (st != KDN_OK)
-        return st;
-    std::vector<int32_t> offs;
     for (int32_t r = 0; r < n_reqs; ++r) {
         const kdn_request &q = reqs[r];
         if (!q.chunks || !q.offsets || q.n_chunks <= 0 || !q.block_table_dev || q.table_len <= 0
@@ -458,11 +466,70 @@ inline kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kd
             if (st != KDN_OK)
                 return st;
             total += q.chunks[i].num_tokens;
-            offs.push_back(q.offsets[i]);
         }
         if (total > (int64_t)q.table_len * cache->block_size || total > 0x7fffffff)
             return KDN_ERANGE; // token indices are 32-bit in the kernels
     }
+    for (int32_t r = 0; r < n_reqs; ++r) {
+        const kdn_request &q = reqs[r];
+        int32_t S = q.dest_token_start;
+        for (int32_t i = 0; i < q.n_chunks; ++i) {
+            const kdn_chunk &ch = q.chunks[i];
+            PlannedSeg ps;
+            ps.seg.data = static_cast<const uint8_t *>(ch.data);
+            ps.seg.bt = q.block_table_dev;
+            ps.seg.Tp = ch.parent_tokens;
+            ps.seg.tok0 = ch.token_start;
+            ps.seg.T = ch.num_tokens;
+            ps.seg.S = S;
+            ps.seg.rope_row = 0;
+            ps.seg.pad = 0;
+            ps.request = r;
+            ps.chunk = i;
+            ps.offset = q.offsets[i];
+            plan.segs[ch.fmt].push_back(ps);
+            S += ch.num_tokens;
+        }
+    }
+    for (int f = 0; f < kFormats; ++f) {
+        // Segments that read the same stored rows run back to back, so that a popular
+        // chunk is fetched from HBM once and from the last-level cache afterwards.
+        plan.reuse[f] = 0;
+        if (n_reqs <= 1)
+            continue;
+        std::vector<PlannedSeg> &v = plan.segs[f];
+        std::stable_sort(v.begin(), v.end(), [](const PlannedSeg &a, const PlannedSeg &b) {
+            return a.seg.data != b.seg.data ? a.seg.data < b.seg.data : a.seg.tok0 < b.seg.tok0;
+        });
+        // sorted by first row, so a view overlaps an earlier one exactly when it starts
+        // before the furthest end seen so far in its buffer
+        int64_t reach = 0;
+        for (size_t i = 0; i < v.size(); ++i) {
+            if (i == 0 || v[i].seg.data != v[i - 1].seg.data)
+                reach = 0;
+            else if (v[i].seg.tok0 < reach)
+                plan.reuse[f] = 1;
+            reach = std::max<int64_t>(reach, (int64_t)v[i].seg.tok0 + v[i].seg.T);
+        }
+    }
+    return KDN_OK;
+}
+
+inline kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
+                               double rope_base, const kdn_rope_spec *variant, void *stream)
+{
+    ComposePlan plan;
+    kdn_status st = plan_compose(reqs, n_reqs, cache, plan);
+    if (st != KDN_OK)
+        return st;
+    RopeSpec spec;
+    st = resolve_spec(variant, rope_base, cache->head_dim, spec);
+    if (st != KDN_OK)
+        return st;
+    std::vector<int32_t> offs;
+    for (int f = 0; f < kFormats; ++f)
+        for (const PlannedSeg &ps : plan.segs[f])
+            offs.push_back(ps.offset);
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceState *ds = device_state(nullptr);
     if (!ds)
@@ -476,41 +543,16 @@ inline kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kd
     st = rope_rows(ds, spec, offs.data(), (int32_t)offs.size(), rows.data(), &p.rope);
     if (st != KDN_OK)
         return st;
-    std::vector<Seg> segs[kFormats];
     size_t k = 0;
-    for (int32_t r = 0; r < n_reqs; ++r) {
-        const kdn_request &q = reqs[r];
-        int32_t S = q.dest_token_start;
-        for (int32_t i = 0; i < q.n_chunks; ++i, ++k) {
-            const kdn_chunk &ch = q.chunks[i];
-            Seg s;
-            s.data = static_cast<const uint8_t *>(ch.data);
-            s.bt = q.block_table_dev;
-            s.Tp = ch.parent_tokens;
-            s.tok0 = ch.token_start;
-            s.T = ch.num_tokens;
-            s.S = S;
-            s.rope_row = rows[k];
-            s.pad = 0;
-            segs[ch.fmt].push_back(s);
-            S += ch.num_tokens;
-        }
-    }
     for (int f = 0; f < kFormats; ++f) {
-        // Segments that read the same stored rows run back to back, so that a popular
-        // chunk is fetched from HBM once and from the last-level cache afterwards.
-        p.reuse = 0;
-        if (n_reqs > 1) {
-            std::stable_sort(segs[f].begin(), segs[f].end(), [](const Seg &a, const Seg &b) {
-                return a.data != b.data ? a.data < b.data : a.tok0 < b.tok0;
-            });
-            for (size_t i = 1; i < segs[f].size(); ++i) {
-                const Seg &a = segs[f][i - 1], &b = segs[f][i];
-                if (a.data == b.data && b.tok0 < a.tok0 + a.T)
-                    p.reuse = 1;
-            }
+        std::vector<Seg> segs;
+        segs.reserve(plan.segs[f].size());
+        for (const PlannedSeg &ps : plan.segs[f]) {
+            segs.push_back(ps.seg);
+            segs.back().rope_row = rows[k++];
         }
-        st = place_segments(ds, p, f, segs[f], static_cast<hipStream_t>(stream));
+        p.reuse = plan.reuse[f];
+        st = place_segments(ds, p, f, segs, static_cast<hipStream_t>(stream));
         if (st != KDN_OK)
             return st;
     }

@@ -128,6 +128,8 @@ def lib() -> C.CDLL:
                                             vp, u64, i32, vp]
         L.kdn_staging_bytes.restype = u64
         L.kdn_staging_bytes.argtypes = [C.POINTER(ChunkDesc), i32, i32]
+        L.kdn_compose_plan.restype = C.c_int
+        L.kdn_compose_plan.argtypes = [vp, i32, vp, vp, i32, C.POINTER(i32)]
         L.kdn_host_stage_plan.restype = C.c_int
         L.kdn_host_stage_plan.argtypes = [C.POINTER(ChunkDesc), i32, i32, i32, vp, i32, C.POINTER(i32), vp]
         L.kdn_rope_prepare.restype = C.c_int
@@ -152,7 +154,7 @@ EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_ch
            "kdn_store_to_host", "kdn_store_staging_bytes",
            "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_rope",
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host",
-           "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec",
+           "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec",
            "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version", "kdn_pool_create", "kdn_pool_destroy", "kdn_pool_hash", "kdn_pool_lookup",
            "kdn_pool_insert", "kdn_pool_remove", "kdn_pool_get_stats"]
@@ -381,6 +383,23 @@ def kdn_compose_batch(plan_or_requests, cache: PagedCache, rope_base: float, str
     cd = cache.desc()
     _check(lib().kdn_compose_batch(plan.arr, plan.n, C.byref(cd), float(rope_base), _stream(stream)),
            "kdn_compose_batch")
+
+
+class PlacementDesc(C.Structure):
+    _fields_ = [("request", C.c_int32), ("chunk", C.c_int32), ("fmt", C.c_int32), ("launch", C.c_int32),
+                ("dest_token", C.c_int32), ("num_tokens", C.c_int32), ("offset", C.c_int32),
+                ("shares_rows", C.c_int32)]
+
+
+def kdn_compose_plan(plan_or_requests, cache: PagedCache):
+    """The placements of a batched compose, in kernel order, as dicts of the C record's fields."""
+    plan = plan_or_requests if isinstance(plan_or_requests, BatchPlan) else BatchPlan(plan_or_requests)
+    cd = cache.desc()
+    n = C.c_int32(0)
+    _check(lib().kdn_compose_plan(plan.arr, plan.n, C.byref(cd), None, 0, C.byref(n)), "kdn_compose_plan")
+    out = (PlacementDesc * n.value)()
+    _check(lib().kdn_compose_plan(plan.arr, plan.n, C.byref(cd), out, n.value, C.byref(n)), "kdn_compose_plan")
+    return [{f: getattr(r, f) for f, _ in PlacementDesc._fields_} for r in out]
 
 
 def rope_spec(base: float = 10000.0, inv_freq=None, rot_dim: int = 0,

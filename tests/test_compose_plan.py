@@ -1,0 +1,90 @@
+"""Host bookkeeping of the compose (Sec. 3.1 blending module: several chunks put together in
+one context), checked without a GPU through kdn_compose_plan: placement prefix sums,
+grouping by stored form, ordering of views that share stored rows, argument checks."""
+import numpy as np
+import pytest
+import torch
+
+from helpers import FP8, INT4, INT8, RAW
+from paper_2409_13761_amd import kdn, synth
+
+L, NB, BS, H, D = 2, 64, 16, 2, 64
+
+
+def _cache():
+    k = torch.zeros((L, NB, BS, H, D), dtype=torch.bfloat16)
+    return kdn.PagedCache(k, torch.zeros_like(k))
+
+
+def _chunk(cache, T, fmt):
+    n = kdn.kdn_chunk_bytes(L, H, D, T, fmt)
+    return kdn.chunk_from_buffer(torch.zeros(n, dtype=torch.uint8), fmt, L, H, D, T)
+
+
+def _table(n):
+    return torch.arange(n, dtype=torch.int32)
+
+
+def test_placement_is_the_running_sum_of_token_counts():
+    cache = _cache()
+    a, b, c = _chunk(cache, 90, INT8), _chunk(cache, 70, INT8), _chunk(cache, 33, INT8)
+    views = [a.slice(10, 75), b, c, a.slice(0, 10), b.slice(20, 31)]
+    offsets = [0, 75, -12, 300, 7]
+    plan = kdn.kdn_compose_plan([(views, offsets, _table(16), 5)], cache)
+    assert [p["chunk"] for p in plan] == [0, 1, 2, 3, 4]          # one request: caller's order kept
+    want_dest = 5 + np.concatenate([[0], np.cumsum([75, 70, 33, 10])])
+    assert [p["dest_token"] for p in plan] == want_dest.tolist()
+    assert [p["num_tokens"] for p in plan] == [75, 70, 33, 10, 31]
+    assert [p["offset"] for p in plan] == offsets
+    assert {p["launch"] for p in plan} == {0} and {p["fmt"] for p in plan} == {INT8}
+    assert {p["shares_rows"] for p in plan} == {0}
+
+
+def test_one_launch_per_stored_form_and_placement_independent_of_grouping():
+    cache = _cache()
+    chunks = [_chunk(cache, 40, f) for f in (INT8, RAW, INT4, FP8, RAW, INT8)]
+    plan = kdn.kdn_compose_plan([(chunks, [0] * 6, _table(16), 0)], cache)
+    by_chunk = {p["chunk"]: p for p in plan}
+    assert [by_chunk[i]["dest_token"] for i in range(6)] == [0, 40, 80, 120, 160, 200]
+    launches = [p["launch"] for p in plan]
+    assert launches == sorted(launches) and len(set(launches)) == 4
+    for ln in set(launches):                                      # a launch holds one stored form
+        assert len({p["fmt"] for p in plan if p["launch"] == ln}) == 1
+    assert sorted(p["chunk"] for p in plan) == list(range(6))
+
+
+def test_batched_views_of_the_same_rows_adjoin_and_are_flagged():
+    cache = _cache()
+    pool = [_chunk(cache, 64, INT8) for _ in range(5)]
+    draws = synth.zipf_distinct_draws(9, 12, 3, 5)
+    reqs = [([pool[j] for j in row], [0, 64, 128], _table(12), 0) for row in draws]
+    plan = kdn.kdn_compose_plan(reqs, cache)
+    assert len(plan) == 36 and {p["shares_rows"] for p in plan} == {1}
+    key = [pool[int(draws[p["request"], p["chunk"]])].data.data_ptr() for p in plan]
+    assert key == sorted(key)                                     # equal buffers back to back
+    for p in plan:                                                # placement untouched by the reordering
+        assert p["dest_token"] == 64 * p["chunk"]
+    assert sorted((p["request"], p["chunk"]) for p in plan) == [(r, c) for r in range(12) for c in range(3)]
+    # distinct chunks per request, disjoint slices across requests: nothing is shared
+    a = _chunk(cache, 128, INT8)
+    reqs = [([a.slice(0, 64)], [0], _table(4), 0), ([a.slice(64, 64)], [0], _table(4), 0)]
+    assert {p["shares_rows"] for p in kdn.kdn_compose_plan(reqs, cache)} == {0}
+    reqs = [([a.slice(0, 64)], [0], _table(4), 0), ([a.slice(63, 64)], [0], _table(4), 0)]
+    assert {p["shares_rows"] for p in kdn.kdn_compose_plan(reqs, cache)} == {1}
+
+
+def test_argument_checks():
+    cache = _cache()
+    a = _chunk(cache, 100, INT8)
+    with pytest.raises(kdn.KdnError) as e:                        # 5 + 100 tokens do not fit 6 blocks of 16
+        kdn.kdn_compose_plan([([a], [0], _table(6), 5)], cache)
+    assert e.value.status == kdn.ERANGE
+    kdn.kdn_compose_plan([([a], [0], _table(7), 5)], cache)       # 105 <= 112
+    wrong = kdn.chunk_from_buffer(torch.zeros(kdn.kdn_chunk_bytes(L, H, 32, 8, RAW), dtype=torch.uint8),
+                                  RAW, L, H, 32, 8)
+    with pytest.raises(kdn.KdnError) as e:                        # a chunk of another head_dim
+        kdn.kdn_compose_plan([([wrong], [0], _table(7), 0)], cache)
+    assert e.value.status == kdn.EINVAL
+    with pytest.raises(kdn.KdnError) as e:
+        kdn.kdn_compose_plan([([a], [0], _table(7), -1)], cache)
+    assert e.value.status == kdn.EINVAL

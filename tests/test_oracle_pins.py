@@ -384,7 +384,9 @@ def test_e4m3_encode_matches_torch_below_saturation(oracle):
     inside = np.abs(x) <= 448.0
     assert np.array_equal(got[inside], want[inside])
     assert np.all((got[~inside] & 0x7F) == 0x7E)
-    assert oracle.f32_to_e4m3(np.array([464.0, 1e9, -1e9], dtype=np.float32)).tolist() == [0x7E, 0x7E, 0xFE]
+    # saturation starts right above 448, not at the next binade: 465..479 would round to the NaN code
+    over = np.array([464.0, 465.0, 479.0, 480.0, 1e9, -1e9, np.inf, -470.0], dtype=np.float32)
+    assert oracle.f32_to_e4m3(over).tolist() == [0x7E, 0x7E, 0x7E, 0x7E, 0x7E, 0xFE, 0x7E, 0xFE]
 
 
 def test_fp8_rows(oracle):

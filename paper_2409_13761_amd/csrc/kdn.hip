@@ -220,11 +220,9 @@ kdn_status kdn_store_to_host(const kdn_cache_desc *cache, const int32_t *block_t
     uint8_t *staging = static_cast<uint8_t *>(staging_dev);
     uint8_t *host = static_cast<uint8_t *>(out_host->data);
     const uint64_t half_bytes = need / 2;
-    st = wait_for_other_direction(ds->to_device, staging, staging + need, user);
+    st = begin_staging(ln, ds->to_device, staging, need, user); // the kernels write the staging memory
     if (st != KDN_OK)
         return st;
-    ln.last_lo = staging;
-    ln.last_hi = staging + need;
     int stage_no = 0;
     for (int32_t l0 = 0; l0 < L; l0 += layers_per_stage, ++stage_no) {
         const int32_t Lg = std::min(layers_per_stage, L - l0);
@@ -497,11 +495,9 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
     const uint64_t half_bytes = need / 2;
     std::vector<StageCopy> copies;
     std::vector<uint64_t> staged_at;
-    st = wait_for_other_direction(ds->to_host, staging, staging + need, ln.stream);
+    st = begin_staging(ln, ds->to_host, staging, need, ln.stream); // the copies write the staging memory
     if (st != KDN_OK)
         return st;
-    ln.last_lo = staging;
-    ln.last_hi = staging + need;
     int stage_no = 0;
     for (int32_t l0 = 0; l0 < L; l0 += layers_per_stage, ++stage_no) {
         const int32_t Lg = std::min(layers_per_stage, L - l0);

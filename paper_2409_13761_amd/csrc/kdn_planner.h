@@ -165,16 +165,26 @@ inline kdn_status ensure_link(LinkDir &ln)
     return KDN_OK;
 }
 
-// Before a call writes staging memory [lo, hi): if the other direction's last call used
-// memory that overlaps it, `first_writer` waits until that call has let go of both halves.
-inline kdn_status wait_for_other_direction(const LinkDir &other, const uint8_t *lo, const uint8_t *hi,
-                                           hipStream_t first_writer)
+// Orders a call's first writes to its staging memory [staging, staging + need) behind what
+// earlier calls still do there.  Within a direction the stage loop waits per half, which is
+// exact only when the halves are the same memory as last time; otherwise, and when the
+// other direction's last call used overlapping memory, `first_writer` waits until those
+// calls have let go of both halves.
+inline kdn_status begin_staging(LinkDir &ln, const LinkDir &other, const uint8_t *staging, uint64_t need,
+                                hipStream_t first_writer)
 {
-    if (!other.last_lo || hi <= other.last_lo || other.last_hi <= lo)
-        return KDN_OK;
-    for (int b = 0; b < 2; ++b)
-        if (other.drained_valid[b] && hipStreamWaitEvent(first_writer, other.drained[b], 0) != hipSuccess)
+    const uint8_t *hi = staging + need;
+    const bool same_halves = ln.last_lo == staging && ln.last_hi == hi;
+    const bool other_overlaps = other.last_lo && staging < other.last_hi && other.last_lo < hi;
+    for (int b = 0; b < 2; ++b) {
+        if (!same_halves && ln.drained_valid[b] && hipStreamWaitEvent(first_writer, ln.drained[b], 0) != hipSuccess)
             return KDN_EDEVICE;
+        if (other_overlaps && other.drained_valid[b]
+            && hipStreamWaitEvent(first_writer, other.drained[b], 0) != hipSuccess)
+            return KDN_EDEVICE;
+    }
+    ln.last_lo = staging;
+    ln.last_hi = hi;
     return KDN_OK;
 }
 

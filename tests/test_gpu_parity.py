@@ -400,6 +400,14 @@ def test_compose_from_pinned_host_chunks_equals_compose(layers_per_stage):
         kdn.kdn_compose_from_host(hchunks, offsets, dd, dev_table(dst_bt), 10000.0, staging,
                                   layers_per_stage, dest_token_start=5)
     assert_cache_equal(dd, hd)
+    # the same staging memory cut into halves of another size, with the previous call still in flight
+    other = 3 if layers_per_stage != 3 else 2
+    big = torch.empty(max(need, kdn.kdn_staging_bytes(hchunks, other)), dtype=torch.uint8, device="cuda")
+    dd2 = dev_cache(host_cache(72, L, nb, bs, H, D))
+    kdn.kdn_compose_from_host(hchunks, offsets, dd2, dev_table(dst_bt), 10000.0, big[:need], layers_per_stage, dest_token_start=5)
+    kdn.kdn_compose_from_host(hchunks, offsets, dd, dev_table(dst_bt), 10000.0, big, other, dest_token_start=5)
+    assert_cache_equal(dd, hd)
+    assert_cache_equal(dd2, hd)
     small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
     with pytest.raises(kdn.KdnError) as e:
         kdn.kdn_compose_from_host(hchunks, offsets, dd, dev_table(dst_bt), 10000.0, small, layers_per_stage)

@@ -18,7 +18,8 @@ compose of four 8192-token slices) and "batched_reuse" (64 requests x 4 chunks o
 compose per step).
 
 "pool_trace" is a serving loop over the text-keyed index (store on miss, compose on
-hit) and reports the hit rate.  "host_stream_int8" / "host_stream_raw" compose a chunk that lives in pinned host memory
+hit) and reports the hit rate; "pool_trace_tiered" adds a host-memory tier under it
+(demote on eviction, promote on hit).  "host_stream_int8" / "host_stream_raw" compose a chunk that lives in pinned host memory
 (the rate there includes PCIe and is link bound; its roofline entry is still priced
 against HBM and is not a kernel-quality figure).
 
@@ -466,6 +467,109 @@ def workload_pool_trace(args, dev):
     }
 
 
+def workload_pool_trace_tiered(args, dev):
+    """The serving loop of "pool_trace" with a second tier: 64 chunks resident in HBM, 128 more
+    in pinned host memory, each with its own text-keyed index (LRU).  A chunk evicted from HBM
+    is demoted to the host tier (its compact bytes copied out); a text found there is promoted
+    back (copied in, host entry released); a text found nowhere is stored from paged memory.
+    The request's 4 chunks are then composed from HBM."""
+    import numpy as np
+    import torch
+    from paper_2409_13761_amd import kdn, synth
+
+    w = synth.WORKLOADS["batched_reuse"]
+    sh = w.shape
+    n_texts, per_req, Tc, in_hbm, in_host = w.extra["pool"], 4, 1024, 64, 128
+    cb = Tc // sh.bs
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    n_src = 16
+    nb = n_src * cb + 2 * per_req * cb
+    k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
+    v = torch.empty_like(k)
+    fill_normal(k, g)
+    fill_normal(v, g)
+    cache = kdn.PagedCache(k, v)
+    tabs = synth.disjoint_block_tables(w.seed, nb, [cb] * n_src + [per_req * cb] * 2)
+    src_tabs = [torch.from_numpy(t).to(dev) for t in tabs[:n_src]]
+    dst_tabs = [torch.from_numpy(t).to(dev) for t in tabs[n_src:]]
+    fmt = kdn.FMT_INT8_ROWSCALE
+    chunk_bytes = kdn.kdn_chunk_bytes(sh.L, sh.H, sh.D, Tc, fmt)
+    dev_free = [kdn.alloc_chunk(cache, Tc, fmt) for _ in range(in_hbm + per_req)]
+    host_free = [kdn.alloc_host_chunk(cache, Tc, fmt) for _ in range(in_host + per_req)]
+    by_ptr = {c.data.data_ptr(): c for c in dev_free + host_free}
+    text_of = {}                                  # buffer address -> text it holds
+    hbm, host = kdn.Pool(in_hbm * chunk_bytes, 0), kdn.Pool(in_host * chunk_bytes, 0)
+    total = args.warmup + args.steps
+    draws = synth.zipf_distinct_draws(w.seed, total, per_req, n_texts, w.extra["alpha"])
+    text_ids = [np.ascontiguousarray(synth._rng(w.seed + 7, 100 + t).integers(0, 128000, size=Tc), dtype=np.int32)
+                for t in range(n_texts)]
+    offsets = list(w.offsets)
+    kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
+    counts = {"hbm_hit": 0, "host_hit": 0, "miss": 0, "demoted": 0}
+
+    def into_hbm(t, buf):
+        """Index `buf` (already holding text t) in the HBM tier; what falls out goes to the host tier."""
+        text_of[buf.data.data_ptr()] = t
+        for e in hbm.insert(text_ids[t], buf.desc):
+            out_dev = by_ptr[e.data]
+            out_t = text_of.pop(e.data)
+            hbuf = host_free.pop()
+            hbuf.data.copy_(out_dev.data, non_blocking=True)          # compact bytes, device to host
+            counts["demoted"] += 1
+            text_of[hbuf.data.data_ptr()] = out_t
+            for he in host.insert(text_ids[out_t], hbuf.desc):
+                text_of.pop(he.data)
+                host_free.append(by_ptr[he.data])
+            dev_free.append(out_dev)
+
+    def step(i, rec):
+        def body():
+            chunks = []
+            for t in draws[i]:
+                t = int(t)
+                d = hbm.lookup(text_ids[t])
+                if d is not None:
+                    counts["hbm_hit"] += 1
+                    chunks.append(by_ptr[d.data])
+                    continue
+                buf = dev_free.pop()
+                hd = host.remove(text_ids[t])
+                if hd is not None:
+                    counts["host_hit"] += 1
+                    hbuf = by_ptr[hd.data]
+                    buf.data.copy_(hbuf.data, non_blocking=True)      # promotion: host to device
+                    text_of.pop(hd.data)
+                    host_free.append(hbuf)
+                else:
+                    counts["miss"] += 1
+                    kdn.kdn_store_chunk(cache, src_tabs[t % n_src], 0, Tc, buf)
+                into_hbm(t, buf)
+                chunks.append(buf)
+            kdn.kdn_compose(chunks, offsets, cache, dst_tabs[i % 2], w.rope_base)
+        rec("request", body)
+
+    wall, ms = Timed(("request",), args.steps).run(step, args.warmup)
+    tokens = per_req * Tc
+    n = sum(counts[k_] for k_ in ("hbm_hit", "host_hit", "miss"))
+    return {
+        "tokens_per_step": tokens, "wall": wall, "ms": ms,
+        "bytes": {"request": tokens * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)},
+        "place_calls": ("request",),
+        "workload": "serving loop over two tiers of the text-keyed index (L32 H8 D128 bs16): per step one request "
+                    "of 4 texts of 1024 tokens drawn by Zipf(1.0) from 256; %d chunks resident in HBM, %d in pinned "
+                    "host memory (LRU each); demote on HBM eviction, promote on host hit, store (int8) on miss; "
+                    "then one compose of the 4 chunks" % (in_hbm, in_host),
+        "extra": {"hbm_hit_rate": counts["hbm_hit"] / n, "host_hit_rate": counts["host_hit"] / n,
+                  "miss_rate": counts["miss"] / n, "demotions": counts["demoted"],
+                  "link_bytes_per_promotion_or_demotion": chunk_bytes,
+                  "note": "counts include the warm-up requests; the request figure counts the compose bytes only; "
+                          "a miss adds a store, a host hit a copy over the link, an HBM eviction another; the "
+                          "prefill that would produce a missing text's KV is outside this path"},
+        "traffic": None,
+    }
+
+
 def cpu_baseline(kdn, cache, buf_set, order, offsets, base, T, n_slices, steps):
     """The oracle as it stands, on the host cores: the same step (store, load, compose
     of one 4096-token context, all layers), layers split over threads; once more on one
@@ -545,7 +649,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", choices=("8b", "toy", "70b_long", "batched_reuse", "host_stream_int8",
-                             "host_stream_raw", "pool_trace"),
+                             "host_stream_raw", "pool_trace", "pool_trace_tiered"),
                     default="8b")
     ap.add_argument("--fmt", choices=("int8", "int4", "fp8", "raw"), default="int8",
                     help="stored form used by the 8b and 70b_long workloads")
@@ -564,7 +668,7 @@ def main() -> int:
               "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
         return 2
     defaults = {"8b": (40, 8), "toy": (200, 20), "70b_long": (10, 3), "batched_reuse": (10, 3),
-                "host_stream_int8": (10, 3), "host_stream_raw": (10, 3), "pool_trace": (400, 100)}[args.workload]
+                "host_stream_int8": (10, 3), "host_stream_raw": (10, 3), "pool_trace": (400, 100), "pool_trace_tiered": (400, 100)}[args.workload]
     args.steps = defaults[0] if args.steps is None else args.steps
     args.warmup = defaults[1] if args.warmup is None else args.warmup
 
@@ -581,7 +685,7 @@ def main() -> int:
     res = {"8b": workload_8b, "toy": workload_toy, "70b_long": workload_70b, "batched_reuse": workload_batched,
            "host_stream_int8": lambda a, d: workload_host_stream(a, d, "int8"),
            "host_stream_raw": lambda a, d: workload_host_stream(a, d, "raw"),
-           "pool_trace": workload_pool_trace}[args.workload](args, dev)
+           "pool_trace": workload_pool_trace, "pool_trace_tiered": workload_pool_trace_tiered}[args.workload](args, dev)
 
     if args.calibration_copy:
         a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()

@@ -702,7 +702,9 @@ def test_kernels_on_chunks_in_pinned_host_memory(fmt):
     offsets = [0, 30, -20, 4000]
     O.compose(views, offsets, hd, b, 500000.0, dest=9)
     O.load(want.slice(3, 100), hd, c, 11)
-    hviews = [out.slice(100, 30), out_t, out.slice(0, 64), out.slice(50, 37)]
+    # host- and device-resident chunks side by side in one call
+    on_dev = chunk_to_dev(want)
+    hviews = [out.slice(100, 30), out_t, on_dev.slice(0, 64), out.slice(50, 37)]
     kdn.kdn_compose(hviews, offsets, dd, dev_table(b), 500000.0, dest_token_start=9)
     kdn.kdn_load_chunk(out.slice(3, 100), dd, dev_table(c), 11)
     assert_cache_equal(dd, hd)

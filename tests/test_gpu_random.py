@@ -93,3 +93,56 @@ def test_random_store_compose_patch(seed):
     O.patch_rows(rows, tok, hd, dst_bt)
     kdn.kdn_patch_rows(to_dev_bf16(rows), torch.from_numpy(tok).cuda(), dd, dev_table(dst_bt))
     assert_cache_equal(dd, hd)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_host_paths(seed):
+    """Random shapes, formats, views and stage depths through the host-memory paths: the staged
+    store, the staged compose and the kernels addressing pinned host chunks directly."""
+    rng, L, H, D, bs, fmts, n_tab, nb = _case(5000 + seed)
+    cap = n_tab * bs
+    lps = int(rng.integers(1, L + 2))
+    print("[case] host seed=%d L=%d H=%d D=%d bs=%d cap=%d lps=%d" % (seed, L, H, D, bs, cap, lps), flush=True)
+    src = host_cache(6000 + seed, L, nb, bs, H, D)
+    t_a, t_b, dst_bt = synth.disjoint_block_tables(seed, nb, [n_tab, n_tab, n_tab])
+    dsrc = dev_cache(src)
+    hch, pch = [], []                       # oracle chunks, pinned host chunks written by the library
+    for n, tab in enumerate((t_a, t_b)):
+        fmt = int(rng.choice(fmts))
+        t0 = int(rng.integers(0, cap // 2))
+        T = int(rng.integers(1, cap - t0 + 1))
+        h = O.store(src, tab, t0, T, fmt)
+        out = kdn.alloc_host_chunk(dsrc, T, fmt)
+        out.data.fill_(0x5C)
+        if n == 0:                          # staged through HBM by the copy engine
+            staging = torch.empty(kdn.kdn_store_staging_bytes(dsrc, T, fmt, lps), dtype=torch.uint8, device="cuda")
+            kdn.kdn_store_to_host(dsrc, dev_table(tab), t0, T, out, staging, lps)
+        else:                               # written across the link by the kernel itself
+            kdn.kdn_store_chunk(dsrc, dev_table(tab), t0, T, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.data.numpy(), h.data)
+        hch.append(h)
+        pch.append(out)
+    views_h, views_p, offsets, total = [], [], [], 0
+    dest = int(rng.integers(0, bs + 1))
+    for _ in range(int(rng.integers(1, 6))):
+        i = int(rng.integers(0, 2))
+        ts = int(rng.integers(0, hch[i].T))
+        Tv = int(rng.integers(1, hch[i].T - ts + 1))
+        if dest + total + Tv > cap:
+            break
+        views_h.append(hch[i].slice(ts, Tv))
+        views_p.append(pch[i].slice(ts, Tv))
+        offsets.append(int(rng.integers(-5000, 5000)) if rng.random() < 0.8 else 0)
+        total += Tv
+    if not views_h:
+        views_h, views_p, offsets = [hch[0].slice(0, 1)], [pch[0].slice(0, 1)], [3]
+        dest = 0
+    hd = host_cache(7000 + seed, L, nb, bs, H, D)
+    O.compose(views_h, offsets, hd, dst_bt, 10000.0, dest=dest)
+    d1, d2 = dev_cache(host_cache(7000 + seed, L, nb, bs, H, D)), dev_cache(host_cache(7000 + seed, L, nb, bs, H, D))
+    st = torch.empty(kdn.kdn_staging_bytes(views_p, lps), dtype=torch.uint8, device="cuda")
+    kdn.kdn_compose_from_host(views_p, offsets, d1, dev_table(dst_bt), 10000.0, st, lps, dest_token_start=dest)
+    kdn.kdn_compose(views_p, offsets, d2, dev_table(dst_bt), 10000.0, dest_token_start=dest)
+    assert_cache_equal(d1, hd)
+    assert_cache_equal(d2, hd)

@@ -305,6 +305,20 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
                                  void *staging_dev, uint64_t staging_bytes, int32_t layers_per_stage,
                                  void *stream);
 
+/* kdn_compose_from_host that also tells the engine when each stage is in place, so that
+ * it can run the layers of a stage while later stages are still crossing the link
+ * (loading overlapped with inference; Sec. 3 "Limited storage", the bandwidth of loading
+ * KV into GPU memory).  stage_done: [host] array of n_stage_events hipEvent_t (as void*),
+ * created and owned by the caller; event s is recorded on `stream` behind the kernels
+ * that place layers [s*layers_per_stage, min(L, (s+1)*layers_per_stage)): once it has
+ * completed, those layers of the request hold their final values.  n_stage_events must be
+ * ceil(num_layers / layers_per_stage), else KDN_EINVAL.  Everything else as above. */
+kdn_status kdn_compose_from_host_staged(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                                        const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                                        int32_t table_len, int32_t dest_token_start, double rope_base,
+                                        void *staging_dev, uint64_t staging_bytes, int32_t layers_per_stage,
+                                        void *const *stage_done, int32_t n_stage_events, void *stream);
+
 /* Bytes of staging memory kdn_compose_from_host needs for these chunk views at this
  * stage depth: two stages of compact rows; views of one host buffer share one staged
  * copy of the token range they span; each copy is padded to 256 bytes.  0 on invalid

@@ -430,11 +430,14 @@ kdn_status kdn_host_stage_plan(const kdn_chunk *chunks, int32_t n_chunks, int32_
     return KDN_OK;
 }
 
-kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
-                                 const kdn_cache_desc *cache, const int32_t *block_table_dev,
-                                 int32_t table_len, int32_t dest_token_start, double rope_base,
-                                 void *staging_dev, uint64_t staging_bytes, int32_t layers_per_stage,
-                                 void *stream)
+} // extern "C"
+
+// stage_done: null, or one caller-owned event per stage, recorded behind the stage's kernels
+static kdn_status compose_from_host_impl(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                                         const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                                         int32_t table_len, int32_t dest_token_start, double rope_base,
+                                         void *staging_dev, uint64_t staging_bytes, int32_t layers_per_stage,
+                                         void *const *stage_done, void *stream)
 {
     if (!chunks || !offsets || n_chunks <= 0 || !block_table_dev || table_len <= 0
         || dest_token_start < 0 || !staging_dev || layers_per_stage <= 0)
@@ -550,8 +553,40 @@ kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets
         if (hipEventRecord(ln.drained[b], user) != hipSuccess)
             return KDN_EDEVICE;
         ln.drained_valid[b] = true;
+        if (stage_done && hipEventRecord(static_cast<hipEvent_t>(stage_done[stage_no]), user) != hipSuccess)
+            return KDN_EDEVICE;
     }
     return KDN_OK;
+}
+
+extern "C" {
+
+kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                                 const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                                 int32_t table_len, int32_t dest_token_start, double rope_base,
+                                 void *staging_dev, uint64_t staging_bytes, int32_t layers_per_stage,
+                                 void *stream)
+{
+    return compose_from_host_impl(chunks, offsets, n_chunks, cache, block_table_dev, table_len, dest_token_start,
+                                  rope_base, staging_dev, staging_bytes, layers_per_stage, nullptr, stream);
+}
+
+kdn_status kdn_compose_from_host_staged(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                                        const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                                        int32_t table_len, int32_t dest_token_start, double rope_base,
+                                        void *staging_dev, uint64_t staging_bytes, int32_t layers_per_stage,
+                                        void *const *stage_done, int32_t n_stage_events, void *stream)
+{
+    if (!stage_done || !cache || layers_per_stage <= 0 || cache->num_layers <= 0)
+        return KDN_EINVAL;
+    const int32_t stages = (cache->num_layers + layers_per_stage - 1) / layers_per_stage;
+    if (n_stage_events != stages)
+        return KDN_EINVAL;
+    for (int32_t s = 0; s < stages; ++s)
+        if (!stage_done[s])
+            return KDN_EINVAL;
+    return compose_from_host_impl(chunks, offsets, n_chunks, cache, block_table_dev, table_len, dest_token_start,
+                                  rope_base, staging_dev, staging_bytes, layers_per_stage, stage_done, stream);
 }
 
 static kdn_status rope_prepare_impl(const kdn_rope_spec *variant, double rope_base, int32_t head_dim,

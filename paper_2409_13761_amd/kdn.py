@@ -126,6 +126,10 @@ def lib() -> C.CDLL:
         L.kdn_compose_from_host.argtypes = [C.POINTER(ChunkDesc), C.POINTER(i32), i32,
                                             C.POINTER(CacheDesc), vp, i32, i32, C.c_double,
                                             vp, u64, i32, vp]
+        L.kdn_compose_from_host_staged.restype = C.c_int
+        L.kdn_compose_from_host_staged.argtypes = [C.POINTER(ChunkDesc), C.POINTER(i32), i32,
+                                                   C.POINTER(CacheDesc), vp, i32, i32, C.c_double,
+                                                   vp, u64, i32, C.POINTER(vp), i32, vp]
         L.kdn_staging_bytes.restype = u64
         L.kdn_staging_bytes.argtypes = [C.POINTER(ChunkDesc), i32, i32]
         L.kdn_compose_plan.restype = C.c_int
@@ -153,7 +157,7 @@ def lib() -> C.CDLL:
 EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk", "kdn_store_tokens",
            "kdn_store_to_host", "kdn_store_staging_bytes",
            "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_rope",
-           "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host",
+           "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host", "kdn_compose_from_host_staged",
            "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec",
            "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version", "kdn_pool_create", "kdn_pool_destroy", "kdn_pool_hash", "kdn_pool_lookup",
@@ -481,16 +485,27 @@ def kdn_host_stage_plan(chunks, layers_per_stage: int, stage: int):
 
 def kdn_compose_from_host(chunks, offsets, cache: PagedCache, block_table: torch.Tensor,
                           rope_base: float, staging: torch.Tensor, layers_per_stage: int,
-                          dest_token_start: int = 0, stream=None) -> None:
+                          dest_token_start: int = 0, stream=None, stage_events=None) -> None:
+    """stage_events: optional list of torch.cuda.Event, one per stage, each recorded at least
+    once before (torch creates the HIP event on first record); the library records event s
+    behind the kernels of stage s."""
     assert block_table.dtype == torch.int32 and block_table.is_contiguous()
     assert len(chunks) == len(offsets) and staging.is_cuda and staging.is_contiguous()
     cd = cache.desc()
     arr = _chunk_array(chunks)
     off = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
-    _check(lib().kdn_compose_from_host(arr, off, len(chunks), C.byref(cd), block_table.data_ptr(),
-                                       block_table.numel(), dest_token_start, float(rope_base),
-                                       staging.data_ptr(), staging.numel() * staging.element_size(),
-                                       layers_per_stage, _stream(stream)), "kdn_compose_from_host")
+    if stage_events is None:
+        _check(lib().kdn_compose_from_host(arr, off, len(chunks), C.byref(cd), block_table.data_ptr(),
+                                           block_table.numel(), dest_token_start, float(rope_base),
+                                           staging.data_ptr(), staging.numel() * staging.element_size(),
+                                           layers_per_stage, _stream(stream)), "kdn_compose_from_host")
+        return
+    evs = (C.c_void_p * len(stage_events))(*[int(e.cuda_event) for e in stage_events])
+    _check(lib().kdn_compose_from_host_staged(arr, off, len(chunks), C.byref(cd), block_table.data_ptr(),
+                                              block_table.numel(), dest_token_start, float(rope_base),
+                                              staging.data_ptr(), staging.numel() * staging.element_size(),
+                                              layers_per_stage, evs, len(stage_events), _stream(stream)),
+           "kdn_compose_from_host_staged")
 
 
 def kdn_rope_prepare(rope_base: float, head_dim: int, offsets) -> None:

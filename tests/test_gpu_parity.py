@@ -417,6 +417,45 @@ def test_compose_from_pinned_host_chunks_equals_compose(layers_per_stage):
     assert e.value.status == kdn.EINVAL
 
 
+def test_compose_from_host_stage_events_release_layers_in_order():
+    """A second stream waits for the event of each stage and snapshots that stage's layers
+    while later stages are still being streamed: every snapshot already holds the oracle's
+    final values."""
+    L, nb, bs, H, D = 6, 64, 16, 2, 128
+    lps = 2
+    _say("compose_from_host_staged")
+    src = host_cache(81, L, nb, bs, H, D)
+    t1, t2, dst_bt = synth.disjoint_block_tables(81, nb, [8, 8, 20])
+    a, b = O.store(src, t1, 0, 128, INT8), O.store(src, t2, 0, 120, FP8)
+    views, offsets = [a.slice(5, 100), b, a.slice(0, 60)], [17, 0, 2000]
+    hd = host_cache(82, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    O.compose(views, offsets, hd, dst_bt, 500000.0, dest=3)
+    ha, hb = kdn.pinned_host_copy(chunk_to_dev(a)), kdn.pinned_host_copy(chunk_to_dev(b))
+    hviews = [ha.slice(5, 100), hb, ha.slice(0, 60)]
+    staging = torch.empty(kdn.kdn_staging_bytes(hviews, lps), dtype=torch.uint8, device="cuda")
+    events = [torch.cuda.Event() for _ in range(L // lps)]
+    for e in events:
+        e.record()
+    side = torch.cuda.Stream()
+    snaps = []
+    kdn.kdn_compose_from_host(hviews, offsets, dd, dev_table(dst_bt), 500000.0, staging, lps,
+                              dest_token_start=3, stage_events=events)
+    with torch.cuda.stream(side):
+        for s, e in enumerate(events):
+            side.wait_event(e)
+            snaps.append((dd.k[s * lps:(s + 1) * lps].clone(), dd.v[s * lps:(s + 1) * lps].clone()))
+    torch.cuda.synchronize()
+    for s, (ks, vs) in enumerate(snaps):
+        assert np.array_equal(bits_of(ks), hd.k[s * lps:(s + 1) * lps]), "K of stage %d" % s
+        assert np.array_equal(bits_of(vs), hd.v[s * lps:(s + 1) * lps]), "V of stage %d" % s
+    assert_cache_equal(dd, hd)
+    with pytest.raises(kdn.KdnError) as e:                      # one event per stage, no fewer
+        kdn.kdn_compose_from_host(hviews, offsets, dd, dev_table(dst_bt), 500000.0, staging, lps,
+                                  dest_token_start=3, stage_events=events[:2])
+    assert e.value.status == kdn.EINVAL
+
+
 # ------------------------------------------------------------------ RoPE variants, patching
 @pytest.mark.parametrize("fmt", [RAW, INT8, INT4, FP8])
 @pytest.mark.parametrize("variant", [

@@ -96,3 +96,49 @@ def test_plan_refuses_a_chunk_whose_bytes_do_not_cover_its_layout():
     with pytest.raises(kdn.KdnError) as e:
         kdn.kdn_host_stage_plan([short], 2, 0)
     assert e.value.status == kdn.ESIZE
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_plans_stage_the_stored_rows(seed):
+    """Random shapes, forms, views and stage depths: carrying the planned copies out always
+    yields, per view, the stored chunk of the stage's layers over the spanned tokens."""
+    rng = np.random.default_rng(900 + seed)
+    l_, h_ = int(rng.integers(1, 7)), int(rng.integers(1, 5))
+    d_ = int(rng.choice([16, 32, 64, 96, 128, 256]))
+    lps = int(rng.integers(1, l_ + 2))
+    parents = []
+    for _ in range(int(rng.integers(1, 4))):
+        fmt = int(rng.choice([f for f in (RAW, INT8, INT4, FP8) if f != INT4 or d_ % 32 == 0]))
+        tp = int(rng.integers(1, 70))
+        data = rng.integers(0, 256, size=O.chunk_bytes(l_, h_, d_, tp, fmt), dtype=np.uint8)
+        parents.append(O.Chunk(data, fmt, l_, h_, d_, tp))
+    views = []
+    for _ in range(int(rng.integers(1, 7))):
+        p = parents[int(rng.integers(0, len(parents)))]
+        ts = int(rng.integers(0, p.Tp))
+        views.append(p.slice(ts, int(rng.integers(1, p.Tp - ts + 1))))
+    bviews = [_binding_chunk(v) for v in views]
+    half = kdn.kdn_staging_bytes(bviews, lps) // 2
+    span = {}
+    for v in views:
+        lo, hi = span.get(id(v.data), (v.tok_start, v.tok_start + v.T))
+        span[id(v.data)] = (min(lo, v.tok_start), max(hi, v.tok_start + v.T))
+    for stage in range(-(-l_ // lps)):
+        l0, lg = stage * lps, min(lps, l_ - stage * lps)
+        copies, view_off = kdn.kdn_host_stage_plan(bviews, lps, stage)
+        staging = np.zeros(half, dtype=np.uint8)
+        for c in copies:
+            srcbuf = views[c["chunk"]].data
+            for r in range(c["rows"]):
+                s, t = c["src_offset"] + r * c["src_pitch"], c["dst_offset"] + r * c["width"]
+                assert s + c["width"] <= srcbuf.nbytes and t + c["width"] <= half
+                staging[t:t + c["width"]] = srcbuf[s:s + c["width"]]
+        for v, off in zip(views, view_off):
+            lo, hi = span[id(v.data)]
+            n = O.chunk_bytes(lg, h_, d_, hi - lo, v.fmt)
+            image = O.Chunk(np.ascontiguousarray(staging[off:off + n]), v.fmt, lg, h_, d_, hi - lo)
+            got_c, got_s = _typed(image)
+            want_c, want_s = _typed(O.Chunk(v.data, v.fmt, l_, h_, d_, v.Tp))
+            assert np.array_equal(got_c, want_c[l0:l0 + lg, :, lo:hi])
+            if want_s is not None:
+                assert np.array_equal(got_s.view(np.uint32), want_s[l0:l0 + lg, :, lo:hi].view(np.uint32))

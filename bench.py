@@ -220,12 +220,27 @@ def workload_toy(args, dev):
         rec("compose", lambda: kdn.kdn_compose([c1, c2], offsets, cache, dst, w.rope_base))
 
     wall, ms = Timed(("store", "compose"), args.steps).run(step, args.warmup)
+    # the same three launches captured once into a HIP graph and replayed (kernels only: the
+    # cos/sin rows are resident and the segments travel in the kernel arguments)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(0, lambda name, fn: fn())
+    for _ in range(args.warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_wall = time.perf_counter() - t0
     bytes_call = 512 * (sh.paged_bytes_per_token + sh.stored_bytes_per_token(args.fmt))
     return {
         "tokens_per_step": 512, "wall": wall, "ms": ms, "bytes": {n: bytes_call for n in ms},
         "place_calls": ("compose",),
         "workload": "toy KV (L2 H4 D64 bs16, 128 blocks): per step store two 256-token chunks to %s "
                     "(two calls) and compose them at offsets 0 and 256, base 10000; latency bound" % args.fmt,
+        "extra": {"ms_per_step_as_hip_graph_replay": graph_wall / args.steps * 1e3,
+                  "tokens_per_s_as_hip_graph_replay": 512 * args.steps / graph_wall},
         "traffic": None,
     }
 

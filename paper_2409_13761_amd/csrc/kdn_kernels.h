@@ -372,10 +372,12 @@ __device__ __forceinline__ T load_stored(const uint8_t *ptr)
     return __builtin_nontemporal_load(q);
 }
 
-// VAR selects the RoPE variants (partial rotary, interleaved pairs): lanes of the rotary
-// part keep the 8 + 8 paired ownership (half-split) or own 16 consecutive elements whose
-// pairs are neighbours (interleaved); lanes beyond the rotary part own 16 consecutive
-// elements and never rotate.
+// VAR selects the RoPE variants (partial rotary, interleaved pairs).  Every lane keeps the
+// 8 + 8 ownership, so that a store instruction writes whole runs whatever the variant: a
+// lane of the rotary part owns 8 elements of its lower half and the 8 at the same place of
+// its upper half (half-split: these pair up; interleaved: each vector holds 4 neighbouring
+// pairs of its own); the part behind the rotary one is split into halves the same way and
+// never rotates.
 template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 {
@@ -421,14 +423,11 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
         const int rl = p.rot >> 4; // lanes of the rotary part
         interleaved = p.pairing == KDN_ROPE_INTERLEAVED;
         rot_lane = sub < rl;
-        if (interleaved) {
-            lo_off = sub * 16;
-            hi_off = lo_off + 8;
-        } else if (rot_lane) {
+        if (rot_lane) {
             hi_off = (p.rot >> 1) + sub * 8;
-        } else {
-            lo_off = p.rot + (sub - rl) * 16;
-            hi_off = lo_off + 8;
+        } else { // the part behind the rotary one is split into halves the same way
+            lo_off = p.rot + (sub - rl) * 8;
+            hi_off = lo_off + ((D - p.rot) >> 1);
         }
     }
     const int rhalf = VAR ? p.rot >> 1 : half; // entries of a cos/sin row
@@ -440,9 +439,19 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
             s_cs[i] = row[i];
         __syncthreads();
         if (sub < R && rot_lane) {
+            if (VAR && interleaved) {
+                // each 8-element vector holds 4 whole pairs: pairs sub*4.. of the lower
+                // half of the rotary part, and the same of its upper half
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                cs[e] = s_cs[sub * 8 + e];
+                for (int e = 0; e < 4; ++e) {
+                    cs[e] = s_cs[sub * 4 + e];
+                    cs[4 + e] = s_cs[(p.rot >> 2) + sub * 4 + e];
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    cs[e] = s_cs[sub * 8 + e];
+            }
         }
     }
     if (sub >= R)

@@ -577,6 +577,192 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
     }
 }
 
+// the 8 values that the stored words of 8 consecutive elements stand for
+template <int FMT>
+__device__ __forceinline__ void dequantise8(const uint32_t *w, float scale, float *x)
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if (FMT == KDN_FMT_RAW_BF16)
+            x[e] = (e & 1) ? bf16_hi(w[e >> 1]) : bf16_lo(w[e >> 1]);
+        else if (FMT == KDN_FMT_INT4_GROUP32)
+            x[e] = (float)((int32_t)(w[0] << (28 - 4 * e)) >> 28) * scale;
+        else if (FMT == KDN_FMT_FP8_ROWSCALE)
+            x[e] = fp8_f32(w[e >> 2], e & 3) * scale;
+        else
+            x[e] = code_f32(w[e >> 2], e & 3) * scale;
+    }
+}
+
+// place with row-contiguous ownership, for head dims where half a row is not a whole
+// number of 128-byte lines (head_dim not a multiple of 128; k_place serves the others).
+// D/8 lanes own a row, 8 consecutive elements each, and a wavefront takes 64/(D/8) whole
+// rows at a time, so every load and store instruction covers rows back to back.  A lane
+// of a half-split rotary pair fetches the stored words of its partner, the lane rot/16
+// places away, with ds_bpermute, dequantises both and forms its own 8 outputs:
+// out = fma(partner, -+sin, own*cos), which is the pair rotation read from either side.
+// Interleaved pairs lie inside a lane's own 8 elements.  All lanes stay active through
+// the exchange; loads and stores are predicated instead.
+// Grid as k_place.
+template <int DT, int FMT, bool DENSE, bool REUSE, typename Segs>
+__global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
+{
+    constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 4 : 8;
+    constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT4_GROUP32 ? 1 : 2; // words per 8 stored elements
+    const int D = DT ? DT : p.c.D;
+    const int R8 = D >> 3;   // lanes per row
+    const int RW = 64 / R8;  // rows per wavefront and pass
+    const int H = p.c.H, G = p.c.G, bs = p.c.bs;
+    const int L2 = 2 * p.c.L;
+
+    const Seg &sg = segs.at(blockIdx.y);
+    const int S = sg.S, T = sg.T;
+    const int piece = blockIdx.x / L2;
+    const int ls = blockIdx.x - piece * L2;
+    const int gi = S / G + piece;
+    const int tok_lo = max(S, gi * G);
+    const int tok_hi = min(S + T, (gi + 1) * G);
+    if (tok_lo >= tok_hi)
+        return;
+    const int blk = sg.bt[tok_lo / bs];
+    const int slot0 = tok_lo % bs;
+    uint16_t *tile = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(p.layer0 + (ls >> 1)) * p.c.layer_stride
+                     + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
+    const int Tp = sg.Tp;
+    const int64_t row_base = ((int64_t)ls * Tp + sg.tok0 + (tok_lo - S)) * H;
+    const int64_t total_rows = (int64_t)p.c.L * 2 * Tp * H;
+    const int n_rows = (tok_hi - tok_lo) * H;
+    const uint8_t *data = sg.data + ((row_base * D * W) >> 1); // first stored row of this tile
+    const int spr = FMT == KDN_FMT_INT4_GROUP32 ? D >> 5 : 1;  // scales per row
+    const float *scales = reinterpret_cast<const float *>(sg.data + ((total_rows * D * W) >> 1)) + row_base * spr;
+    const bool rotate = (ls & 1) == 0 && sg.rope_row >= 0;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rw = lane / R8; // row of the wavefront's batch that this lane serves
+    const int sub = lane - rw * R8;
+    const bool lane_ok = rw < RW;
+    // the lane's part in the rotation
+    const bool interleaved = p.pairing == KDN_ROPE_INTERLEAVED;
+    const bool rot_lane = rotate && lane_ok && sub < (p.rot >> 3);
+    const int hl = p.rot >> 4; // lanes of half the rotary part
+    const bool lo_lane = sub < hl;
+    const bool exchange = rotate && !interleaved; // uniform over the workgroup
+    const int partner = (rot_lane && !interleaved) ? (lo_lane ? lane + hl : lane - hl) : lane;
+    __shared__ f32x2 s_cs[kMaxHeadDim / 2];
+    f32x2 cs[8];
+    if (rotate) {
+        const int rhalf = p.rot >> 1;
+        const f32x2 *row = p.rope + (int64_t)sg.rope_row * rhalf;
+        for (int i = threadIdx.x; i < rhalf; i += kThreads)
+            s_cs[i] = row[i];
+        __syncthreads();
+        if (rot_lane) {
+            if (interleaved) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    cs[e] = s_cs[sub * 4 + e];
+            } else {
+                const int j0 = (lo_lane ? sub : sub - hl) * 8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    cs[e] = s_cs[j0 + e];
+                    if (lo_lane)
+                        cs[e].y = -cs[e].y; // lower element: own*cos - partner*sin
+                }
+            }
+        }
+    }
+
+    const int rows_pass = (kThreads / 64) * RW;
+    for (int b = 0; b < n_rows; b += rows_pass * U) { // same trip count for every lane
+        uint32_t w[U][W];
+        float sc[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = b + u * rows_pass + wave * RW + rw;
+#pragma unroll
+            for (int i = 0; i < W; ++i)
+                w[u][i] = 0;
+            sc[u] = 0.0f;
+            if (lane_ok && r < n_rows) {
+                const uint8_t *src = data + (((uint32_t)(r * D + sub * 8) * W) >> 1);
+                if (FMT == KDN_FMT_INT4_GROUP32) {
+                    w[u][0] = load_stored<uint32_t, REUSE>(src);
+                    sc[u] = scales[r * spr + (sub >> 2)];
+                } else if (FMT == KDN_FMT_RAW_BF16) {
+                    const u32x4 v4 = load_stored<u32x4, REUSE>(src);
+#pragma unroll
+                    for (int i = 0; i < W; ++i)
+                        w[u][i] = v4[i & 3];
+                } else {
+                    const u32x2 v2 = load_stored<u32x2, REUSE>(src);
+#pragma unroll
+                    for (int i = 0; i < W; ++i)
+                        w[u][i] = v2[i & 1];
+                    sc[u] = scales[r];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int r = b + u * rows_pass + wave * RW + rw;
+            uint32_t pw[W];
+            float psc = sc[u];
+            if (exchange) {
+#pragma unroll
+                for (int i = 0; i < W; ++i)
+                    pw[i] = (uint32_t)__builtin_amdgcn_ds_bpermute(partner << 2, (int)w[u][i]);
+                if (FMT == KDN_FMT_INT4_GROUP32) // the partner's group has a scale of its own
+                    psc = __int_as_float(__builtin_amdgcn_ds_bpermute(partner << 2, __float_as_int(sc[u])));
+            } else {
+#pragma unroll
+                for (int i = 0; i < W; ++i)
+                    pw[i] = 0;
+            }
+            if (!lane_ok || r >= n_rows)
+                continue;
+            uint16_t *dst; // the row's first element
+            if (DENSE) {
+                dst = tile + (uint32_t)(r * D);
+            } else {
+                const int tok = r / H, h = r - tok * H;
+                dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
+            }
+            u32x4 out;
+            if (FMT == KDN_FMT_RAW_BF16 && !rot_lane) { // bit copy
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    out[i] = w[u][i % W];
+            } else {
+                float x[8];
+                dequantise8<FMT>(w[u], sc[u], x);
+                if (rot_lane && interleaved) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float c = cs[e].x, s = cs[e].y;
+                        const float x0 = x[2 * e], x1 = x[2 * e + 1];
+                        const float x0c = x0 * c, x1c = x1 * c;
+                        x[2 * e] = __builtin_fmaf(-x1, s, x0c);
+                        x[2 * e + 1] = __builtin_fmaf(x0, s, x1c);
+                    }
+                } else if (rot_lane) {
+                    float y[8];
+                    dequantise8<FMT>(pw, psc, y);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float xc = x[e] * cs[e].x;
+                        x[e] = __builtin_fmaf(y[e], cs[e].y, xc);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    out[i] = pack_bf16(x[2 * i], x[2 * i + 1]);
+            }
+            __builtin_nontemporal_store(out, reinterpret_cast<u32x4 *>(dst + sub * 8));
+        }
+    }
+}
+
 // patch: rows [L][2][n][H][D] replace the rows of n request tokens (bit copy).
 // One workgroup per (token, layer, side); a token outside the table is skipped.
 struct PatchP {

@@ -375,15 +375,46 @@ void launch_place(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_d
     }
 }
 
+// the row-contiguous kernel; the RoPE variant is a run-time matter there
+template <int DT, int FMT>
+void launch_place_c(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
+                    hipStream_t st)
+{
+    const int flavour = !p.c.dense ? 0 : p.reuse ? 2 : 1;
+    if (segs_dev) {
+        SegsDevice sd{segs_dev};
+        if (flavour == 0)
+            hipLaunchKernelGGL((k_place_c<DT, FMT, false, false, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+        else if (flavour == 1)
+            hipLaunchKernelGGL((k_place_c<DT, FMT, true, false, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+        else
+            hipLaunchKernelGGL((k_place_c<DT, FMT, true, true, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+    } else {
+        SegsInline si;
+        std::memset(&si, 0, sizeof si);
+        std::memcpy(si.s, segs, (size_t)n * sizeof(Seg));
+        if (flavour == 0)
+            hipLaunchKernelGGL((k_place_c<DT, FMT, false, false, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+        else if (flavour == 1)
+            hipLaunchKernelGGL((k_place_c<DT, FMT, true, false, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+        else
+            hipLaunchKernelGGL((k_place_c<DT, FMT, true, true, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+    }
+}
+
+// k_place where half a row is a whole number of 128-byte lines, k_place_c elsewhere
 template <int FMT>
 void launch_place_d(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
                     hipStream_t st)
 {
-    switch (p.c.D) {
-    case 64: launch_place<64, FMT>(p, segs, n, segs_dev, grid, st); break;
-    case 128: launch_place<128, FMT>(p, segs, n, segs_dev, grid, st); break;
-    default: launch_place<0, FMT>(p, segs, n, segs_dev, grid, st); break;
-    }
+    if (p.c.D == 128)
+        launch_place<128, FMT>(p, segs, n, segs_dev, grid, st);
+    else if (p.c.D % 128 == 0)
+        launch_place<0, FMT>(p, segs, n, segs_dev, grid, st);
+    else if (p.c.D == 64)
+        launch_place_c<64, FMT>(p, segs, n, segs_dev, grid, st);
+    else
+        launch_place_c<0, FMT>(p, segs, n, segs_dev, grid, st);
 }
 
 // Enqueue the placement of `segs` (all of one format).  Up to kMaxInlineSegs travel

@@ -59,8 +59,9 @@ struct CacheP {
     uint16_t *k, *v;
     int64_t layer_stride, block_stride, token_stride, head_stride;
     int32_t L, H, D, bs;
-    int32_t G;     // tokens per group; divides bs
-    int32_t dense; // head_stride == D and token_stride == H*D
+    int32_t G;         // tokens per group; divides bs unless per_token
+    int32_t dense;     // head_stride == D and token_stride == H*D (and one block per group)
+    int32_t per_token; // blocks smaller than a group: every row resolves its own token's block
 };
 
 struct StoreP {
@@ -206,8 +207,9 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     const int tok_hi = min(p.t0 + p.T, (gi + 1) * G);
     if (tok_lo >= tok_hi)
         return;
-    // a token list (strided instantiation only) resolves every row's token by itself
-    const bool listed = !DENSE && p.tokens != nullptr;
+    // a token list, or blocks smaller than the group (strided instantiation only): every
+    // row resolves its token by itself
+    const bool listed = !DENSE && (p.tokens != nullptr || p.c.per_token);
     const uint16_t *plane = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(p.layer0 + (ls >> 1)) * p.c.layer_stride;
     const int blk = listed ? 0 : p.bt[tok_lo / bs];
     const int slot0 = listed ? 0 : tok_lo % bs;
@@ -238,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
                 } else {
                     const int tok = r / H, h = r - tok * H;
                     if (listed) {
-                        const int t = min(max(p.tokens[tok_lo + tok], 0), p.limit - 1);
+                        const int t = p.tokens ? min(max(p.tokens[tok_lo + tok], 0), p.limit - 1) : tok_lo + tok;
                         src = plane + (int64_t)p.bt[t / bs] * p.c.block_stride + (int64_t)(t % bs) * p.c.token_stride
                               + (int64_t)h * p.c.head_stride + sub * 8;
                     } else {
@@ -403,8 +405,8 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
         return;
     const int blk = sg.bt[tok_lo / bs];
     const int slot0 = tok_lo % bs;
-    uint16_t *tile = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(p.layer0 + (ls >> 1)) * p.c.layer_stride
-                     + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
+    uint16_t *plane = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(p.layer0 + (ls >> 1)) * p.c.layer_stride;
+    uint16_t *tile = plane + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
     const int Tp = sg.Tp;
     const int64_t row_base = ((int64_t)ls * Tp + sg.tok0 + (tok_lo - S)) * H;
     const int64_t total_rows = (int64_t)p.c.L * 2 * Tp * H;
@@ -504,7 +506,13 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
                 dst = tile + (uint32_t)(r * D);
             } else {
                 const int tok = r / H, h = r - tok * H;
-                dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
+                if (p.c.per_token) {
+                    const int t = tok_lo + tok;
+                    dst = plane + (int64_t)sg.bt[t / bs] * p.c.block_stride + (int64_t)(t % bs) * p.c.token_stride
+                          + (int64_t)h * p.c.head_stride;
+                } else {
+                    dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
+                }
             }
             u32x4 olo, ohi;
             if (FMT == KDN_FMT_RAW_BF16 && !rotate_lane) { // bit copy
@@ -626,8 +634,8 @@ __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
         return;
     const int blk = sg.bt[tok_lo / bs];
     const int slot0 = tok_lo % bs;
-    uint16_t *tile = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(p.layer0 + (ls >> 1)) * p.c.layer_stride
-                     + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
+    uint16_t *plane = ((ls & 1) ? p.c.v : p.c.k) + (int64_t)(p.layer0 + (ls >> 1)) * p.c.layer_stride;
+    uint16_t *tile = plane + (int64_t)blk * p.c.block_stride + (int64_t)slot0 * p.c.token_stride;
     const int Tp = sg.Tp;
     const int64_t row_base = ((int64_t)ls * Tp + sg.tok0 + (tok_lo - S)) * H;
     const int64_t total_rows = (int64_t)p.c.L * 2 * Tp * H;
@@ -726,7 +734,13 @@ __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
                 dst = tile + (uint32_t)(r * D);
             } else {
                 const int tok = r / H, h = r - tok * H;
-                dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
+                if (p.c.per_token) {
+                    const int t = tok_lo + tok;
+                    dst = plane + (int64_t)sg.bt[t / bs] * p.c.block_stride + (int64_t)(t % bs) * p.c.token_stride
+                          + (int64_t)h * p.c.head_stride;
+                } else {
+                    dst = tile + (int64_t)tok * p.c.token_stride + (int64_t)h * p.c.head_stride;
+                }
             }
             u32x4 out;
             if (FMT == KDN_FMT_RAW_BF16 && !rot_lane) { // bit copy

@@ -16,6 +16,7 @@
 namespace kdn_impl {
 
 constexpr int kFormats = 4; // kdn_format values
+constexpr int kPerTokenMaxBlock = 3; // block sizes served by per-token block lookup
 
 // Resolved RoPE variant of one call: frequencies either derived from `base` or given.
 struct RopeSpec {
@@ -129,10 +130,18 @@ inline CacheP make_cache_p(const kdn_cache_desc *c)
     p.H = c->num_kv_heads;
     p.D = c->head_dim;
     p.bs = c->block_size;
-    // token group: a whole block when it is small, else 16-token pieces of it
+    // token group: 16-token pieces of a block, or a whole block of another size; blocks of
+    // a few tokens would leave most of a workgroup idle, so there a group is 16 tokens
+    // whose rows each look their own block up
     p.G = (c->block_size > 16 && c->block_size % 16 == 0) ? 16 : c->block_size;
     p.dense = (c->head_stride == c->head_dim
                && c->token_stride == (int64_t)c->num_kv_heads * c->head_dim);
+    p.per_token = 0;
+    if (c->block_size <= kPerTokenMaxBlock) {
+        p.G = 16;
+        p.per_token = 1;
+        p.dense = 0;
+    }
     return p;
 }
 

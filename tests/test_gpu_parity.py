@@ -34,6 +34,8 @@ def _say(msg):
     (1, 20, 8, 2, 96, 3, 100),         # head_dim whose lane group is padded
     (1, 10, 16, 2, 256, 1, 77),
     (1, 6, 16, 1, 512, 0, 40),         # largest head_dim
+    (2, 30, 3, 2, 64, 4, 70),          # blocks of 3 tokens: rows look their own block up
+    (2, 64, 2, 3, 128, 1, 90),         # blocks of 2 tokens
 ])
 def test_store_matches_oracle(fmt, shape):
     L, nb, bs, H, D, t0, T = shape
@@ -130,6 +132,8 @@ def test_store_strided_cache():
     (1, 20, 8, 2, 96, 3, 100),
     (1, 10, 16, 2, 256, 1, 77),
     (1, 6, 16, 1, 512, 0, 40),
+    (2, 30, 3, 2, 64, 4, 70),
+    (2, 64, 2, 3, 128, 1, 90),
 ])
 def test_load_matches_oracle_and_touches_nothing_else(fmt, shape):
     L, nb, bs, H, D, dest, T = shape

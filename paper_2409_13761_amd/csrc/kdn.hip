@@ -112,7 +112,7 @@ static kdn_status store_launch(const kdn_cache_desc *cache, const int32_t *block
     p.tokens = tokens_dev;
     p.limit = (int32_t)std::min<int64_t>((int64_t)table_len * cache->block_size, 0x7fffffff);
     if (tokens_dev)
-        p.c.G = 16; // list entries need no block alignment
+        p.c.G = std::max(p.c.G, 16); // list entries need no block alignment
     const int64_t groups = groups_spanned(token_start, num_tokens, p.c.G);
     if (groups * 2 * p.c.L > 0x7fffffff / kThreads)
         return KDN_ESIZE;

@@ -17,6 +17,8 @@ namespace kdn_impl {
 
 constexpr int kFormats = 4; // kdn_format values
 constexpr int kPerTokenMaxBlock = 3; // block sizes served by per-token block lookup
+constexpr int64_t kTileElements = 16384;     // elements a workgroup owns at the common shapes (16 tokens x 8 heads x 128)
+constexpr int64_t kSmallTileElements = 2048; // a tile this small is widened (measured: at 4096 it no longer pays)
 
 // Resolved RoPE variant of one call: frequencies either derived from `base` or given.
 struct RopeSpec {
@@ -141,6 +143,19 @@ inline CacheP make_cache_p(const kdn_cache_desc *c)
         p.G = 16;
         p.per_token = 1;
         p.dense = 0;
+    }
+    // one or two short heads: widen the group until a workgroup owns kTileElements again
+    const int64_t per_token_elems = (int64_t)c->num_kv_heads * c->head_dim;
+    if ((int64_t)p.G * per_token_elems <= kSmallTileElements) {
+        const int32_t want = (int32_t)((kTileElements + per_token_elems - 1) / per_token_elems);
+        const int32_t wide = std::min((want + 15) / 16 * 16, 256);
+        if (wide > p.G) {
+            p.G = wide;
+            if (c->block_size % wide != 0) { // the group spans blocks
+                p.per_token = 1;
+                p.dense = 0;
+            }
+        }
     }
     return p;
 }

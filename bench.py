@@ -19,7 +19,8 @@ compose per step).
 
 "pool_trace" is a serving loop over the text-keyed index (store on miss, compose on
 hit) and reports the hit rate; "pool_trace_tiered" adds a host-memory tier under it
-(demote on eviction, promote on hit).  "host_stream_int8" / "host_stream_raw" compose a chunk that lives in pinned host memory
+(demote on eviction, promote on hit).  "sweep" times store and compose over a range of
+model shapes (head_dim 64..512, 1..32 KV heads) and paged block sizes (1..128).  "host_stream_int8" / "host_stream_raw" compose a chunk that lives in pinned host memory
 (the rate there includes PCIe and is link bound; its roofline entry is still priced
 against HBM and is not a kernel-quality figure).
 
@@ -585,6 +586,107 @@ def workload_pool_trace_tiered(args, dev):
     }
 
 
+SWEEP_SHAPES = (
+    # (L, H, D, block size, note): 4096 tokens each, stored and composed back as 8 shifted slices
+    (32, 8, 128, 16, "Llama-3-8B shape (the default workload's)"),
+    (32, 32, 128, 16, "32 KV heads (no grouped-query sharing)"),
+    (32, 16, 64, 16, "head_dim 64"),
+    (32, 8, 96, 16, "head_dim 96"),
+    (24, 8, 192, 16, "head_dim 192"),
+    (16, 8, 256, 16, "head_dim 256"),
+    (8, 8, 512, 16, "head_dim 512"),
+    (64, 1, 128, 16, "one KV head"),
+    (64, 2, 64, 16, "two KV heads of 64"),
+    (32, 8, 128, 1, "block size 1 (paging by the token)"),
+    (32, 8, 128, 2, "block size 2"),
+    (32, 8, 128, 8, "block size 8"),
+    (32, 8, 128, 32, "block size 32"),
+    (32, 8, 128, 128, "block size 128"),
+)
+
+
+def workload_sweep(args, dev):
+    """The store and compose kernels over a range of model shapes and paged block sizes:
+    4096 tokens stored and composed back as 8 shifted slices, per shape, stored form
+    (--fmt) and RoPE pairing.  One row of config.rows per shape; `value` is the default
+    shape's tokens/s over store + compose."""
+    import torch
+    from paper_2409_13761_amd import kdn, synth
+
+    T, n_slices, n_sets = 4096, 8, 4
+    fmt = FMT_IDS[args.fmt]
+    offsets = [j * (T // n_slices) for j in range(n_slices)]
+    rows, first = [], None
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    for (L, H, D, bs, note) in SWEEP_SHAPES:
+        if args.fmt == "int4" and D % 32:
+            continue
+        blocks = T // bs
+        nb = blocks * 2 * n_sets
+        g = torch.Generator(device=dev)
+        g.manual_seed(1002)
+        k = torch.empty((L, nb, bs, H, D), device=dev, dtype=torch.bfloat16)
+        v = torch.empty_like(k)
+        fill_normal(k, g)
+        fill_normal(v, g)
+        cache = kdn.PagedCache(k, v)
+        tabs = [torch.from_numpy(t).to(dev) for t in synth.disjoint_block_tables(1002, nb, [blocks] * (2 * n_sets))]
+        chunks = [kdn.alloc_chunk(cache, T, fmt) for _ in range(n_sets)]
+        kdn.kdn_rope_prepare(500000.0, D, offsets)
+        per_tok = L * 2 * H * D * 2 + kdn.kdn_chunk_bytes(L, H, D, 1, fmt)
+        row = {"L": L, "H": H, "D": D, "block_size": bs, "note": note, "bytes_per_call": T * per_tok}
+        for pairing in ("half_split", "interleaved"):
+            spec = kdn.rope_spec(500000.0, None, 0, kdn.ROPE_INTERLEAVED if pairing == "interleaved"
+                                 else kdn.ROPE_HALF_SPLIT)
+
+            def store(i):
+                kdn.kdn_store_chunk(cache, tabs[2 * (i % n_sets)], 0, T, chunks[i % n_sets])
+
+            def compose(i):
+                s = (i + 2) % n_sets              # a chunk stored two steps ago, not the cached one
+                views = [chunks[s].slice(j * (T // n_slices), T // n_slices) for j in range(n_slices)]
+                kdn.kdn_compose_rope(views, offsets, cache, tabs[2 * s + 1], spec)
+
+            for i in range(n_sets):
+                store(i)
+            for i in range(n_sets):
+                compose(i)
+            torch.cuda.synchronize()
+            marks = []
+            for i in range(args.steps):
+                a_, b_, c_ = ev(), ev(), ev()
+                a_.record()
+                store(i)
+                b_.record()
+                compose(i)
+                c_.record()
+                marks.append((a_, b_, c_))
+            torch.cuda.synchronize()
+            ms_store = sum(x.elapsed_time(y) for x, y, _ in marks) / args.steps
+            ms_comp = sum(y.elapsed_time(z) for _, y, z in marks) / args.steps
+            row[pairing] = {"store_ms": ms_store, "store_GBps": T * per_tok / ms_store / 1e6,
+                            "compose_ms": ms_comp, "compose_GBps": T * per_tok / ms_comp / 1e6}
+        rows.append(row)
+        if first is None:
+            first = row
+        del k, v, cache, chunks, tabs
+        torch.cuda.empty_cache()
+    ms = {"store": first["half_split"]["store_ms"], "compose": first["half_split"]["compose_ms"]}
+    return {
+        "tokens_per_step": T, "wall": (ms["store"] + ms["compose"]) * 1e-3 * args.steps, "ms": ms,
+        "bytes": {n: first["bytes_per_call"] for n in ms},
+        "place_calls": ("compose",),
+        "workload": "sweep over KV shapes and paged block sizes, %s stored form: per shape 4096 tokens stored "
+                    "and composed back as 8x512-token shifted slices (base 500000), half-split and interleaved "
+                    "RoPE pairing; the headline fields are the first row's" % args.fmt,
+        "extra": {"rows": rows},
+        "traffic": None,
+    }
+
+
 def cpu_baseline(kdn, cache, buf_set, order, offsets, base, T, n_slices, steps):
     """The oracle as it stands, on the host cores: the same step (store, load, compose
     of one 4096-token context, all layers), layers split over threads; once more on one
@@ -664,7 +766,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", choices=("8b", "toy", "70b_long", "batched_reuse", "host_stream_int8",
-                             "host_stream_raw", "pool_trace", "pool_trace_tiered"),
+                             "host_stream_raw", "pool_trace", "pool_trace_tiered", "sweep"),
                     default="8b")
     ap.add_argument("--fmt", choices=("int8", "int4", "fp8", "raw"), default="int8",
                     help="stored form used by the 8b and 70b_long workloads")
@@ -683,7 +785,7 @@ def main() -> int:
               "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
         return 2
     defaults = {"8b": (40, 8), "toy": (200, 20), "70b_long": (10, 3), "batched_reuse": (10, 3),
-                "host_stream_int8": (10, 3), "host_stream_raw": (10, 3), "pool_trace": (400, 100), "pool_trace_tiered": (400, 100)}[args.workload]
+                "host_stream_int8": (10, 3), "host_stream_raw": (10, 3), "pool_trace": (400, 100), "pool_trace_tiered": (400, 100), "sweep": (8, 0)}[args.workload]
     args.steps = defaults[0] if args.steps is None else args.steps
     args.warmup = defaults[1] if args.warmup is None else args.warmup
 
@@ -700,7 +802,7 @@ def main() -> int:
     res = {"8b": workload_8b, "toy": workload_toy, "70b_long": workload_70b, "batched_reuse": workload_batched,
            "host_stream_int8": lambda a, d: workload_host_stream(a, d, "int8"),
            "host_stream_raw": lambda a, d: workload_host_stream(a, d, "raw"),
-           "pool_trace": workload_pool_trace, "pool_trace_tiered": workload_pool_trace_tiered}[args.workload](args, dev)
+           "pool_trace": workload_pool_trace, "pool_trace_tiered": workload_pool_trace_tiered, "sweep": workload_sweep}[args.workload](args, dev)
 
     if args.calibration_copy:
         a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()

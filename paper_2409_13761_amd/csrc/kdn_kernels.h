@@ -225,12 +225,13 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     const int sub = threadIdx.x & (P - 1);
     const int lane = __lane_id();
     const int grp_addr = (lane & ~(P - 1)) << 2; // byte address of the group's first lane for bpermute
+    const int NT = blockDim.x; // a small tile is launched with fewer wavefronts
 
-    for (int base = 0; base < n_items; base += kThreads * U) {
+    for (int base = 0; base < n_items; base += NT * U) {
         u32x4 w[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int it = base + u * kThreads + threadIdx.x;
+            const int it = base + u * NT + threadIdx.x;
             const int r = it >> LOGP;
             w[u] = u32x4{0, 0, 0, 0};
             if (it < n_items && sub < R) {
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
         if (FMT == KDN_FMT_RAW_BF16) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int it = base + u * kThreads + threadIdx.x;
+                const int it = base + u * NT + threadIdx.x;
                 const int r = it >> LOGP;
                 if (it < n_items && sub < R)
                     __builtin_nontemporal_store(
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
             const bool keep = amax >= 0x1p-121f;
             const float q_inv = keep ? 7.0f / amax : 0.0f;
             const float q_scale = keep ? amax / 7.0f : 0.0f;
-            const int it_s = base + us * kThreads + threadIdx.x;
+            const int it_s = base + us * NT + threadIdx.x;
             if (it_s < n_items && sub < R)
                 scales[(it_s >> LOGP) * spr + (sub >> 2)] = q_scale;
             float inv4[U];
@@ -284,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
             inv4[U - 1] = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(q_inv), 0xFF, 0xf, 0xf, true));
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int it = base + u * kThreads + threadIdx.x;
+                const int it = base + u * NT + threadIdx.x;
                 const int r = it >> LOGP;
                 if (it < n_items && sub < R) {
                     const float magic = 12582912.0f; // see quantise4: rint by adding 1.5 * 2^23
@@ -318,7 +319,7 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 inv[u] = __int_as_float(__builtin_amdgcn_ds_bpermute(grp_addr + 4 * u, __float_as_int(quot)));
-            const int it_s = base + us * kThreads + threadIdx.x; // same row as every lane of the group
+            const int it_s = base + us * NT + threadIdx.x; // same row as every lane of the group
             if (is_scale && sub < 8 && it_s < n_items)
                 scales[it_s >> LOGP] = quot;
         } else {
@@ -327,14 +328,14 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
                 const float amax = __uint_as_float(m[u] << 16);
                 const bool keep = amax >= TINY;
                 inv[u] = keep ? QMAX / amax : 0.0f;
-                const int it = base + u * kThreads + threadIdx.x;
+                const int it = base + u * NT + threadIdx.x;
                 if (sub == 0 && it < n_items)
                     scales[it >> LOGP] = keep ? amax / QMAX : 0.0f;
             }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int it = base + u * kThreads + threadIdx.x;
+            const int it = base + u * NT + threadIdx.x;
             const int r = it >> LOGP;
             if (it < n_items && sub < R) {
                 u32x2 q;
@@ -393,6 +394,7 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
     const int P = 1 << LOGP;
     const int H = p.c.H, G = p.c.G, bs = p.c.bs;
     const int L2 = 2 * p.c.L;
+    const int NT = blockDim.x; // a small tile is launched with fewer wavefronts
 
     const Seg &sg = segs.at(blockIdx.y);
     const int S = sg.S, T = sg.T;
@@ -437,7 +439,7 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
     f32x2 cs[8];
     if (rotate) {
         const f32x2 *row = p.rope + (int64_t)sg.rope_row * rhalf;
-        for (int i = threadIdx.x; i < rhalf; i += kThreads)
+        for (int i = threadIdx.x; i < rhalf; i += NT)
             s_cs[i] = row[i];
         __syncthreads();
         if (sub < R && rot_lane) {
@@ -460,12 +462,12 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
         return;
     const bool rotate_lane = rotate && rot_lane;
 
-    for (int it0 = threadIdx.x; it0 < n_items; it0 += kThreads * U) {
+    for (int it0 = threadIdx.x; it0 < n_items; it0 += NT * U) {
         uint32_t lo[U][W], hi[U][W];
         float sc[U][NS];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int it = it0 + u * kThreads;
+            const int it = it0 + u * NT;
             if (it < n_items) {
                 const int r = it >> LOGP;
                 const uint8_t *src = data + (((uint32_t)(r * D + lo_off) * W) >> 1);
@@ -497,7 +499,7 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int it = it0 + u * kThreads;
+            const int it = it0 + u * NT;
             if (it >= n_items)
                 continue;
             const int r = it >> LOGP;
@@ -622,6 +624,7 @@ __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
     const int RW = 64 / R8;  // rows per wavefront and pass
     const int H = p.c.H, G = p.c.G, bs = p.c.bs;
     const int L2 = 2 * p.c.L;
+    const int NT = blockDim.x; // a small tile is launched with fewer wavefronts
 
     const Seg &sg = segs.at(blockIdx.y);
     const int S = sg.S, T = sg.T;
@@ -661,7 +664,7 @@ __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
     if (rotate) {
         const int rhalf = p.rot >> 1;
         const f32x2 *row = p.rope + (int64_t)sg.rope_row * rhalf;
-        for (int i = threadIdx.x; i < rhalf; i += kThreads)
+        for (int i = threadIdx.x; i < rhalf; i += NT)
             s_cs[i] = row[i];
         __syncthreads();
         if (rot_lane) {
@@ -681,7 +684,7 @@ __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
         }
     }
 
-    const int rows_pass = (kThreads / 64) * RW;
+    const int rows_pass = (NT / 64) * RW;
     for (int b = 0; b < n_rows; b += rows_pass * U) { // same trip count for every lane
         uint32_t w[U][W];
         float sc[U];

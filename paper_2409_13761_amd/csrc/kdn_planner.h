@@ -17,8 +17,6 @@ namespace kdn_impl {
 
 constexpr int kFormats = 4; // kdn_format values
 constexpr int kPerTokenMaxBlock = 3; // block sizes served by per-token block lookup
-constexpr int64_t kTileElements = 16384;     // elements a workgroup owns at the common shapes (16 tokens x 8 heads x 128)
-constexpr int64_t kSmallTileElements = 2048; // a tile this small is widened (measured: at 4096 it no longer pays)
 
 // Resolved RoPE variant of one call: frequencies either derived from `base` or given.
 struct RopeSpec {
@@ -143,19 +141,6 @@ inline CacheP make_cache_p(const kdn_cache_desc *c)
         p.G = 16;
         p.per_token = 1;
         p.dense = 0;
-    }
-    // one or two short heads: widen the group until a workgroup owns kTileElements again
-    const int64_t per_token_elems = (int64_t)c->num_kv_heads * c->head_dim;
-    if ((int64_t)p.G * per_token_elems <= kSmallTileElements) {
-        const int32_t want = (int32_t)((kTileElements + per_token_elems - 1) / per_token_elems);
-        const int32_t wide = std::min((want + 15) / 16 * 16, 256);
-        if (wide > p.G) {
-            p.G = wide;
-            if (c->block_size % wide != 0) { // the group spans blocks
-                p.per_token = 1;
-                p.dense = 0;
-            }
-        }
     }
     return p;
 }
@@ -335,13 +320,24 @@ inline kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t
     return KDN_OK;
 }
 
+// Threads of a workgroup: whole wavefronts, enough for every thread to hold `per_thread`
+// items of a full tile in flight, at most kThreads.  Small tiles (few or short heads) thus
+// run as more, narrower workgroups instead of leaving lanes without work.
+inline unsigned block_threads(int64_t items, int per_thread)
+{
+    int64_t t = (items + per_thread - 1) / per_thread;
+    t = (t + 63) / 64 * 64;
+    return (unsigned)std::min<int64_t>(std::max<int64_t>(t, 64), kThreads);
+}
+
 template <int DT, int FMT, int P>
 void launch_store(const StoreP &p, dim3 grid, hipStream_t st)
 {
+    const dim3 block(block_threads((int64_t)p.c.G * p.c.H * P, 2)); // 2 rather than kStoreU items each: measured
     if (p.c.dense && !p.tokens)
-        hipLaunchKernelGGL((k_store<DT, FMT, P, true>), grid, dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL((k_store<DT, FMT, P, true>), grid, block, 0, st, p);
     else
-        hipLaunchKernelGGL((k_store<DT, FMT, P, false>), grid, dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL((k_store<DT, FMT, P, false>), grid, block, 0, st, p);
 }
 
 template <int FMT>
@@ -366,14 +362,16 @@ template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE>
 void launch_place_v(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
                     hipStream_t st)
 {
+    const int lanes_per_row = 1 << log2_ceil(p.c.D >> 4);
+    const dim3 block(block_threads((int64_t)p.c.G * p.c.H * lanes_per_row, FMT == KDN_FMT_RAW_BF16 ? 2 : 4));
     if (segs_dev) {
         SegsDevice sd{segs_dev};
-        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, REUSE, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, REUSE, SegsDevice>), grid, block, 0, st, p, sd);
     } else {
         SegsInline si;
         std::memset(&si, 0, sizeof si);
         std::memcpy(si.s, segs, (size_t)n * sizeof(Seg));
-        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, REUSE, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+        hipLaunchKernelGGL((k_place<DT, FMT, DENSE, VAR, REUSE, SegsInline>), grid, block, 0, st, p, si);
     }
 }
 
@@ -405,24 +403,27 @@ void launch_place_c(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs
                     hipStream_t st)
 {
     const int flavour = !p.c.dense ? 0 : p.reuse ? 2 : 1;
+    // a wavefront takes 64/(D/8) rows per pass and keeps 8 (raw: 4) passes in flight
+    const int64_t passes = ((int64_t)p.c.G * p.c.H + 64 / (p.c.D >> 3) - 1) / (64 / (p.c.D >> 3));
+    const dim3 block(block_threads(passes * 64, FMT == KDN_FMT_RAW_BF16 ? 4 : 8));
     if (segs_dev) {
         SegsDevice sd{segs_dev};
         if (flavour == 0)
-            hipLaunchKernelGGL((k_place_c<DT, FMT, false, false, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+            hipLaunchKernelGGL((k_place_c<DT, FMT, false, false, SegsDevice>), grid, block, 0, st, p, sd);
         else if (flavour == 1)
-            hipLaunchKernelGGL((k_place_c<DT, FMT, true, false, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+            hipLaunchKernelGGL((k_place_c<DT, FMT, true, false, SegsDevice>), grid, block, 0, st, p, sd);
         else
-            hipLaunchKernelGGL((k_place_c<DT, FMT, true, true, SegsDevice>), grid, dim3(kThreads), 0, st, p, sd);
+            hipLaunchKernelGGL((k_place_c<DT, FMT, true, true, SegsDevice>), grid, block, 0, st, p, sd);
     } else {
         SegsInline si;
         std::memset(&si, 0, sizeof si);
         std::memcpy(si.s, segs, (size_t)n * sizeof(Seg));
         if (flavour == 0)
-            hipLaunchKernelGGL((k_place_c<DT, FMT, false, false, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+            hipLaunchKernelGGL((k_place_c<DT, FMT, false, false, SegsInline>), grid, block, 0, st, p, si);
         else if (flavour == 1)
-            hipLaunchKernelGGL((k_place_c<DT, FMT, true, false, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+            hipLaunchKernelGGL((k_place_c<DT, FMT, true, false, SegsInline>), grid, block, 0, st, p, si);
         else
-            hipLaunchKernelGGL((k_place_c<DT, FMT, true, true, SegsInline>), grid, dim3(kThreads), 0, st, p, si);
+            hipLaunchKernelGGL((k_place_c<DT, FMT, true, true, SegsInline>), grid, block, 0, st, p, si);
     }
 }
 

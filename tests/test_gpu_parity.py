@@ -36,8 +36,8 @@ def _say(msg):
     (1, 6, 16, 1, 512, 0, 40),         # largest head_dim
     (2, 30, 3, 2, 64, 4, 70),          # blocks of 3 tokens: rows look their own block up
     (2, 64, 2, 3, 128, 1, 90),         # blocks of 2 tokens
-    (3, 40, 16, 1, 128, 5, 300),       # one head: the token group is widened over several blocks
-    (2, 12, 128, 1, 128, 9, 700),      # one head, large blocks: a widened group inside one block
+    (3, 40, 16, 1, 128, 5, 300),       # one head: small tiles, workgroups of one wavefront
+    (2, 12, 128, 1, 128, 9, 700),      # one head, large blocks
     (2, 40, 16, 2, 64, 3, 333),        # two short heads
 ])
 def test_store_matches_oracle(fmt, shape):

@@ -35,8 +35,9 @@
  *     kdn_patch_rows, and kdn_compose / kdn_compose_rope with at most 64 chunks whose
  *     cos/sin rows are resident (kdn_rope_prepare) enqueue kernels only and may be
  *     captured.  Composes with more chunks (their segment table is copied from pinned
- *     memory and guarded by events), kdn_compose_from_host and
- *     kdn_validate_block_table must not be captured.
+ *     memory and guarded by events), the staged host paths (kdn_store_to_host,
+ *     kdn_compose_from_host, kdn_compose_from_host_staged: copies and events on
+ *     library streams) and kdn_validate_block_table must not be captured.
  *   - Calls may come from several host threads and target several streams; the
  *     library serialises its own bookkeeping.  Two calls that write the same
  *     destination blocks race like any two kernels would.

@@ -10,7 +10,9 @@
 // Work decomposition (both directions): a workgroup owns one (layer, K|V, token group)
 // tile.  A token group is a run of at most G consecutive request tokens that lies inside
 // one paged block, so a tile is contiguous in the paged cache (for the dense layout) and
-// contiguous in the stored chunk.
+// contiguous in the stored chunk.  Blocks of one to three tokens are the exception: there
+// a group is 16 tokens and every row looks its own block up.  The host sizes the workgroup
+// to the tile (whole wavefronts, at most kThreads), so the kernels stride by blockDim.x.
 #ifndef KDN_KERNELS_H
 #define KDN_KERNELS_H
 
@@ -363,6 +365,8 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 // read twice.
 // Grid: x = group * 2L + (layer, side), so that neighbouring workgroups write to
 // different (layer, side) planes; y = segment.
+// Serves head dims that are multiples of 128, where each of the two stores of a lane group
+// fills whole 128-byte lines; k_place_c below serves the others.
 // Stored rows are streamed past the caches unless several segments read the same rows
 // (a popular chunk in a batched compose): then they are loaded normally, so that the
 // first reader leaves them in L2 and the last-level cache for the others.

@@ -322,11 +322,14 @@ def test_many_chunks_go_through_the_device_segment_table():
     assert_cache_equal(dd, hd)
 
 
-def test_batched_compose_matches_independent_oracle_composes():
-    L, nb, bs, H, D = 2, 200, 16, 2, 128
+@pytest.mark.parametrize("D,fmt", [(128, INT8), (64, INT8), (96, FP8), (64, INT4), (256, RAW)])
+def test_batched_compose_matches_independent_oracle_composes(D, fmt):
+    """Requests that share chunks (the cached-load flavour of both place kernels)."""
+    L, nb, bs, H = 2, 200, 16, 2
+    _say("compose_batch D=%d fmt=%d" % (D, fmt))
     src = host_cache(51, L, nb, bs, H, D)
     tabs = synth.disjoint_block_tables(51, nb, [8] * 6 + [18] * 8)
-    pool = [O.store(src, tabs[i], 0, 128 - 3 * i, INT8) for i in range(6)]
+    pool = [O.store(src, tabs[i], 0, 128 - 3 * i, fmt) for i in range(6)]
     dpool = [chunk_to_dev(c) for c in pool]
     draws = synth.zipf_distinct_draws(51, 8, 2, 6)
     hd = host_cache(52, L, nb, bs, H, D)

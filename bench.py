@@ -784,6 +784,8 @@ def main() -> int:
         print("bench.py: this library runs on one GPU only; the path shards without any exchange "
               "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
         return 2
+    from paper_2409_13761_amd import build as lib_build
+    lib_build.ensure_built()
     defaults = {"8b": (40, 8), "toy": (200, 20), "70b_long": (10, 3), "batched_reuse": (10, 3),
                 "host_stream_int8": (10, 3), "host_stream_raw": (10, 3), "pool_trace": (400, 100), "pool_trace_tiered": (400, 100), "sweep": (8, 0)}[args.workload]
     args.steps = defaults[0] if args.steps is None else args.steps

@@ -42,5 +42,11 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def ensure_built() -> str:
+    """Build only when no library is there at all (a fresh checkout); one that is there is
+    used as it is."""
+    return LIB_PATH if os.path.exists(LIB_PATH) else build_library(force=True)
+
+
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True))

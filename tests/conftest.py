@@ -24,5 +24,4 @@ def _library_present():
     """A fresh checkout holds no built library: build it once (hipcc cross-compiles without a
     GPU).  A library that is there is used as it is."""
     from paper_2409_13761_amd import build
-    if not os.path.exists(build.LIB_PATH):
-        build.build_library()
+    build.ensure_built()

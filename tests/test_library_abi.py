@@ -121,3 +121,29 @@ def test_status_strings(lib):
     for s in (0, -1, -2, -3, -4, -5, -6, -7):
         assert kdn.status_str(s)
     assert "kdn" in kdn.kdn_version()
+
+
+def test_headers_are_plain_c_and_the_library_links_from_c(lib, tmp_path):
+    """The boundary is a C ABI: a C99 program that includes both headers compiles without a
+    warning, links against the library and calls it (host-only entry points)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("needs gcc")
+    src = tmp_path / "abi.c"
+    src.write_text('#include "kdn.h"\n#include "kdn_pool.h"\n#include <stdio.h>\n'
+                   'int main(void) {\n'
+                   '    kdn_chunk c; char buf[16] __attribute__((aligned(16)));\n'
+                   '    unsigned long long n = kdn_chunk_bytes(32, 8, 128, 1, KDN_FMT_INT8_ROWSCALE);\n'
+                   '    int st = kdn_chunk_init(&c, buf, sizeof buf, KDN_FMT_RAW_BF16, 1, 1, 16, 1);\n'
+                   '    printf("%llu %d %s\\n", n, st, kdn_status_str(KDN_ESIZE));\n'
+                   '    return 0;\n}\n')
+    exe = str(tmp_path / "abi")
+    libdir = os.path.dirname(build.LIB_PATH)
+    p = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        str(src), "-o", exe, "-L", libdir, "-lkdn", "-Wl,-rpath," + libdir],
+                       capture_output=True, text=True)
+    assert p.returncode == 0, p.stderr
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=60)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.split()[:2] == ["67584", str(kdn.ESIZE)]

@@ -153,7 +153,11 @@ def workload_8b(args, dev):
     fill_normal(k, g)
     fill_normal(v, g)
     cache = kdn.PagedCache(k, v)
-    tables = synth.disjoint_block_tables(w.seed, nb, [blocks] * (3 * n_sets))
+    if args.tables == "random":
+        tables = synth.disjoint_block_tables(w.seed, nb, [blocks] * (3 * n_sets))
+    else:   # every table a run of consecutive blocks: what the kernels do when the engine places a request so
+        import numpy as np
+        tables = [np.arange(i * blocks, (i + 1) * blocks, dtype=np.int32) for i in range(3 * n_sets)]
     order = synth.permutation(w.seed, n_slices)
     offsets = [int(j * (T // n_slices)) for j in range(n_slices)]   # j-th placed slice moves by 512*j
     sets = []
@@ -184,9 +188,11 @@ def workload_8b(args, dev):
         "place_calls": ("load", "compose"),
         "workload": "Llama-3-8B-shaped KV (L32 H8 D128 bs16): per step store 4096 tokens to %s, "
                     "load them at offset 0, compose them as 8x512-token slices in seeded order with "
-                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled; cache layout %s"
-                    % (args.fmt, w.rope_base, n_sets, args.layout),
-        "traffic": counter_traffic() if args.fmt == "int8" else None,
+                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled; cache layout %s; %s block tables"
+                    % (args.fmt, w.rope_base, n_sets, args.layout,
+                       "random disjoint" if args.tables == "random" else "consecutive-block"),
+        "traffic": counter_traffic() if args.fmt == "int8" and args.tables == "random" and args.layout == "planes"
+        else None,
     }
     if not args.no_cpu_baseline and args.fmt == "int8":
         res["cpu_baseline"] = cpu_baseline(kdn, cache, sets[0], order, offsets, w.rope_base, T, n_slices,
@@ -774,6 +780,9 @@ def main() -> int:
                     help="paged cache layout of the 8b workload, all expressed through the "
                          "descriptor's strides: separate K and V tensors [L][blocks][bs][H][D] "
                          "(default), K and V of a block adjoining, or all layers of a block adjoining")
+    ap.add_argument("--tables", choices=("random", "consecutive"), default="random",
+                    help="block tables of the 8b workload: sampled without replacement from the pool "
+                         "(default, the stated workload) or runs of consecutive blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=8)
     ap.add_argument("--calibration-copy", action="store_true",
@@ -835,7 +844,8 @@ def main() -> int:
             or args.workload == "host_stream_int8" else
             "int4 codes + fp32 group scales" if args.fmt == "int4" else
             "fp8 e4m3 codes + fp32 row scales" if args.fmt == "fp8" else "raw bf16"),
-        "data": "synthetic N(0,1) bf16 KV, seeded; random disjoint block tables",
+        "data": "synthetic N(0,1) bf16 KV, seeded; %s block tables"
+                % ("consecutive-block" if args.workload == "8b" and args.tables == "consecutive" else "random disjoint"),
         "config": {
             "workload": res["workload"],
             "tokens_per_step": res["tokens_per_step"],

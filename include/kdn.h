@@ -204,6 +204,30 @@ kdn_status kdn_store_tokens(const kdn_cache_desc *cache, const int32_t *block_ta
                             int32_t table_len, const int32_t *tokens_dev, int32_t num_tokens,
                             kdn_chunk *out, void *stream);
 
+/* Launch options.  max_workgroups > 0 caps the workgroups of the call's kernels, which
+ * then stride over the tiles; 0 (or a NULL options pointer) launches one workgroup per
+ * tile.  The cap is for chunks in pinned host memory: a few dozen workgroups keep the
+ * link busy (the link, not the device, bounds such a call), and the rest of the device
+ * stays free for the kernels of other streams, where an uncapped launch would sit on
+ * every wave slot while it waits for the link.  Results do not depend on the cap. */
+typedef struct kdn_launch_opts {
+    int32_t max_workgroups;
+} kdn_launch_opts;
+
+/* kdn_store_chunk with launch options. */
+kdn_status kdn_store_chunk_opts(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                                int32_t table_len, int32_t token_start, int32_t num_tokens,
+                                kdn_chunk *out, const kdn_launch_opts *opts, void *stream);
+
+/* kdn_compose / kdn_compose_rope with launch options.  rope: NULL selects the default
+ * variant at rope_base; otherwise rope_base is ignored.  Kernels only when the cos/sin
+ * rows are resident and there are at most 64 chunks, hence capturable into a HIP graph,
+ * chunks in host memory included. */
+kdn_status kdn_compose_opts(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                            const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                            int32_t table_len, int32_t dest_token_start, double rope_base,
+                            const kdn_rope_spec *rope, const kdn_launch_opts *opts, void *stream);
+
 /* Store into pinned HOST memory: the way out of the engine toward the storage device
  * (Sec. 3.1, storage module; CPU memory as the KV store, Sec. 3 "Limited storage").
  * out_host->data: [host], allocated with hipHostMalloc (or a pinned torch tensor), at

@@ -99,7 +99,7 @@ static kdn_status store_check(const kdn_cache_desc *cache, const int32_t *block_
 static kdn_status store_launch(const kdn_cache_desc *cache, const int32_t *block_table_dev,
                                int32_t table_len, int32_t token_start, int32_t num_tokens,
                                const int32_t *tokens_dev, int32_t fmt, void *dst, int32_t layer0,
-                               int32_t n_layers, hipStream_t hs)
+                               int32_t n_layers, hipStream_t hs, int32_t max_workgroups = 0)
 {
     StoreP p;
     p.c = make_cache_p(cache);
@@ -116,7 +116,8 @@ static kdn_status store_launch(const kdn_cache_desc *cache, const int32_t *block
     const int64_t groups = groups_spanned(token_start, num_tokens, p.c.G);
     if (groups * 2 * p.c.L > 0x7fffffff / kThreads)
         return KDN_ESIZE;
-    dim3 grid((unsigned)(groups * 2 * p.c.L), 1, 1);
+    p.tiles_x = (uint32_t)(groups * 2 * p.c.L);
+    dim3 grid(max_workgroups > 0 ? std::min<uint32_t>(p.tiles_x, (uint32_t)max_workgroups) : p.tiles_x, 1, 1);
     if (fmt == KDN_FMT_RAW_BF16)
         launch_store_d<KDN_FMT_RAW_BF16>(p, grid, hs);
     else if (fmt == KDN_FMT_INT8_ROWSCALE)
@@ -140,13 +141,13 @@ static void describe_stored(const kdn_cache_desc *cache, int32_t num_tokens, kdn
 
 static kdn_status store_impl(const kdn_cache_desc *cache, const int32_t *block_table_dev,
                              int32_t table_len, int32_t token_start, int32_t num_tokens,
-                             const int32_t *tokens_dev, kdn_chunk *out, void *stream)
+                             const int32_t *tokens_dev, kdn_chunk *out, void *stream, int32_t max_workgroups = 0)
 {
     kdn_status st = store_check(cache, block_table_dev, table_len, token_start, num_tokens, tokens_dev, out);
     if (st != KDN_OK)
         return st;
     st = store_launch(cache, block_table_dev, table_len, token_start, num_tokens, tokens_dev, out->fmt,
-                      out->data, 0, cache->num_layers, static_cast<hipStream_t>(stream));
+                      out->data, 0, cache->num_layers, static_cast<hipStream_t>(stream), max_workgroups);
     if (st != KDN_OK)
         return st;
     describe_stored(cache, num_tokens, out);
@@ -167,6 +168,16 @@ kdn_status kdn_store_tokens(const kdn_cache_desc *cache, const int32_t *block_ta
     if (!tokens_dev)
         return KDN_EINVAL;
     return store_impl(cache, block_table_dev, table_len, 0, num_tokens, tokens_dev, out, stream);
+}
+
+kdn_status kdn_store_chunk_opts(const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                                int32_t table_len, int32_t token_start, int32_t num_tokens,
+                                kdn_chunk *out, const kdn_launch_opts *opts, void *stream)
+{
+    if (opts && opts->max_workgroups < 0)
+        return KDN_EINVAL;
+    return store_impl(cache, block_table_dev, table_len, token_start, num_tokens, nullptr, out, stream,
+                      opts ? opts->max_workgroups : 0);
 }
 
 uint64_t kdn_store_staging_bytes(const kdn_cache_desc *cache, int32_t num_tokens, int32_t fmt,
@@ -285,6 +296,17 @@ kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
                              const kdn_cache_desc *cache, double rope_base, void *stream)
 {
     return compose_impl(requests, n_requests, cache, rope_base, nullptr, stream);
+}
+
+kdn_status kdn_compose_opts(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
+                            const kdn_cache_desc *cache, const int32_t *block_table_dev,
+                            int32_t table_len, int32_t dest_token_start, double rope_base,
+                            const kdn_rope_spec *rope, const kdn_launch_opts *opts, void *stream)
+{
+    if (opts && opts->max_workgroups < 0)
+        return KDN_EINVAL;
+    kdn_request q = {chunks, offsets, n_chunks, block_table_dev, table_len, dest_token_start};
+    return compose_impl(&q, 1, cache, rope_base, rope, stream, opts ? opts->max_workgroups : 0);
 }
 
 kdn_status kdn_compose_plan(const kdn_request *requests, int32_t n_requests, const kdn_cache_desc *cache,

@@ -74,6 +74,7 @@ struct StoreP {
     const int32_t *tokens; // token-list store: row t holds request token tokens[t]; else NULL
     int32_t limit;         // request tokens the block table covers (list entries are clamped to it)
     int32_t layer0;        // cache layer that stored layer 0 comes from (c.L layers are stored)
+    uint32_t tiles_x;      // tiles along x; a launch with fewer workgroups strides over them
 };
 
 struct PlaceP {
@@ -83,6 +84,7 @@ struct PlaceP {
     int32_t rot;       // rotary leading dimensions (head_dim unless partial rotary)
     int32_t pairing;   // kdn_rope_pairing
     int32_t reuse;     // some stored rows are read by more than one segment: let them stay cached
+    uint32_t tiles_x;  // tiles along x; a launch with fewer workgroups strides over them
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
@@ -185,7 +187,7 @@ __device__ __forceinline__ uint32_t quantise4_fp8(uint32_t w0, uint32_t w1, floa
 }
 
 template <int DT, int FMT, int P, bool DENSE>
-__global__ __launch_bounds__(kThreads) void k_store(StoreP p)
+__device__ __forceinline__ void store_tile(const StoreP &p, const uint32_t bx)
 {
     constexpr int U = kStoreU;
     constexpr int LOGP = log2_ceil(P);
@@ -201,9 +203,9 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     const int L2 = 2 * p.c.L;
 
     // group-fastest order: neighbouring workgroups write neighbouring rows of the chunk
-    const int n_groups = gridDim.x / L2;
-    const int ls = blockIdx.x / n_groups;
-    const int piece = blockIdx.x - ls * n_groups;
+    const int n_groups = p.tiles_x / L2;
+    const int ls = bx / n_groups;
+    const int piece = bx - ls * n_groups;
     const int gi = p.t0 / G + piece;
     const int tok_lo = max(p.t0, gi * G);
     const int tok_hi = min(p.t0 + p.T, (gi + 1) * G);
@@ -355,6 +357,16 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
     }
 }
 
+// One workgroup per tile; a launch capped below the tile count (chunks in host memory: a few
+// workgroups keep the link busy and leave the rest of the device to other work) strides.
+template <int DT, int FMT, int P, bool DENSE>
+__global__ __launch_bounds__(kThreads) void k_store(StoreP p)
+{
+    store_tile<DT, FMT, P, DENSE>(p, blockIdx.x); // the common launch ends here
+    for (uint32_t bx = blockIdx.x + gridDim.x; bx < p.tiles_x; bx += gridDim.x)
+        store_tile<DT, FMT, P, DENSE>(p, bx);
+}
+
 // ---------------------------------------------------------------------------------
 // place: dequantise (or copy), rotate K pairs, round to bf16, scatter.
 // Lane group: D/16 lanes own one row; a lane takes 8 elements of the lower half and
@@ -386,7 +398,7 @@ __device__ __forceinline__ T load_stored(const uint8_t *ptr)
 // pairs of its own); the part behind the rotary one is split into halves the same way and
 // never rotates.
 template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE, typename Segs>
-__global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
+__device__ __forceinline__ void place_tile(const PlaceP &p, const Segs &segs, const uint32_t bx)
 {
     constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 2 : 4;
     constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT4_GROUP32 ? 1 : 2; // 32-bit words per 8 stored elements
@@ -402,8 +414,8 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 
     const Seg &sg = segs.at(blockIdx.y);
     const int S = sg.S, T = sg.T;
-    const int piece = blockIdx.x / L2;
-    const int ls = blockIdx.x - piece * L2;
+    const int piece = bx / L2;
+    const int ls = bx - piece * L2;
     const int gi = S / G + piece;
     const int tok_lo = max(S, gi * G);
     const int tok_hi = min(S + T, (gi + 1) * G);
@@ -591,6 +603,19 @@ __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
     }
 }
 
+// One workgroup per tile, or fewer workgroups striding over the tiles (see k_store).  The
+// barrier between tiles keeps a fast wavefront from restaging the cos/sin row while a slow
+// one still reads the previous tile's.
+template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE, typename Segs>
+__global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
+{
+    place_tile<DT, FMT, DENSE, VAR, REUSE, Segs>(p, segs, blockIdx.x); // the common launch ends here
+    for (uint32_t bx = blockIdx.x + gridDim.x; bx < p.tiles_x; bx += gridDim.x) {
+        __syncthreads();
+        place_tile<DT, FMT, DENSE, VAR, REUSE, Segs>(p, segs, bx);
+    }
+}
+
 // the 8 values that the stored words of 8 consecutive elements stand for
 template <int FMT>
 __device__ __forceinline__ void dequantise8(const uint32_t *w, float scale, float *x)
@@ -619,7 +644,7 @@ __device__ __forceinline__ void dequantise8(const uint32_t *w, float scale, floa
 // the exchange; loads and stores are predicated instead.
 // Grid as k_place.
 template <int DT, int FMT, bool DENSE, bool REUSE, typename Segs>
-__global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
+__device__ __forceinline__ void place_tile_c(const PlaceP &p, const Segs &segs, const uint32_t bx)
 {
     constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 4 : 8;
     constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT4_GROUP32 ? 1 : 2; // words per 8 stored elements
@@ -632,8 +657,8 @@ __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
 
     const Seg &sg = segs.at(blockIdx.y);
     const int S = sg.S, T = sg.T;
-    const int piece = blockIdx.x / L2;
-    const int ls = blockIdx.x - piece * L2;
+    const int piece = bx / L2;
+    const int ls = bx - piece * L2;
     const int gi = S / G + piece;
     const int tok_lo = max(S, gi * G);
     const int tok_hi = min(S + T, (gi + 1) * G);
@@ -781,6 +806,16 @@ __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
             }
             __builtin_nontemporal_store(out, reinterpret_cast<u32x4 *>(dst + sub * 8));
         }
+    }
+}
+
+template <int DT, int FMT, bool DENSE, bool REUSE, typename Segs>
+__global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
+{
+    place_tile_c<DT, FMT, DENSE, REUSE, Segs>(p, segs, blockIdx.x);
+    for (uint32_t bx = blockIdx.x + gridDim.x; bx < p.tiles_x; bx += gridDim.x) {
+        __syncthreads();
+        place_tile_c<DT, FMT, DENSE, REUSE, Segs>(p, segs, bx);
     }
 }
 

@@ -444,8 +444,9 @@ void launch_place_d(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs
 
 // Enqueue the placement of `segs` (all of one format).  Up to kMaxInlineSegs travel
 // in the kernel arguments; more go through a ring of device tables.
-inline kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, const std::vector<Seg> &segs,
-                                 hipStream_t st)
+// max_workgroups > 0 caps the launch; the workgroups then stride over the tiles.
+inline kdn_status place_segments(DeviceState *ds, const PlaceP &p_in, int32_t fmt, const std::vector<Seg> &segs,
+                                 hipStream_t st, int32_t max_workgroups = 0)
 {
     if (segs.empty())
         return KDN_OK;
@@ -453,10 +454,15 @@ inline kdn_status place_segments(DeviceState *ds, const PlaceP &p, int32_t fmt, 
         return KDN_ESIZE;
     int64_t max_groups = 0;
     for (const Seg &s : segs)
-        max_groups = std::max(max_groups, groups_spanned(s.S, s.T, p.c.G));
-    if (max_groups * 2 * p.c.L > 0x7fffffff / kThreads)
+        max_groups = std::max(max_groups, groups_spanned(s.S, s.T, p_in.c.G));
+    if (max_groups * 2 * p_in.c.L > 0x7fffffff / kThreads)
         return KDN_ESIZE;
-    dim3 grid((unsigned)(max_groups * 2 * p.c.L), (unsigned)segs.size(), 1);
+    PlaceP p = p_in;
+    p.tiles_x = (uint32_t)(max_groups * 2 * p.c.L);
+    uint32_t gx = p.tiles_x;
+    if (max_workgroups > 0)
+        gx = std::min<uint32_t>(gx, std::max<uint32_t>(1u, (uint32_t)max_workgroups / (uint32_t)segs.size()));
+    dim3 grid(gx, (unsigned)segs.size(), 1);
 
     const Seg *segs_dev = nullptr;
     int slot = -1;
@@ -582,7 +588,8 @@ inline kdn_status plan_compose(const kdn_request *reqs, int32_t n_reqs, const kd
 }
 
 inline kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
-                               double rope_base, const kdn_rope_spec *variant, void *stream)
+                               double rope_base, const kdn_rope_spec *variant, void *stream,
+                               int32_t max_workgroups = 0)
 {
     ComposePlan plan;
     kdn_status st = plan_compose(reqs, n_reqs, cache, plan);
@@ -618,7 +625,7 @@ inline kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kd
             segs.back().rope_row = rows[k++];
         }
         p.reuse = plan.reuse[f];
-        st = place_segments(ds, p, f, segs, static_cast<hipStream_t>(stream));
+        st = place_segments(ds, p, f, segs, static_cast<hipStream_t>(stream), max_workgroups);
         if (st != KDN_OK)
             return st;
     }

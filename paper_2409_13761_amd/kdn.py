@@ -53,6 +53,10 @@ ROPE_HALF_SPLIT = 0
 ROPE_INTERLEAVED = 1
 
 
+class LaunchOpts(C.Structure):
+    _fields_ = [("max_workgroups", C.c_int32)]
+
+
 class PoolStats(C.Structure):
     _fields_ = [("hits", C.c_uint64), ("misses", C.c_uint64), ("inserts", C.c_uint64),
                 ("evictions", C.c_uint64), ("bytes", C.c_uint64), ("entries", C.c_uint64)]
@@ -84,6 +88,13 @@ def lib() -> C.CDLL:
         L.kdn_chunk_slice.argtypes = [C.POINTER(ChunkDesc), i32, i32, C.POINTER(ChunkDesc)]
         L.kdn_store_chunk.restype = C.c_int
         L.kdn_store_chunk.argtypes = [C.POINTER(CacheDesc), vp, i32, i32, i32, C.POINTER(ChunkDesc), vp]
+        L.kdn_store_chunk_opts.restype = C.c_int
+        L.kdn_store_chunk_opts.argtypes = [C.POINTER(CacheDesc), vp, i32, i32, i32, C.POINTER(ChunkDesc),
+                                           C.POINTER(LaunchOpts), vp]
+        L.kdn_compose_opts.restype = C.c_int
+        L.kdn_compose_opts.argtypes = [C.POINTER(ChunkDesc), C.POINTER(i32), i32, C.POINTER(CacheDesc),
+                                       vp, i32, i32, C.c_double, C.POINTER(RopeSpecDesc),
+                                       C.POINTER(LaunchOpts), vp]
         L.kdn_store_tokens.restype = C.c_int
         L.kdn_store_tokens.argtypes = [C.POINTER(CacheDesc), vp, i32, vp, i32, C.POINTER(ChunkDesc), vp]
         L.kdn_store_to_host.restype = C.c_int
@@ -155,7 +166,7 @@ def lib() -> C.CDLL:
 
 
 EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk", "kdn_store_tokens",
-           "kdn_store_to_host", "kdn_store_staging_bytes",
+           "kdn_store_to_host", "kdn_store_staging_bytes", "kdn_store_chunk_opts", "kdn_compose_opts",
            "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_rope",
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host", "kdn_compose_from_host_staged",
            "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec",
@@ -289,9 +300,16 @@ def chunk_slice(chunk: Chunk, token_start: int, num_tokens: int) -> Chunk:
 
 
 def kdn_store_chunk(cache: PagedCache, block_table: torch.Tensor, token_start: int,
-                    num_tokens: int, out: Chunk, stream=None) -> Chunk:
+                    num_tokens: int, out: Chunk, stream=None, max_workgroups: int = 0) -> Chunk:
+    """max_workgroups > 0 goes through kdn_store_chunk_opts (a capped launch)."""
     assert block_table.dtype == torch.int32 and block_table.is_contiguous()
     cd = cache.desc()
+    if max_workgroups:
+        opts = LaunchOpts(int(max_workgroups))
+        _check(lib().kdn_store_chunk_opts(C.byref(cd), block_table.data_ptr(), block_table.numel(),
+                                          token_start, num_tokens, C.byref(out.desc), C.byref(opts),
+                                          _stream(stream)), "kdn_store_chunk_opts")
+        return out
     _check(lib().kdn_store_chunk(C.byref(cd), block_table.data_ptr(), block_table.numel(),
                                  token_start, num_tokens, C.byref(out.desc), _stream(stream)),
            "kdn_store_chunk")
@@ -355,12 +373,21 @@ def _chunk_array(chunks):
 
 
 def kdn_compose(chunks, offsets, cache: PagedCache, block_table: torch.Tensor, rope_base: float,
-                dest_token_start: int = 0, stream=None) -> None:
+                dest_token_start: int = 0, stream=None, max_workgroups: int = 0, spec=None) -> None:
+    """max_workgroups > 0 (a capped launch) or spec (a pair from rope_spec()) go through
+    kdn_compose_opts."""
     assert block_table.dtype == torch.int32 and block_table.is_contiguous()
     assert len(chunks) == len(offsets)
     cd = cache.desc()
     arr = _chunk_array(chunks)
     off = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
+    if max_workgroups or spec is not None:
+        opts = LaunchOpts(int(max_workgroups))
+        _check(lib().kdn_compose_opts(arr, off, len(chunks), C.byref(cd), block_table.data_ptr(),
+                                      block_table.numel(), dest_token_start, float(rope_base),
+                                      C.byref(spec[0]) if spec is not None else None, C.byref(opts),
+                                      _stream(stream)), "kdn_compose_opts")
+        return
     _check(lib().kdn_compose(arr, off, len(chunks), C.byref(cd), block_table.data_ptr(),
                              block_table.numel(), dest_token_start, float(rope_base),
                              _stream(stream)), "kdn_compose")

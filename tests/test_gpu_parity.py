@@ -762,6 +762,38 @@ def test_kernels_on_chunks_in_pinned_host_memory(fmt):
     assert_cache_equal(dd, hd)
 
 
+@pytest.mark.parametrize("cap", [1, 7, 64, 100000])
+@pytest.mark.parametrize("D,fmt", [(128, INT8), (64, INT4), (96, RAW), (128, FP8)])
+def test_capped_launch_gives_the_same_result(cap, D, fmt):
+    """A launch with fewer workgroups than tiles strides over them: same stored bytes, same
+    composed cache, for both place kernels, device- and host-resident chunks, a RoPE variant."""
+    L, nb, bs, H = 3, 64, 16, 2
+    _say("capped launch cap=%d D=%d fmt=%d" % (cap, D, fmt))
+    src = host_cache(151, L, nb, bs, H, D)
+    a, b, dst_bt = synth.disjoint_block_tables(151, nb, [10, 8, 22])
+    want_a, want_b = O.store(src, a, 3, 150, fmt), O.store(src, b, 0, 100, fmt)
+    dc = dev_cache(src)
+    out_a = kdn.alloc_chunk(dc, 150, fmt)
+    out_b = kdn.alloc_host_chunk(dc, 100, fmt)
+    kdn.kdn_store_chunk(dc, dev_table(a), 3, 150, out_a, max_workgroups=cap)
+    kdn.kdn_store_chunk(dc, dev_table(b), 0, 100, out_b, max_workgroups=cap)
+    assert_chunk_equal(out_a, want_a)
+    assert np.array_equal(out_b.data.numpy(), want_b.data)
+    views_h = [want_a.slice(20, 100), want_b, want_a.slice(0, 33), want_b.slice(50, 50)]
+    views_d = [out_a.slice(20, 100), out_b, out_a.slice(0, 33), out_b.slice(50, 50)]
+    offsets = [0, 100, -7, 2048]
+    for spec in (None, kdn.rope_spec(10000.0, None, 32, kdn.ROPE_INTERLEAVED)):
+        hd = host_cache(152, L, nb, bs, H, D)
+        dd = dev_cache(hd)
+        if spec is None:
+            O.compose(views_h, offsets, hd, dst_bt, 10000.0, dest=5)
+        else:
+            O.compose_spec(views_h, offsets, hd, dst_bt, 10000.0, rot_dim=32, pairing=1, dest=5)
+        kdn.kdn_compose(views_d, offsets, dd, dev_table(dst_bt), 10000.0, dest_token_start=5,
+                        max_workgroups=cap, spec=spec)
+        assert_cache_equal(dd, hd)
+
+
 def lib_store_to_host_with_device_chunk(dc, a, fmt, staging, layers_per_stage):
     import ctypes as C
     dev_chunk = kdn.alloc_chunk(dc, 110, fmt)

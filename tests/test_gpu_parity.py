@@ -566,6 +566,44 @@ def test_patch_rows_matches_oracle(shape):
 
 
 # ------------------------------------------------------------------ HIP graph capture
+def test_capped_store_to_and_compose_from_host_memory_replay_inside_a_hip_graph():
+    """Chunks in pinned host memory, capped launches, kernels only: the store into host
+    memory and the compose back from it are captured once and replayed with fresh data."""
+    L, nb, bs, H, D = 2, 48, 16, 2, 64
+    a, c = synth.disjoint_block_tables(93, nb, [8, 12])
+    offsets = [40, 0]
+    base = 10000.0
+    hc = host_cache(94, L, nb, bs, H, D)
+    dc = dev_cache(hc)
+    ta, tc = dev_table(a), dev_table(c)
+    out = kdn.alloc_host_chunk(dc, 120, FP8)
+    kdn.kdn_rope_prepare(base, D, offsets)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        kdn.kdn_store_chunk(dc, ta, 2, 120, out, max_workgroups=8)       # warm-up outside the capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            kdn.kdn_store_chunk(dc, ta, 2, 120, out, max_workgroups=8)
+            kdn.kdn_compose([out.slice(60, 60), out.slice(0, 60)], offsets, dc, tc, base, dest_token_start=1,
+                            max_workgroups=8)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        fresh = host_cache(110 + rep, L, nb, bs, H, D)
+        dc.k.copy_(to_dev_bf16(fresh.k))
+        dc.v.copy_(to_dev_bf16(fresh.v))
+        out.data.fill_(0x11 * rep)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        h = O.store(fresh, a, 2, 120, FP8)
+        O.compose([h.slice(60, 60), h.slice(0, 60)], offsets, fresh, c, base, dest=1)
+        assert np.array_equal(out.data.numpy(), h.data)
+        assert_cache_equal(dc, fresh)
+        _ = (dc.k.float().sum() + dc.v.float().sum()).item()   # unrelated eager work between replays
+
+
 def test_store_and_compose_replay_inside_a_hip_graph():
     """With the cos/sin rows resident, store / load / compose enqueue kernels only, so a
     captured sequence can be replayed: every replay is checked against the oracle with

@@ -38,6 +38,11 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     proc = subprocess.run(cmd, capture_output=True, text=True)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + proc.stdout + proc.stderr)
+    # hipcc's host pass does not know the packed-fp32 target feature and says so; anything else is shown
+    noise = ("packed-fp32-ops", "warning generated", "warnings generated")
+    for line in (proc.stdout + proc.stderr).splitlines():
+        if line.strip() and not any(n in line for n in noise):
+            print(line, flush=True)
     os.replace(tmp, LIB_PATH)
     return LIB_PATH
 

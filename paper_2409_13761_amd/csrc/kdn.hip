@@ -515,7 +515,7 @@ static kdn_status compose_from_host_impl(const kdn_chunk *chunks, const int32_t 
     if (st != KDN_OK)
         return st;
 
-    const int32_t L = cache->num_layers, H = cache->num_kv_heads, D = cache->head_dim;
+    const int32_t L = cache->num_layers;
     uint8_t *staging = static_cast<uint8_t *>(staging_dev);
     const uint64_t half_bytes = need / 2;
     std::vector<StageCopy> copies;

@@ -355,7 +355,7 @@ def workload_batched(args, dev):
 def workload_host_stream(args, dev, fmt_name):
     """A 4096-token context is stored into pinned host memory and composed back from there as
     8 shifted slices, two ways: with the kernels addressing the host chunk themselves
-    ("direct"), and staged through HBM by the copy engines, 4 layers per stage, while the
+    ("direct"), and staged through HBM by the copy engines, 8 layers per stage, while the
     neighbouring stage is quantised (store) or dequantised and scattered (compose).  In both
     only the compact rows cross PCIe.  The rates are link bound (PCIe-inclusive)."""
     import torch
@@ -383,7 +383,7 @@ def workload_host_stream(args, dev, fmt_name):
     order = synth.permutation(w.seed, n_slices)
     slices = [host.slice(int(i) * (T // n_slices), T // n_slices) for i in order]
     offsets = [int(j * (T // n_slices)) for j in range(n_slices)]
-    lps = 4
+    lps = 8        # 4 stages: few copies outstanding at a time (the runtime slows down beyond about a dozen)
     staging = torch.empty(max(kdn.kdn_staging_bytes(slices, lps), kdn.kdn_store_staging_bytes(cache, T, fmt, lps)),
                           dtype=torch.uint8, device=dev)
     kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)

@@ -323,7 +323,11 @@ kdn_status kdn_patch_rows(const void *rows_dev, const int32_t *tokens_dev, int32
  * scattered on `stream`: copy and kernels overlap, and the two halves of the staging
  * buffer alternate.  The staging buffer may be reused by the next call on any stream.
  * KDN_EINVAL if a chunk is not in pinned host memory, KDN_ESIZE if the staging buffer is
- * too small. */
+ * too small.  Choosing layers_per_stage: the kernels are about a hundred times faster
+ * than the link, so a handful of stages already hides them; each stage enqueues one or
+ * two copies per host buffer, and calls issued back to back run slower once more than
+ * about a dozen copies are outstanding (measured: 32 layers in 8 stages 6.5 ms per call,
+ * in 4 stages or fewer 5.0 ms). */
 kdn_status kdn_compose_from_host(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
                                  const kdn_cache_desc *cache, const int32_t *block_table_dev,
                                  int32_t table_len, int32_t dest_token_start, double rope_base,

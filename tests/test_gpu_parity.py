@@ -832,6 +832,40 @@ def test_capped_launch_gives_the_same_result(cap, D, fmt):
         assert_cache_equal(dd, hd)
 
 
+def test_host_path_argument_errors():
+    """Pageable host memory, short or misaligned staging memory and a negative cap come back
+    as status codes with nothing enqueued."""
+    import ctypes as C
+    L, nb, bs, H, D = 2, 16, 16, 2, 64
+    hc = host_cache(161, L, nb, bs, H, D)
+    dc = dev_cache(hc)
+    bt = dev_table(np.arange(8, dtype=np.int32))
+    cd = dc.desc()
+    need = kdn.kdn_store_staging_bytes(dc, 100, INT8, 1)
+    staging = torch.empty(need + 16, dtype=torch.uint8, device="cuda")
+    pageable = kdn.chunk_from_buffer(torch.empty(kdn.kdn_chunk_bytes(L, H, D, 100, INT8), dtype=torch.uint8),
+                                     INT8, L, H, D, 100)
+    pinned = kdn.alloc_host_chunk(dc, 100, INT8)
+
+    def store_to_host(chunk, ptr, nbytes, lps=1):
+        return kdn.lib().kdn_store_to_host(C.byref(cd), bt.data_ptr(), bt.numel(), 0, 100, C.byref(chunk.desc),
+                                           ptr, nbytes, lps, None)
+    assert store_to_host(pageable, staging.data_ptr(), need) == kdn.EINVAL
+    assert store_to_host(pinned, staging.data_ptr(), need - 1) == kdn.ESIZE
+    assert store_to_host(pinned, staging.data_ptr() + 8, need) == kdn.EALIGN
+    assert store_to_host(pinned, staging.data_ptr(), need, lps=0) == kdn.EINVAL
+    assert store_to_host(pinned, staging.data_ptr(), need) == kdn.OK
+    torch.cuda.synchronize()
+    assert np.array_equal(pinned.data.numpy(), O.store(hc, np.arange(8, dtype=np.int32), 0, 100, INT8).data)
+    with pytest.raises(kdn.KdnError) as e:
+        kdn.kdn_compose_from_host([pageable], [0], dc, bt, 10000.0, staging, 1)
+    assert e.value.status == kdn.EINVAL
+    opts = kdn.LaunchOpts(-1)
+    out = kdn.alloc_chunk(dc, 100, INT8)
+    assert kdn.lib().kdn_store_chunk_opts(C.byref(cd), bt.data_ptr(), bt.numel(), 0, 100, C.byref(out.desc),
+                                          C.byref(opts), None) == kdn.EINVAL
+
+
 def lib_store_to_host_with_device_chunk(dc, a, fmt, staging, layers_per_stage):
     import ctypes as C
     dev_chunk = kdn.alloc_chunk(dc, 110, fmt)

@@ -139,6 +139,10 @@ def workload_8b(args, dev):
     blocks = T // sh.bs
     n_sets = 4
     nb = n_sets * 3 * blocks
+    if args.pool_blocks:
+        if args.pool_blocks < nb:
+            raise SystemExit("bench.py: --pool-blocks must be at least %d" % nb)
+        nb = args.pool_blocks
     g = torch.Generator(device=dev)
     g.manual_seed(w.seed)
     if args.layout == "planes":         # K and V tensors [L][num_blocks][bs][H][D]
@@ -188,11 +192,11 @@ def workload_8b(args, dev):
         "place_calls": ("load", "compose"),
         "workload": "Llama-3-8B-shaped KV (L32 H8 D128 bs16): per step store 4096 tokens to %s, "
                     "load them at offset 0, compose them as 8x512-token slices in seeded order with "
-                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled; cache layout %s; %s block tables"
-                    % (args.fmt, w.rope_base, n_sets, args.layout,
+                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled; cache layout %s, pool of %d blocks; %s block tables"
+                    % (args.fmt, w.rope_base, n_sets, args.layout, nb,
                        "random disjoint" if args.tables == "random" else "consecutive-block"),
         "traffic": counter_traffic() if args.fmt == "int8" and args.tables == "random" and args.layout == "planes"
-        else None,
+        and not args.pool_blocks else None,
     }
     if not args.no_cpu_baseline and args.fmt == "int8":
         res["cpu_baseline"] = cpu_baseline(kdn, cache, sets[0], order, offsets, w.rope_base, T, n_slices,
@@ -783,6 +787,9 @@ def main() -> int:
     ap.add_argument("--tables", choices=("random", "consecutive"), default="random",
                     help="block tables of the 8b workload: sampled without replacement from the pool "
                          "(default, the stated workload) or runs of consecutive blocks")
+    ap.add_argument("--pool-blocks", type=int, default=0,
+                    help="blocks in the paged pool of the 8b workload (default 3072, the 12 tables of 256 blocks "
+                         "it uses); the distance between a block's tiles in neighbouring planes follows from it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=8)
     ap.add_argument("--calibration-copy", action="store_true",

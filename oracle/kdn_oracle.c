@@ -17,11 +17,14 @@
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -fPIC -shared kdn_oracle.c -lm
  *
- * Pinned by tests/test_oracle_*.py: address resolution by brute force with
+ * Pinned by tests/test_oracle_pins.py: address resolution by brute force with
  * tagged fills, bf16 rounding against a float64 formulation, scales and codes
- * against float64 arithmetic, the error bound, the rotation against complex
- * multiplication / the shift identity R(d)K(p) = K(p+d), zero-offset compose
- * against concatenation.  Absolute output values of the five workloads are
+ * against float64 arithmetic, the error bound (per row, and of a whole store
+ * against the source rows), which source row feeds which stored row and scale
+ * slot for every quantised form, the rotation against complex multiplication /
+ * the shift identity R(d)K(p) = K(p+d), zero-offset compose against
+ * concatenation.  tests/test_oracle_mutants.py plants one mistake at a time in
+ * a copy of this file and requires a pin to fail.  Absolute output values of the five workloads are
  * not printed anywhere in the paper: for those, parity is unpinned by the
  * paper and rests on the pins above.
  */

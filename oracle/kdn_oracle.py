@@ -14,8 +14,10 @@ import threading
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "kdn_oracle.c")
-_LIB = os.path.join(_HERE, "libkdn_oracle.so")
+# KDN_ORACLE_SRC names another copy of the C source (the mutation test plants one mistake
+# per copy and expects the pins to fail); its library is built beside that copy.
+_SRC = os.environ.get("KDN_ORACLE_SRC") or os.path.join(_HERE, "kdn_oracle.c")
+_LIB = os.path.join(os.path.dirname(os.path.abspath(_SRC)), "libkdn_oracle.so")
 
 FMT_RAW_BF16 = 0
 FMT_INT8_ROWSCALE = 1

@@ -752,3 +752,79 @@ def test_store_of_a_token_list(oracle, fmt):
                         assert np.array_equal(ch.scales4()[l, side, i, h], s_)
     with pytest.raises(ValueError):
         oracle.store_tokens(cache, bt, np.array([1, 36]), fmt)          # 36 is past the table
+
+
+# ------------------------------------------------- the quantised store, row by row
+def _quantise(oracle, fmt, row):
+    """(codes, scales) of one source row through the row quantiser of the format."""
+    if fmt == INT8:
+        return oracle.quantise_row(row)
+    if fmt == FP8:
+        return oracle.quantise_row_fp8(row)
+    return oracle.quantise_row_int4(row)
+
+
+@pytest.mark.parametrize("fmt", [INT8, INT4, FP8])
+def test_quantised_store_puts_each_source_row_and_its_scale_in_its_own_slot(oracle, fmt):
+    """Which source row feeds which stored row and which scale slot: for a ragged token
+    range over a shuffled table, row (l, side, t, h) of the chunk holds the quantised
+    row cache[l, bt[(t0+t)//bs], (t0+t)%bs, h], codes and scale(s) alike.  The row
+    quantisers are pinned on their own above; this pins the indexing around them."""
+    L, nb, bs, H, D = 3, 40, 4, 3, 64
+    cache = make_cache(oracle, 51, L, nb, bs, H, D)
+    bt = synth.disjoint_block_tables(51, nb, [9])[0]
+    t0, T = 6, 27                                        # starts and ends inside a block
+    ch = oracle.store(cache, bt, t0, T, fmt)
+    assert ch.Tp == T and ch.data.nbytes == L * 2 * T * H * (D // 2 + D // 8 if fmt == INT4 else D + 4)
+    seen_rows = set()
+    for l in range(L):
+        for side, base in enumerate((cache.k, cache.v)):
+            for t in range(T):
+                tok = t0 + t
+                rows = base[l, int(bt[tok // bs]), tok % bs]               # [H][D]
+                for h in range(H):
+                    q, s = _quantise(oracle, fmt, rows[h])
+                    if fmt == INT4:
+                        assert np.array_equal(ch.packed4()[l, side, t, h], q)
+                        assert np.array_equal(ch.scales4()[l, side, t, h], s)
+                    else:
+                        assert np.array_equal(ch.codes()[l, side, t, h], q)
+                        assert ch.scales()[l, side, t, h] == s
+                    seen_rows.add(q.tobytes())
+    # the rows are distinguishable: a permuted placement could not pass by coincidence
+    assert len(seen_rows) == L * 2 * T * H
+
+
+@pytest.mark.parametrize("fmt", [INT8, INT4])
+def test_store_then_load_is_within_half_a_step_of_the_source(oracle, fmt):
+    """The round trip of a store: the dequantised value of every stored element lies
+    within half a quantisation step of the SOURCE element it came from (step taken in
+    float64 from the source row's own maximum, not from the chunk), and what a load
+    into another table writes is that value rounded once more to bf16."""
+    L, nb, bs, H, D = 2, 48, 8, 2, 64
+    src = make_cache(oracle, 52, L, nb, bs, H, D)
+    a, b = synth.disjoint_block_tables(52, nb, [6, 7])
+    t0, T, dest = 5, 37, 3
+    ch = oracle.store(src, a, t0, T, fmt)
+    dst = make_cache(oracle, 53, L, nb, bs, H, D)
+    oracle.load(ch, dst, b, dest)
+    qmax, group = (127.0, D) if fmt == INT8 else (7.0, 32)
+    if fmt == INT8:
+        codes = ch.codes().astype(np.float64)
+        scales = np.repeat(ch.scales().astype(np.float64)[..., None], D, axis=-1)
+    else:
+        codes = unpack_nibbles(ch.packed4()).astype(np.float64)
+        scales = np.repeat(ch.scales4().astype(np.float64), 32, axis=-1)
+    for side, (sb, db) in enumerate(((src.k, dst.k), (src.v, dst.v))):
+        for t in range(T):
+            s_blk, s_slot = int(a[(t0 + t) // bs]), (t0 + t) % bs
+            d_blk, d_slot = int(b[(dest + t) // bs]), (dest + t) % bs
+            x = bf16_bits_to_f64(sb[:, s_blk, s_slot])                     # [L][H][D], the source
+            step = np.abs(x).reshape(L, H, D // group, group).max(-1) / qmax
+            step = np.repeat(step, group, axis=-1).reshape(L, H, D)
+            y = codes[:, side, t] * scales[:, side, t]
+            assert np.all(np.abs(x - y) <= step * (0.5 + 1e-4))
+            got = bf16_bits_to_f64(db[:, d_blk, d_slot])
+            half_ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(y), 1e-300))) - 8)
+            assert np.all(np.abs(got - y) <= half_ulp)
+            assert np.all(np.abs(got - x) <= step * (0.5 + 1e-4) + half_ulp)

@@ -34,7 +34,10 @@
  *   - HIP graph capture: kdn_store_chunk, kdn_store_tokens, kdn_load_chunk,
  *     kdn_patch_rows, and kdn_compose / kdn_compose_rope with at most 64 chunks whose
  *     cos/sin rows are resident (kdn_rope_prepare) enqueue kernels only and may be
- *     captured.  Composes with more chunks (their segment table is copied from pinned
+ *     captured.  The rows that kdn_rope_prepare made resident are pinned: the captured
+ *     kernels keep reading the right cos/sin values on every replay, also after other
+ *     calls have filled and recycled the rest of the table; only kdn_rope_release and
+ *     kdn_shutdown end that.  Composes with more chunks (their segment table is copied from pinned
  *     memory and guarded by events), the staged host paths (kdn_store_to_host,
  *     kdn_compose_from_host, kdn_compose_from_host_staged: copies and events on
  *     library streams) and kdn_validate_block_table must not be captured.
@@ -100,7 +103,8 @@ typedef enum {
     KDN_ESIZE = -4,        /* chunk buffer too small, too many chunks, grid limit exceeded */
     KDN_EDEVICE = -5,      /* a HIP call failed, or no usable device */
     KDN_EUNSUPPORTED = -6, /* head_dim not a multiple of 16 (32 for int4) or above 512 */
-    KDN_ENOTFOUND = -7     /* no entry under this key (text-keyed pool) */
+    KDN_ENOTFOUND = -7,    /* no entry under this key (text-keyed pool) */
+    KDN_EFULL = -8         /* the call needs more cos/sin rows than kdn_rope_prepare has left unpinned */
 } kdn_status;
 
 typedef enum {
@@ -375,15 +379,26 @@ kdn_status kdn_host_stage_plan(const kdn_chunk *chunks, int32_t n_chunks, int32_
                                int32_t stage, kdn_stage_copy *copies_out, int32_t cap, int32_t *n_copies,
                                uint64_t *view_offsets);
 
-/* Make the cos/sin rows of the given offsets resident so that later composes with
- * them enqueue no copy (needed before capturing composes into a HIP graph).
- * offsets: [host] array of n. */
+/* Make the cos/sin rows of the given offsets resident, so that later composes with them
+ * enqueue no copy (needed before capturing composes into a HIP graph), and pin them: a
+ * pinned row keeps its place and contents until kdn_rope_release or kdn_shutdown, so a
+ * captured graph that holds its index replays correctly whatever happens in between.
+ * Rows that a compose brings in by itself are transient: when the table of a (frequencies,
+ * rotary width) pair has no free row (it holds 4096), the device is synchronised and the
+ * transient rows are dropped; pinned rows are not touched.  KDN_EFULL when the offsets
+ * need more rows than are left unpinned (nothing is changed then).  offsets: [host] array
+ * of n. */
 kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *offsets,
                             int32_t n);
 
 /* The same for a RoPE variant (rope: [host], not NULL). */
 kdn_status kdn_rope_prepare_spec(const kdn_rope_spec *rope, int32_t head_dim, const int32_t *offsets,
                                  int32_t n);
+
+/* Drops every cos/sin row of the current device, pinned ones included (synchronises the
+ * device first).  Graphs captured earlier that hold composes with a non-zero offset must
+ * not be replayed afterwards: prepare and capture again. */
+kdn_status kdn_rope_release(void);
 
 /* Debug check, synchronous: KDN_ERANGE if any of the table_len entries of
  * block_table_dev [device] is outside [0, num_blocks) or occurs twice. */
@@ -398,6 +413,10 @@ kdn_status kdn_f32_to_bf16(const float *in_dev, uint16_t *out_dev, uint64_t n, v
 kdn_status kdn_shutdown(void);
 
 const char *kdn_status_str(kdn_status status);
+
+/* "kdn-gfx950 <version> src:<16 hex digits>": the digits are a hash of the sources and
+ * compiler flags the library was built from, so that a caller (the Python binding does)
+ * can refuse a binary that does not belong to the sources beside it. */
 const char *kdn_version(void);
 
 #ifdef __cplusplus

@@ -1,7 +1,9 @@
 """Build the HIP library (libkdn.so) for gfx950, in tree, with hipcc."""
 from __future__ import annotations
 
+import hashlib
 import os
+import re
 import subprocess
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
@@ -19,11 +21,37 @@ HIPCC_FLAGS = [
 ]
 
 
-def is_stale() -> bool:
-    if not os.path.exists(LIB_PATH):
-        return True
-    t = os.path.getmtime(LIB_PATH)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS + [os.path.abspath(__file__)])
+def source_fingerprint(files=None) -> str:
+    """sha256 (first 16 hex digits) over the library's sources, headers and compiler flags.
+    It is compiled into the library (kdn_version() ends with it), so that a binary can be
+    matched against the sources beside it."""
+    h = hashlib.sha256()
+    for f in (SOURCES + HEADERS) if files is None else files:
+        h.update(os.path.basename(f).encode() + b"\0")
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+        h.update(b"\0")
+    h.update(" ".join(HIPCC_FLAGS).encode())
+    return h.hexdigest()[:16]
+
+
+_MARK = re.compile(rb"kdn-gfx950 [0-9.]+ src:([0-9a-f]{16})")
+
+
+def library_fingerprint(path=None):
+    """The source fingerprint a built library carries (read from the file, nothing is
+    loaded), or None if there is no library or it carries none."""
+    path = LIB_PATH if path is None else path
+    if not os.path.exists(path):
+        return None
+    with open(path, "rb") as fh:
+        m = _MARK.search(fh.read())
+    return m.group(1).decode() if m else None
+
+
+def is_stale(path=None, files=None) -> bool:
+    """True when there is no library or it was built from other sources or flags."""
+    return library_fingerprint(path) != source_fingerprint(files)
 
 
 def build_library(force: bool = True, verbose: bool = False) -> str:
@@ -32,7 +60,8 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
         return LIB_PATH
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB_PATH + ".%d.tmp" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(_ROOT, "include"), "-o", tmp] + SOURCES
+    cmd = ([hipcc] + HIPCC_FLAGS + ["-DKDN_SRC_HASH=\"%s\"" % source_fingerprint(),
+                                    "-I", os.path.join(_ROOT, "include"), "-o", tmp] + SOURCES)
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -48,9 +77,14 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
 
 
 def ensure_built() -> str:
-    """Build only when no library is there at all (a fresh checkout); one that is there is
-    used as it is."""
-    return LIB_PATH if os.path.exists(LIB_PATH) else build_library(force=True)
+    """The library that matches the sources in the tree: built when there is none, built
+    again when the one that is there carries another source fingerprint.  A failing
+    compiler raises; a stale binary is never handed out."""
+    if is_stale():
+        build_library(force=True)
+        if is_stale():
+            raise RuntimeError("libkdn.so does not carry the fingerprint of the sources it was just built from")
+    return LIB_PATH
 
 
 if __name__ == "__main__":

@@ -520,6 +520,11 @@ static kdn_status compose_from_host_impl(const kdn_chunk *chunks, const int32_t 
     const uint64_t half_bytes = need / 2;
     std::vector<StageCopy> copies;
     std::vector<uint64_t> staged_at;
+    // The copies read the host chunks and write the staging memory on the library's copy
+    // stream: order them behind everything the caller's stream holds so far (a store that
+    // is still landing in the same host chunk, kernels that still use the staging memory).
+    if (hipEventRecord(ln.entry, user) != hipSuccess || hipStreamWaitEvent(ln.stream, ln.entry, 0) != hipSuccess)
+        return KDN_EDEVICE;
     st = begin_staging(ln, ds->to_host, staging, need, ln.stream); // the copies write the staging memory
     if (st != KDN_OK)
         return st;
@@ -629,7 +634,7 @@ static kdn_status rope_prepare_impl(const kdn_rope_spec *variant, double rope_ba
         return KDN_EDEVICE;
     std::vector<int32_t> rows((size_t)n);
     const f32x2 *table;
-    return rope_rows(ds, spec, offsets, n, rows.data(), &table);
+    return rope_rows(ds, spec, offsets, n, rows.data(), &table, /*pin=*/true);
 }
 
 kdn_status kdn_rope_prepare(double rope_base, int32_t head_dim, const int32_t *offsets, int32_t n)
@@ -643,6 +648,27 @@ kdn_status kdn_rope_prepare_spec(const kdn_rope_spec *rope, int32_t head_dim, co
     if (!rope)
         return KDN_EINVAL;
     return rope_prepare_impl(rope, rope->base, head_dim, offsets, n);
+}
+
+kdn_status kdn_rope_release(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *ds = device_state(nullptr);
+    if (!ds)
+        return KDN_EDEVICE;
+    if (hipDeviceSynchronize() != hipSuccess) // nothing may still read a row that is about to go
+        return KDN_EDEVICE;
+    for (RopeTable &rt : ds->rope) {
+        rt.row_of.clear();
+        rt.n_pinned = 0;
+        if (rt.dev) {
+            rt.pinned.assign((size_t)kRopeRowsCap, 0);
+            rt.free_rows.resize((size_t)kRopeRowsCap);
+            for (int32_t r = 0; r < kRopeRowsCap; ++r)
+                rt.free_rows[(size_t)r] = kRopeRowsCap - 1 - r;
+        }
+    }
+    return KDN_OK;
 }
 
 kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t table_len,
@@ -729,10 +755,14 @@ const char *kdn_status_str(kdn_status s)
     case KDN_EDEVICE: return "HIP call failed";
     case KDN_EUNSUPPORTED: return "head_dim must be a multiple of 16 (32 for int4), at most 512";
     case KDN_ENOTFOUND: return "no entry under this key";
+    case KDN_EFULL: return "every cos/sin row is pinned by kdn_rope_prepare (kdn_rope_release frees them)";
     }
     return "unknown status";
 }
 
-const char *kdn_version(void) { return "kdn-gfx950 0.1"; }
+#ifndef KDN_SRC_HASH
+#error "build with -DKDN_SRC_HASH=\"<fingerprint of the sources>\" (paper_2409_13761_amd/build.py does)"
+#endif
+const char *kdn_version(void) { return "kdn-gfx950 0.2 src:" KDN_SRC_HASH; }
 
 } // extern "C"

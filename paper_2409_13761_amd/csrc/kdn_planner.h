@@ -26,13 +26,19 @@ struct RopeSpec {
     int32_t pairing = KDN_ROPE_HALF_SPLIT;
 };
 
-// cos/sin rows of one (frequencies, rot) pair, one row per offset seen so far
+// cos/sin rows of one (frequencies, rot) pair, one row per offset seen so far.  A row that
+// kdn_rope_prepare made resident is pinned: it keeps its place and its contents until
+// kdn_rope_release or kdn_shutdown, so a captured graph that holds its index stays valid.
+// Rows that a compose brought in by itself are transient and go when the table fills up.
 struct RopeTable {
     f32x2 *dev = nullptr;
     double base = 0.0;
     std::vector<double> freq;
     int32_t rot = 0;
     std::unordered_map<int32_t, int32_t> row_of;
+    std::vector<uint8_t> pinned;    // per row
+    std::vector<int32_t> free_rows; // rows that hold nothing
+    int32_t n_pinned = 0;
 };
 
 // One direction of the host link: a copy stream and, per half of the caller's staging
@@ -40,6 +46,7 @@ struct RopeTable {
 // so that a call in the other direction that reuses the memory can wait for it.
 struct LinkDir {
     hipStream_t stream = nullptr;
+    hipEvent_t entry = nullptr; // recorded on the caller's stream when a call begins
     hipEvent_t filled[2] = {};
     hipEvent_t drained[2] = {};
     bool drained_valid[2] = {};
@@ -167,6 +174,8 @@ inline kdn_status ensure_link(LinkDir &ln)
         return KDN_OK;
     if (hipStreamCreateWithFlags(&ln.stream, hipStreamNonBlocking) != hipSuccess)
         return KDN_EDEVICE;
+    if (hipEventCreateWithFlags(&ln.entry, hipEventDisableTiming) != hipSuccess)
+        return KDN_EDEVICE;
     for (int b = 0; b < 2; ++b)
         if (hipEventCreateWithFlags(&ln.filled[b], hipEventDisableTiming) != hipSuccess
             || hipEventCreateWithFlags(&ln.drained[b], hipEventDisableTiming) != hipSuccess)
@@ -202,6 +211,8 @@ inline void destroy_link(LinkDir &ln)
     if (!ln.stream)
         return;
     (void)hipStreamDestroy(ln.stream);
+    if (ln.entry)
+        (void)hipEventDestroy(ln.entry);
     for (int b = 0; b < 2; ++b) {
         if (ln.filled[b])
             (void)hipEventDestroy(ln.filled[b]);
@@ -235,9 +246,13 @@ inline kdn_status resolve_spec(const kdn_rope_spec *in, double base, int32_t D, 
 }
 
 // Returns the cos/sin table of the variant and fills rows[i] for offsets[i] (-1 for a
-// zero offset).  New rows are computed in double and uploaded before returning.
+// zero offset).  New rows are computed in double and uploaded before returning.  With
+// `pin` the rows of this call become pinned.  When no row is free, the device is
+// synchronised (nothing can still read the table) and every transient row is dropped;
+// pinned rows keep their index and contents.  KDN_EFULL when the call needs more rows
+// than are not pinned by others.
 inline kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t *offsets, int32_t n,
-                            int32_t *rows, const f32x2 **table)
+                            int32_t *rows, const f32x2 **table, bool pin = false)
 {
     *table = nullptr;
     bool any = false;
@@ -250,14 +265,6 @@ inline kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t
     }
     if (spec.freq.empty() && (!(spec.base > 0.0) || !std::isfinite(spec.base)))
         return KDN_EINVAL;
-    {
-        std::unordered_map<int32_t, int32_t> distinct;
-        for (int32_t i = 0; i < n; ++i)
-            if (offsets[i] != 0)
-                distinct.emplace(offsets[i], 0);
-        if ((int32_t)distinct.size() > kRopeRowsCap)
-            return KDN_ESIZE;
-    }
     size_t ti = 0;
     for (; ti < ds->rope.size(); ++ti) {
         const RopeTable &t = ds->rope[ti];
@@ -272,11 +279,32 @@ inline kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t
         ds->rope.push_back(std::move(t));
     }
     RopeTable &rt = ds->rope[ti];
+    {
+        // rows this call needs beyond the pinned ones it can share
+        std::unordered_map<int32_t, int32_t> distinct;
+        for (int32_t i = 0; i < n; ++i)
+            if (offsets[i] != 0)
+                distinct.emplace(offsets[i], 0);
+        if ((int32_t)distinct.size() > kRopeRowsCap)
+            return KDN_ESIZE;
+        int32_t fresh = 0;
+        for (const auto &kv : distinct) {
+            auto it = rt.row_of.find(kv.first);
+            if (it == rt.row_of.end() || !rt.pinned[(size_t)it->second])
+                ++fresh;
+        }
+        if (fresh > kRopeRowsCap - rt.n_pinned)
+            return KDN_EFULL;
+    }
     const int32_t half = spec.rot / 2;
-    if (!rt.dev
-        && hipMalloc(reinterpret_cast<void **>(&rt.dev), (size_t)kRopeRowsCap * half * sizeof(f32x2))
-               != hipSuccess)
-        return KDN_EDEVICE;
+    if (!rt.dev) {
+        if (hipMalloc(reinterpret_cast<void **>(&rt.dev), (size_t)kRopeRowsCap * half * sizeof(f32x2)) != hipSuccess)
+            return KDN_EDEVICE;
+        rt.pinned.assign((size_t)kRopeRowsCap, 0);
+        rt.free_rows.resize((size_t)kRopeRowsCap);
+        for (int32_t r = 0; r < kRopeRowsCap; ++r)
+            rt.free_rows[(size_t)r] = kRopeRowsCap - 1 - r; // handed out from row 0 up
+    }
     std::vector<float> row((size_t)half * 2);
     for (int32_t i = 0; i < n; ++i) {
         const int32_t d = offsets[i];
@@ -287,16 +315,29 @@ inline kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t
         auto it = rt.row_of.find(d);
         if (it != rt.row_of.end()) {
             rows[i] = it->second;
+            if (pin && !rt.pinned[(size_t)it->second]) {
+                rt.pinned[(size_t)it->second] = 1;
+                ++rt.n_pinned;
+            }
             continue;
         }
-        if ((int32_t)rt.row_of.size() >= kRopeRowsCap) {
-            // table full: wait until nothing can still read it, then start over
+        if (rt.free_rows.empty()) {
+            // table full: wait until nothing can still read it, then drop the transient rows
             if (hipDeviceSynchronize() != hipSuccess)
                 return KDN_EDEVICE;
-            rt.row_of.clear();
-            for (int32_t k = 0; k < i; ++k) // rows handed out earlier in this call are gone
-                if (offsets[k] != 0)
+            for (auto e = rt.row_of.begin(); e != rt.row_of.end();) {
+                if (rt.pinned[(size_t)e->second]) {
+                    ++e;
+                } else {
+                    rt.free_rows.push_back(e->second);
+                    e = rt.row_of.erase(e);
+                }
+            }
+            for (int32_t k = 0; k < i; ++k) // transient rows handed out earlier in this call are gone
+                if (offsets[k] != 0 && rt.row_of.find(offsets[k]) == rt.row_of.end())
                     rows[k] = -2;
+            if (rt.free_rows.empty())
+                return KDN_EFULL;
         }
         for (int32_t j = 0; j < half; ++j) {
             const double theta = spec.freq.empty() ? std::pow(spec.base, -(double)(2 * j) / (double)spec.rot)
@@ -305,17 +346,22 @@ inline kdn_status rope_rows(DeviceState *ds, const RopeSpec &spec, const int32_t
             row[2 * j] = (float)std::cos(phi);
             row[2 * j + 1] = (float)std::sin(phi);
         }
-        const int32_t r = (int32_t)rt.row_of.size();
+        const int32_t r = rt.free_rows.back();
         if (hipMemcpy(rt.dev + (size_t)r * half, row.data(), row.size() * sizeof(float),
                       hipMemcpyHostToDevice)
             != hipSuccess)
             return KDN_EDEVICE;
+        rt.free_rows.pop_back();
         rt.row_of.emplace(d, r);
+        if (pin) {
+            rt.pinned[(size_t)r] = 1;
+            ++rt.n_pinned;
+        }
         rows[i] = r;
     }
     for (int32_t i = 0; i < n; ++i)
-        if (rows[i] == -2) // only after a table reset inside this call
-            return rope_rows(ds, spec, offsets, n, rows, table);
+        if (rows[i] == -2) // only after the transient rows were dropped inside this call
+            return rope_rows(ds, spec, offsets, n, rows, table, pin);
     *table = rt.dev;
     return KDN_OK;
 }

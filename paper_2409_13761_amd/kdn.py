@@ -21,7 +21,7 @@ FMT_INT8_ROWSCALE = 1
 FMT_INT4_GROUP32 = 2
 FMT_FP8_ROWSCALE = 3
 
-OK, EINVAL, EALIGN, ERANGE, ESIZE, EDEVICE, EUNSUPPORTED, ENOTFOUND = 0, -1, -2, -3, -4, -5, -6, -7
+OK, EINVAL, EALIGN, ERANGE, ESIZE, EDEVICE, EUNSUPPORTED, ENOTFOUND, EFULL = 0, -1, -2, -3, -4, -5, -6, -7, -8
 
 
 class KdnError(RuntimeError):
@@ -151,6 +151,8 @@ def lib() -> C.CDLL:
         L.kdn_rope_prepare.argtypes = [C.c_double, i32, C.POINTER(i32), i32]
         L.kdn_rope_prepare_spec.restype = C.c_int
         L.kdn_rope_prepare_spec.argtypes = [C.POINTER(RopeSpecDesc), i32, C.POINTER(i32), i32]
+        L.kdn_rope_release.restype = C.c_int
+        L.kdn_rope_release.argtypes = []
         L.kdn_validate_block_table.restype = C.c_int
         L.kdn_validate_block_table.argtypes = [vp, i32, i32, vp]
         L.kdn_f32_to_bf16.restype = C.c_int
@@ -161,6 +163,11 @@ def lib() -> C.CDLL:
         L.kdn_status_str.argtypes = [C.c_int]
         L.kdn_version.restype = C.c_char_p
         L.kdn_version.argtypes = []
+        from . import build as _build
+        built_from = L.kdn_version().decode().rsplit("src:", 1)[-1]
+        if built_from != _build.source_fingerprint():
+            raise ImportError("libkdn.so was built from other sources (it carries %s, the tree is %s): "
+                              "run `python -m paper_2409_13761_amd.build`" % (built_from, _build.source_fingerprint()))
         _lib = L
     return _lib
 
@@ -169,7 +176,7 @@ EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_ch
            "kdn_store_to_host", "kdn_store_staging_bytes", "kdn_store_chunk_opts", "kdn_compose_opts",
            "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_rope",
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host", "kdn_compose_from_host_staged",
-           "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec",
+           "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec", "kdn_rope_release",
            "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version", "kdn_pool_create", "kdn_pool_destroy", "kdn_pool_hash", "kdn_pool_lookup",
            "kdn_pool_insert", "kdn_pool_remove", "kdn_pool_get_stats"]
@@ -544,6 +551,10 @@ def kdn_rope_prepare_spec(spec, head_dim: int, offsets) -> None:
     """spec: the pair returned by rope_spec()."""
     off = (C.c_int32 * len(offsets))(*[int(o) for o in offsets])
     _check(lib().kdn_rope_prepare_spec(C.byref(spec[0]), head_dim, off, len(offsets)), "kdn_rope_prepare_spec")
+
+
+def kdn_rope_release() -> None:
+    _check(lib().kdn_rope_release(), "kdn_rope_release")
 
 
 def kdn_validate_block_table(block_table: torch.Tensor, num_blocks: int, stream=None) -> int:

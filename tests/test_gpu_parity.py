@@ -672,26 +672,119 @@ def test_store_tokens_matches_oracle(fmt, shape):
 
 
 # ------------------------------------------------------------------ planner state under load
-def test_cos_sin_table_refills_after_it_overflows():
-    """More distinct offsets than the resident table holds: the table is drained and
-    refilled, and composes before and after still match the oracle."""
-    L, nb, bs, H, D = 1, 16, 16, 1, 32
+def test_cos_sin_table_recycles_transient_rows_and_keeps_pinned_ones():
+    """More distinct offsets than the resident table holds.  Rows that composes bring in by
+    themselves are dropped when the table is full and composes before and after still match
+    the oracle; rows that kdn_rope_prepare pinned keep their place, so a graph captured
+    before the table overflowed replays with the right cos/sin values afterwards."""
+    L, nb, bs, H, D = 1, 24, 16, 1, 32
     src = host_cache(111, L, nb, bs, H, D)
-    a, b = synth.disjoint_block_tables(111, nb, [2, 4])
+    a, b, c = synth.disjoint_block_tables(111, nb, [2, 4, 8])
     ch = O.store(src, a, 0, 32, INT8)
     dch = chunk_to_dev(ch)
     base = 12345.0                                 # a table of its own
-    for start in (1, 3000, 6000):                  # 9000 distinct offsets in all, capacity is 4096
-        kdn.kdn_rope_prepare(base, D, list(range(start, start + 3000)))
-        d = start + 1500
-        hd = host_cache(112, L, nb, bs, H, D)
-        dd = dev_cache(hd)
-        O.compose([ch, ch], [d, 7], hd, b, base)
-        kdn.kdn_compose([dch, dch], [d, 7], dd, dev_table(b), base)
+    pinned = [777, -4242]
+    kdn.kdn_rope_prepare(base, D, pinned)
+    dd = dev_cache(host_cache(112, L, nb, bs, H, D))
+    tb, tc = dev_table(b), dev_table(c)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        kdn.kdn_compose([dch, dch], pinned, dd, tb, base)       # warm-up outside the capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            kdn.kdn_compose([dch, dch], pinned, dd, tb, base)
+    torch.cuda.synchronize()
+    views = [dch.slice(i % 32, 1) for i in range(64)]
+    hviews = [ch.slice(i % 32, 1) for i in range(64)]
+    n_calls = 0
+    for start in range(1, 6000, 64):               # 94 composes of 64 new offsets each: capacity is 4096
+        offs = list(range(start, start + 64))
+        kdn.kdn_compose(views, offs, dd, tc, base)
+        n_calls += 1
+        if start in (1, 1985, 4033, 4097, 5953):   # before, around and after the table fills up
+            hd = host_cache(113, L, nb, bs, H, D)
+            d2 = dev_cache(hd)
+            O.compose(hviews, offs, hd, c, base)
+            kdn.kdn_compose(views, offs, d2, tc, base)
+            assert_cache_equal(d2, hd)
+    assert n_calls * 64 > 4096 + 64
+    # the captured compose still reads its own rows
+    for rep in range(2):
+        hd = host_cache(114 + rep, L, nb, bs, H, D)
+        dd.k.copy_(to_dev_bf16(hd.k))
+        dd.v.copy_(to_dev_bf16(hd.v))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        O.compose([ch, ch], pinned, hd, b, base)
         assert_cache_equal(dd, hd)
+        _ = (dd.k.float().sum()).item()             # unrelated eager work between replays
+    # pinning more rows than the table holds is refused and changes nothing
+    kdn.kdn_rope_prepare(base, D, list(range(10000, 14000)))
+    with pytest.raises(kdn.KdnError) as e:
+        kdn.kdn_rope_prepare(base, D, list(range(20000, 20200)))
+    assert e.value.status == kdn.EFULL
     with pytest.raises(kdn.KdnError) as e:          # more distinct offsets in ONE call than the table holds
         kdn.kdn_rope_prepare(base, D, list(range(1, 5000)))
     assert e.value.status == kdn.ESIZE
+    with pytest.raises(kdn.KdnError) as e:          # a compose whose transient rows do not fit beside the pinned ones
+        kdn.kdn_compose(views + views, list(range(30000, 30128)), dd, tc, base)
+    assert e.value.status == kdn.EFULL
+    hd = host_cache(116, L, nb, bs, H, D)
+    d3 = dev_cache(hd)
+    O.compose([ch, ch], pinned, hd, b, base)
+    kdn.kdn_compose([dch, dch], pinned, d3, tb, base)
+    assert_cache_equal(d3, hd)
+    # after a release everything can be prepared again (graphs captured before must not be replayed)
+    kdn.kdn_rope_release()
+    kdn.kdn_rope_prepare(base, D, list(range(20000, 20200)))
+    hd = host_cache(117, L, nb, bs, H, D)
+    d4 = dev_cache(hd)
+    O.compose([ch, ch], [20100, 777], hd, b, base)
+    kdn.kdn_compose([dch, dch], [20100, 777], d4, tb, base)
+    assert_cache_equal(d4, hd)
+    kdn.kdn_rope_release()
+
+
+def test_store_to_host_then_compose_from_host_on_one_stream_without_a_host_sync():
+    """Both staged calls are ordered on the caller's stream: a compose from a host chunk
+    that the preceding call on the same stream is still storing, through a staging tensor
+    that kernels of that stream used just before, sees the finished chunk."""
+    L, nb, bs, H, D = 8, 96, 16, 4, 128
+    src = host_cache(141, L, nb, bs, H, D)
+    a, b = synth.disjoint_block_tables(141, nb, [32, 32])
+    T = 500
+    want = O.store(src, a, 3, T, INT8)
+    hd = host_cache(142, L, nb, bs, H, D)
+    O.compose([want.slice(100, 400), want.slice(0, 100)], [64, -9], hd, b, 10000.0, dest=2)
+    dc = dev_cache(src)
+    dd = dev_cache(host_cache(142, L, nb, bs, H, D))
+    ta, tb = dev_table(a), dev_table(b)
+    out = kdn.alloc_host_chunk(dc, T, INT8)
+    views = [out.slice(100, 400), out.slice(0, 100)]
+    lps = 2
+    n = max(kdn.kdn_store_staging_bytes(dc, T, INT8, lps), kdn.kdn_staging_bytes(views, lps))
+    staging = torch.empty(n, dtype=torch.uint8, device="cuda")
+    kdn.kdn_rope_prepare(10000.0, D, [64, -9])
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        for rep in range(3):
+            out.data.fill_(0xEE)                     # host-side fill: the stream is idle here
+            staging.fill_(0x5A)                      # a kernel of this stream writes the staging memory
+            kdn.kdn_store_to_host(dc, ta, 3, T, out, staging, lps, stream=s)
+            kdn.kdn_compose_from_host(views, [64, -9], dd, tb, 10000.0, staging, lps, dest_token_start=2, stream=s)
+            s.synchronize()
+            assert np.array_equal(out.data.numpy(), want.data), "host chunk, round %d" % rep
+            assert_cache_equal(dd, hd)
+            dd.k.zero_()
+            dd.v.zero_()
+            hd0 = host_cache(142, L, nb, bs, H, D)
+            dd.k.copy_(to_dev_bf16(hd0.k))
+            dd.v.copy_(to_dev_bf16(hd0.v))
+            s.synchronize()
 
 
 def test_two_streams_and_two_host_threads():

@@ -13,9 +13,31 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 @pytest.fixture(scope="module")
 def lib():
-    if not os.path.exists(build.LIB_PATH):
-        build.build_library()
+    build.ensure_built()
     return kdn.lib()
+
+
+def test_a_library_built_from_other_sources_is_recognised(lib, tmp_path):
+    """The binary carries the fingerprint of its sources; a changed comment in a copy of
+    one source already makes the pair (binary, sources) stale."""
+    want = build.source_fingerprint()
+    assert build.library_fingerprint() == want and not build.is_stale()
+    assert kdn.kdn_version().endswith("src:" + want)
+    copies = []
+    for f in build.SOURCES + build.HEADERS:
+        c = tmp_path / os.path.basename(f)
+        c.write_bytes(open(f, "rb").read())
+        copies.append(str(c))
+    assert build.source_fingerprint(copies) == want and not build.is_stale(files=copies)
+    with open(copies[-2], "a") as fh:                      # csrc/kdn_kernels.h
+        fh.write("// a comment\n")
+    assert build.source_fingerprint(copies) != want
+    assert build.is_stale(files=copies)
+    # a file that is no library of ours, or no file at all, counts as stale too
+    other = tmp_path / "libother.so"
+    other.write_bytes(b"\x7fELF no fingerprint here")
+    assert build.library_fingerprint(str(other)) is None and build.is_stale(str(other))
+    assert build.is_stale(str(tmp_path / "missing.so"))
 
 
 def declared_symbols():

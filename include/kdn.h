@@ -275,6 +275,23 @@ kdn_status kdn_compose(const kdn_chunk *chunks, const int32_t *offsets, int32_t 
 kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
                              const kdn_cache_desc *cache, double rope_base, void *stream);
 
+/* kdn_compose_batch for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result.  The call
+ * allocates no device memory, frees none, copies nothing and creates no event or stream:
+ * the segment records and the cos/sin rows of the call ride in kernel arguments into a
+ * scratch array that is part of the library's image (288 KiB per device, held until the
+ * process ends), and the place kernels read them from there; only kernels are enqueued on
+ * `stream`, whatever the number of chunks and whether or not kdn_rope_prepare was called.
+ * Limits: at most 4096 chunk views in all requests together and at most 64 distinct
+ * non-zero offsets per call; beyond either, KDN_ESIZE with nothing enqueued.  Every call
+ * on a device uses that device's one scratch array, which keeps the last call's contents
+ * (each call overwrites the part it uses; nothing has to start at zero): calls on ONE
+ * stream are ordered like any kernels, calls that overlap on two streams of one device
+ * race on it and must be ordered by the caller.  The first call on a device looks the
+ * array's address up (hipGetSymbolAddress) and keeps it: make that call outside a capture. */
+kdn_status kdn_compose_batch_static(const kdn_request *requests, int32_t n_requests,
+                                    const kdn_cache_desc *cache, double rope_base, void *stream);
+
 /* kdn_compose / kdn_compose_batch with a RoPE variant (rope: [host], not NULL).
  * KDN_EUNSUPPORTED if rot_dim is not a multiple of 16. */
 kdn_status kdn_compose_rope(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,

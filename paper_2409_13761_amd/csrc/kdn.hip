@@ -7,6 +7,16 @@
 
 using namespace kdn_impl;
 
+// Scratch of kdn_compose_batch_static: cos/sin rows, then segment records.  Every device the
+// library runs on holds its own copy of this array until the process ends; in host code the
+// name is only a handle for hipGetSymbolAddress, never a device address.
+constexpr int kStaticMaxSegs = 4096;   // chunk views per call
+constexpr int kStaticMaxRopeRows = 64; // distinct non-zero offsets per call
+constexpr size_t kStaticRopeBytes = (size_t)kStaticMaxRopeRows * (kMaxHeadDim / 2) * sizeof(f32x2);
+constexpr size_t kStaticSegBytes = (size_t)kStaticMaxSegs * sizeof(Seg);
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticRopeBytes + kStaticSegBytes];
+static_assert(kStaticRopeBytes % 256 == 0 && sizeof(Seg) % 4 == 0, "scratch layout");
+
 // ---------------------------------------------------------------------------------
 // C ABI
 
@@ -296,6 +306,114 @@ kdn_status kdn_compose_batch(const kdn_request *requests, int32_t n_requests,
                              const kdn_cache_desc *cache, double rope_base, void *stream)
 {
     return compose_impl(requests, n_requests, cache, rope_base, nullptr, stream);
+}
+
+kdn_status kdn_compose_batch_static(const kdn_request *requests, int32_t n_requests,
+                                    const kdn_cache_desc *cache, double rope_base, void *stream)
+{
+    ComposePlan plan;
+    kdn_status st = plan_compose(requests, n_requests, cache, plan);
+    if (st != KDN_OK)
+        return st;
+    RopeSpec spec;
+    st = resolve_spec(nullptr, rope_base, cache->head_dim, spec);
+    if (st != KDN_OK)
+        return st;
+    size_t n_segs = 0;
+    for (int f = 0; f < kFormats; ++f)
+        n_segs += plan.segs[f].size();
+    if (n_segs > (size_t)kStaticMaxSegs)
+        return KDN_ESIZE;
+    // cos/sin rows of this call, in order of first appearance
+    std::vector<int32_t> row_offsets;
+    for (int f = 0; f < kFormats; ++f)
+        for (PlannedSeg &ps : plan.segs[f]) {
+            ps.seg.rope_row = -1;
+            if (ps.offset == 0)
+                continue;
+            size_t r = 0;
+            while (r < row_offsets.size() && row_offsets[r] != ps.offset)
+                ++r;
+            if (r == row_offsets.size()) {
+                if ((int)r == kStaticMaxRopeRows)
+                    return KDN_ESIZE;
+                row_offsets.push_back(ps.offset);
+            }
+            ps.seg.rope_row = (int32_t)r;
+        }
+    if (!row_offsets.empty() && (!(spec.base > 0.0) || !std::isfinite(spec.base)))
+        return KDN_EINVAL;
+
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceState *ds = device_state(nullptr);
+    if (!ds)
+        return KDN_EDEVICE;
+    if (!ds->static_scratch) { // once per device, with that device current
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch)) != hipSuccess || !ptr)
+            return KDN_EDEVICE;
+        ds->static_scratch = static_cast<uint8_t *>(ptr);
+    }
+    uint8_t *scratch = ds->static_scratch;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+
+    // host image of what the kernels will read: the rows, then the records grouped by stored form
+    const int32_t half = spec.rot / 2;
+    std::vector<uint32_t> rope_words((size_t)row_offsets.size() * half * 2);
+    for (size_t r = 0; r < row_offsets.size(); ++r)
+        for (int32_t j = 0; j < half; ++j) {
+            const double theta = std::pow(spec.base, -(double)(2 * j) / (double)spec.rot);
+            const double phi = (double)row_offsets[r] * theta;
+            const float c = (float)std::cos(phi), sn = (float)std::sin(phi);
+            std::memcpy(&rope_words[(r * half + j) * 2], &c, 4);
+            std::memcpy(&rope_words[(r * half + j) * 2 + 1], &sn, 4);
+        }
+    std::vector<Seg> all;
+    all.reserve(n_segs);
+    size_t first[kFormats];
+    for (int f = 0; f < kFormats; ++f) {
+        first[f] = all.size();
+        for (const PlannedSeg &ps : plan.segs[f])
+            all.push_back(ps.seg);
+    }
+    // the records and rows ride in kernel arguments: no copy call, nothing allocated
+    auto upload = [&](const uint32_t *words, size_t n_words, size_t dst_byte) -> kdn_status {
+        ScratchWords a;
+        for (size_t at = 0; at < n_words; at += kScratchWords) {
+            a.first = (uint32_t)(dst_byte / 4 + at);
+            a.n = (uint32_t)std::min<size_t>(kScratchWords, n_words - at);
+            std::memcpy(a.w, words + at, (size_t)a.n * 4);
+            hipLaunchKernelGGL(k_scratch_write, dim3(1), dim3(kThreads), 0, hs,
+                               reinterpret_cast<uint32_t *>(scratch), a);
+            if (hipGetLastError() != hipSuccess)
+                return KDN_EDEVICE;
+        }
+        return KDN_OK;
+    };
+    st = upload(rope_words.data(), rope_words.size(), 0);
+    if (st != KDN_OK)
+        return st;
+    st = upload(reinterpret_cast<const uint32_t *>(all.data()), all.size() * sizeof(Seg) / 4, kStaticRopeBytes);
+    if (st != KDN_OK)
+        return st;
+
+    PlaceP p;
+    p.c = make_cache_p(cache);
+    p.layer0 = 0;
+    p.rot = spec.rot;
+    p.pairing = spec.pairing;
+    p.rope = reinterpret_cast<const f32x2 *>(scratch);
+    for (int f = 0; f < kFormats; ++f) {
+        if (plan.segs[f].empty())
+            continue;
+        std::vector<Seg> segs(all.begin() + (long)first[f], all.begin() + (long)(first[f] + plan.segs[f].size()));
+        p.reuse = plan.reuse[f];
+        st = place_segments(ds, p, f, segs, hs, 0,
+                            reinterpret_cast<const Seg *>(scratch + kStaticRopeBytes) + first[f]);
+        if (st != KDN_OK)
+            return st;
+    }
+    return KDN_OK;
 }
 
 kdn_status kdn_compose_opts(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,

@@ -863,6 +863,20 @@ __global__ void k_f32_to_bf16(const float *__restrict__ in, uint16_t *__restrict
         out[n - 1] = (uint16_t)pack_bf16(in[n - 1], 0.0f);
 }
 
+// Writes up to kScratchWords 32-bit words that travel in the kernel arguments to
+// dst[first .. first + n): how small host tables reach device memory with no copy call.
+constexpr int kScratchWords = 960;
+struct ScratchWords {
+    uint32_t first, n;
+    uint32_t w[kScratchWords];
+};
+
+__global__ __launch_bounds__(kThreads) void k_scratch_write(uint32_t *dst, ScratchWords a)
+{
+    for (uint32_t i = threadIdx.x; i < a.n; i += blockDim.x)
+        dst[a.first + i] = a.w[i];
+}
+
 // flags: bit 0 = id out of range, bit 1 = id seen twice
 __global__ void k_validate(const int32_t *bt, int32_t n, int32_t num_blocks, uint32_t *seen,
                            uint32_t *flags)

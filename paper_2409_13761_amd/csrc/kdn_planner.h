@@ -61,6 +61,7 @@ struct DeviceState {
     bool seg_used[kSegSlots] = {};
     int next_slot = 0;
     LinkDir to_device, to_host; // the link is full duplex: the directions do not share a stream
+    uint8_t *static_scratch = nullptr; // this device's copy of the library's static scratch array
 };
 
 inline std::mutex g_mu; // guards g_dev and everything in it
@@ -491,8 +492,10 @@ void launch_place_d(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs
 // Enqueue the placement of `segs` (all of one format).  Up to kMaxInlineSegs travel
 // in the kernel arguments; more go through a ring of device tables.
 // max_workgroups > 0 caps the launch; the workgroups then stride over the tiles.
+// resident: the same records already in device memory (the caller put them there on `st`);
+// the kernel then reads them from there and nothing is copied or allocated here.
 inline kdn_status place_segments(DeviceState *ds, const PlaceP &p_in, int32_t fmt, const std::vector<Seg> &segs,
-                                 hipStream_t st, int32_t max_workgroups = 0)
+                                 hipStream_t st, int32_t max_workgroups = 0, const Seg *resident = nullptr)
 {
     if (segs.empty())
         return KDN_OK;
@@ -510,9 +513,9 @@ inline kdn_status place_segments(DeviceState *ds, const PlaceP &p_in, int32_t fm
         gx = std::min<uint32_t>(gx, std::max<uint32_t>(1u, (uint32_t)max_workgroups / (uint32_t)segs.size()));
     dim3 grid(gx, (unsigned)segs.size(), 1);
 
-    const Seg *segs_dev = nullptr;
+    const Seg *segs_dev = resident;
     int slot = -1;
-    if ((int)segs.size() > kMaxInlineSegs) {
+    if (!resident && (int)segs.size() > kMaxInlineSegs) {
         if (!ds->seg_dev) {
             if (hipMalloc(reinterpret_cast<void **>(&ds->seg_dev), kSegSlots * kSegSlotBytes) != hipSuccess)
                 return KDN_EDEVICE;

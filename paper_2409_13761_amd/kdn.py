@@ -110,6 +110,9 @@ def lib() -> C.CDLL:
         L.kdn_compose_batch.restype = C.c_int
         L.kdn_compose_batch.argtypes = [C.POINTER(RequestDesc), i32, C.POINTER(CacheDesc),
                                         C.c_double, vp]
+        L.kdn_compose_batch_static.restype = C.c_int
+        L.kdn_compose_batch_static.argtypes = [C.POINTER(RequestDesc), i32, C.POINTER(CacheDesc),
+                                               C.c_double, vp]
         L.kdn_compose_rope.restype = C.c_int
         L.kdn_compose_rope.argtypes = [C.POINTER(ChunkDesc), C.POINTER(i32), i32, C.POINTER(CacheDesc),
                                        vp, i32, i32, C.POINTER(RopeSpecDesc), vp]
@@ -174,7 +177,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_chunk", "kdn_store_tokens",
            "kdn_store_to_host", "kdn_store_staging_bytes", "kdn_store_chunk_opts", "kdn_compose_opts",
-           "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_rope",
+           "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_batch_static", "kdn_compose_rope",
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host", "kdn_compose_from_host_staged",
            "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec", "kdn_rope_release",
            "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
@@ -421,6 +424,15 @@ def kdn_compose_batch(plan_or_requests, cache: PagedCache, rope_base: float, str
     cd = cache.desc()
     _check(lib().kdn_compose_batch(plan.arr, plan.n, C.byref(cd), float(rope_base), _stream(stream)),
            "kdn_compose_batch")
+
+
+def kdn_compose_batch_static(plan_or_requests, cache: PagedCache, rope_base: float, stream=None) -> None:
+    """kdn_compose_batch through the entry point that allocates nothing (its tables live in
+    the library's static scratch array)."""
+    plan = plan_or_requests if isinstance(plan_or_requests, BatchPlan) else BatchPlan(plan_or_requests)
+    cd = cache.desc()
+    _check(lib().kdn_compose_batch_static(plan.arr, plan.n, C.byref(cd), float(rope_base), _stream(stream)),
+           "kdn_compose_batch_static")
 
 
 class PlacementDesc(C.Structure):

@@ -1,21 +1,22 @@
 #!/usr/bin/env python3
 """Throughput of the KDN hot path on one MI355X.
 
-Default workload ("8b"): one step carries one 4096-token context of Llama-3-8B-shaped
-KV (32 layers, 8 KV heads, head_dim 128, bf16, paged in blocks of 16 tokens) through
-the whole path:
-  store    paged KV -> stored int8 chunk              (kdn_store_chunk)
-  load     stored chunk -> a fresh block table        (kdn_load_chunk, no shift)
-  compose  the chunk as 8 slices of 512 tokens, in a seeded order, each shifted by
-           its cumulative RoPE offset, into another fresh table   (kdn_compose)
-Inputs are resident in HBM before the timed region.  Four disjoint buffer sets are
-cycled, and a step reads chunks that were stored two or three steps earlier, so that
-the 256 MB last-level cache cannot serve a repeat or a just-written chunk.
+Default workload ("70b_long", the largest of the five that is a whole pass of the path):
+one step carries one 32768-token context of Llama-3-70B-shaped KV (80 layers, 8 KV heads,
+head_dim 128, bf16, paged in blocks of 16 tokens, random block tables) through the path:
+  store    paged KV -> one stored int8 chunk (15.2 GiB moved)      (kdn_store_chunk)
+  compose  the chunk as 4 slices of 8192 tokens, shifted by RoPE offsets
+           0 / 8192 / 16384 / 24576, into a fresh table (15.2 GiB)  (kdn_compose)
+Inputs are resident in HBM before the timed region; two disjoint buffer sets alternate.
+The default run then also times, more briefly, the "8b" step (4096 tokens of Llama-3-8B
+shape: store, load at offset 0, compose of 8 shifted 512-token slices; four buffer sets
+cycled so that the 256 MB last-level cache serves no repeat) and the "batched_reuse"
+compose (64 requests x 4 chunks of 1024 tokens drawn by Zipf popularity from a resident
+pool of 256 chunks, one batched launch), and a plain streaming kernel with the same byte
+pattern as a yardstick; these ride in the same JSON line under "other_workloads" and
+"stream_ceiling" (--only leaves them out).
 
-Other workloads (--workload): "toy" (latency bound), "70b_long" (80 layers, 32768 tokens: one store, one
-compose of four 8192-token slices) and "batched_reuse" (64 requests x 4 chunks of
-1024 tokens drawn by Zipf popularity from a resident pool of 256 chunks, one batched
-compose per step).
+Other workloads (--workload): "8b", "batched_reuse", "toy" (latency bound).
 
 "pool_trace" is a serving loop over the text-keyed index (store on miss, compose on
 hit) and reports the hit rate; "pool_trace_tiered" adds a host-memory tier under it
@@ -43,25 +44,25 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 METRIC = "KV tokens composed/sec (store+load+RoPE shift) and achieved HBM GB/s"
 FMT_IDS = {"raw": 0, "int8": 1, "int4": 2, "fp8": 3}
 
-# HBM bytes per k_place launch of the default workload from the FETCH_SIZE / WRITE_SIZE
-# counter runs summarised under profiles/, valid only for the kernel source they were
-# taken with.
-COUNTER_TRAFFIC = {"source_sha256_16": "0649626727e0c693", "k_place_bytes_per_launch": 817256897}
+# HBM bytes per k_place launch from the FETCH_SIZE / WRITE_SIZE counter runs summarised
+# under profiles/ (the file named here), per workload; valid only for the library sources
+# they were taken with, whose fingerprint the library itself carries.
+COUNTER_TRAFFIC = {
+    "source_fingerprint": "",
+    "70b_long": {"k_place_bytes_per_launch": None, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
+    "8b": {"k_place_bytes_per_launch": None, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
+}
 
 
 def kernel_source_fingerprint():
-    """sha256 over the library's device and planner sources (csrc/kdn*.h, csrc/kdn.hip)."""
-    import hashlib
-    d = os.path.join(ROOT, "paper_2409_13761_amd", "csrc")
-    h = hashlib.sha256()
-    for name in ("kdn_kernels.h", "kdn_planner.h", "kdn.hip"):
-        h.update(open(os.path.join(d, name), "rb").read())
-    return h.hexdigest()[:16]
+    """The fingerprint of the library's sources and compiler flags (the one libkdn.so carries)."""
+    from paper_2409_13761_amd import build
+    return build.source_fingerprint()
 
 
-def counter_traffic():
-    same = kernel_source_fingerprint() == COUNTER_TRAFFIC["source_sha256_16"]
-    return COUNTER_TRAFFIC["k_place_bytes_per_launch"] if same else None
+def counter_traffic(workload="70b_long"):
+    same = kernel_source_fingerprint() == COUNTER_TRAFFIC["source_fingerprint"]
+    return COUNTER_TRAFFIC[workload]["k_place_bytes_per_launch"] if same else None
 
 
 def fill_normal(t, gen):
@@ -107,26 +108,90 @@ class Timed:
         return wall, ms
 
 
-def copy_ceiling(dev):
-    """A plain device copy as the box's own yardstick: 1 GiB read + 1 GiB written per
-    copy, over 3 rotating buffer pairs so that the last-level cache serves nothing."""
-    import torch
-    n = 1 << 29
-    bufs = [(torch.empty(n, dtype=torch.bfloat16, device=dev).normal_(),
-             torch.empty(n, dtype=torch.bfloat16, device=dev)) for _ in range(3)]
-    for a, b in bufs:
-        b.copy_(a)
+def _probe_rate(kdn, torch, small, big, tiles, ids, tile_kib, direction, cap, reps):
+    """GB/s of kdn_probe_stream over rotating buffer sets (HIP events on the launch stream)."""
+    sets = len(small)
+    for i in range(sets):
+        kdn.kdn_probe_stream(small[i], big[i], tiles, ids, tile_kib, direction, cap)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = 12
     e0.record()
     for i in range(reps):
-        a, b = bufs[i % 3]
-        b.copy_(a)
+        kdn.kdn_probe_stream(small[i % sets], big[i % sets], tiles, ids, tile_kib, direction, cap)
     e1.record()
     torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / reps
-    return 2.0 * n * 2 / (ms * 1e-3) / 1e9
+    return tiles * tile_kib * 1536 / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
+
+
+def stream_ceiling(dev):
+    """The box's own yardstick: the library's plain streaming kernel (kdn_probe_stream: per
+    workgroup one 32 KiB tile of the big buffer and 16 KiB of the small one, no arithmetic, no
+    table walk), 32768 tiles = 1.61 GB per launch, over 3 rotating buffer sets.  In the pattern of
+    load and compose (small -> big) with the destination tiles in order and scattered by a seeded
+    permutation, as the blocks of a random block table are; and in the pattern of store
+    (big -> small) with the source tiles scattered."""
+    import torch
+    from paper_2409_13761_amd import kdn, synth
+    tiles, sets, reps = 32768, 3, 12
+    small = [torch.empty(tiles * 16384, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(sets)]
+    big = [torch.empty(tiles * 32768, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(sets)]
+    ids = torch.from_numpy(synth.permutation(4242, tiles).astype("int32")).to(dev)
+    out = {"place_pattern_contiguous_GBps": _probe_rate(kdn, torch, small, big, tiles, None, 32, 0, 0, reps),
+           "place_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, ids, 32, 0, 0, reps),
+           "store_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, ids, 32, 1, 0, reps)}
+    out["what"] = ("kdn_probe_stream, one workgroup per tile (32 KiB of the big buffer, 16 KiB of the small one), streamed, "
+                   "no arithmetic; %d tiles (%.2f GB) per launch, %d buffer sets, HIP events. place pattern = read small, "
+                   "write big (load, compose); store pattern = read big, write small; scattered = the big buffer's tiles "
+                   "permuted like the blocks of a random table" % (tiles, tiles * 49152 / 1e9, sets))
+    return out
+
+
+def workload_stream_probe(args, dev):
+    """The streaming yardstick over tile sizes and launch widths: what a kernel with nothing to
+    compute reaches with the byte pattern of load/compose (16 KiB read, 32 KiB written per tile at the
+    Llama shapes and block size 16) when the written tiles are in order or scattered, and how that moves
+    with the tile size (the engine's block size) and with the number of workgroups in flight."""
+    import numpy as np
+    import torch
+    from paper_2409_13761_amd import kdn, synth
+    sets, reps, total_kib = 3, args.steps, 1 << 20            # 1 GiB of the big buffer per launch
+    small = [torch.empty(total_kib * 512, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(sets)]
+    big = [torch.empty(total_kib * 1024, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(sets)]
+    rows = []
+    for tile_kib in (8, 16, 32, 64, 128, 256, 1024, 4096):
+        tiles = total_kib // tile_kib
+        ids = torch.from_numpy(synth.permutation(4242 + tile_kib, tiles).astype("int32")).to(dev)
+        rows.append({"tile_KiB": tile_kib, "workgroups": tiles,
+                     "place_contiguous_GBps": _probe_rate(kdn, torch, small, big, tiles, None, tile_kib, 0, 0, reps),
+                     "place_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, ids, tile_kib, 0, 0, reps),
+                     "store_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, ids, tile_kib, 1, 0, reps)})
+    tiles = total_kib // 32
+    ids = torch.from_numpy(synth.permutation(4242 + 32, tiles).astype("int32")).to(dev)
+    caps = []
+    for cap in (256, 512, 1024, 2048, 4096, 0):
+        caps.append({"max_workgroups": cap or tiles,
+                     "place_contiguous_GBps": _probe_rate(kdn, torch, small, big, tiles, None, 32, 0, cap, reps),
+                     "place_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, ids, 32, 0, cap, reps)})
+    windows = []
+    rng = np.random.default_rng(4242)
+    for w_tiles in (1, 64, 256, 1024, 4096, tiles):      # tiles shuffled only within windows of this many tiles
+        local = np.stack([rng.permutation(r) for r in np.arange(tiles).reshape(-1, w_tiles)]).reshape(-1)
+        local_ids = torch.from_numpy(local.astype(np.int32)).to(dev)
+        windows.append({"window_MiB": w_tiles / 32,
+                        "place_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, local_ids, 32, 0, 0, reps)})
+    r32 = rows[2]
+    ms = {"place_scattered": 1.5 * (1 << 30) / r32["place_scattered_GBps"] / 1e6}
+    return {
+        "tokens_per_step": 0, "wall": ms["place_scattered"] * 1e-3 * args.steps, "ms": ms,
+        "bytes": {"place_scattered": int(1.5 * (1 << 30))},
+        "place_calls": ("place_scattered",),
+        "workload": "stream_probe: kdn_probe_stream (no arithmetic, no table walk) moving 0.5 GiB of a small buffer and 1 GiB "
+                    "of a big one per launch, by tile size and by launch width; the headline fields are the 32 KiB-tile, "
+                    "scattered, place-pattern row (no tokens are moved: value is 0)",
+        "extra": {"by_tile_size": rows, "by_launch_width_at_32KiB_tiles": caps,
+                  "by_scatter_window_at_32KiB_tiles": windows},
+        "traffic": None,
+    }
 
 
 def workload_8b(args, dev):
@@ -195,7 +260,7 @@ def workload_8b(args, dev):
                     "RoPE offsets 0..3584 (base %g); %d buffer sets cycled; cache layout %s, pool of %d blocks; %s block tables"
                     % (args.fmt, w.rope_base, n_sets, args.layout, nb,
                        "random disjoint" if args.tables == "random" else "consecutive-block"),
-        "traffic": counter_traffic() if args.fmt == "int8" and args.tables == "random" and args.layout == "planes"
+        "traffic": counter_traffic("8b") if args.fmt == "int8" and args.tables == "random" and args.layout == "planes"
         and not args.pool_blocks else None,
     }
     if not args.no_cpu_baseline and args.fmt == "int8":
@@ -288,14 +353,18 @@ def workload_70b(args, dev):
 
     wall, ms = Timed(("store", "compose"), args.steps).run(step, args.warmup)
     bytes_call = T * (sh.paged_bytes_per_token + sh.stored_bytes_per_token(args.fmt))
-    return {
+    res = {
         "tokens_per_step": T, "wall": wall, "ms": ms, "bytes": {n: bytes_call for n in ms},
         "place_calls": ("compose",),
-        "workload": "Llama-3-70B-shaped KV (L80 H8 D128 bs16): per step store 32768 tokens to %s and "
-                    "compose them back as 4x8192-token slices with RoPE offsets 0/8192/16384/24576; "
-                    "%d buffer sets cycled" % (args.fmt, n_sets),
-        "traffic": None,
+        "workload": "70b_long: Llama-3-70B-shaped KV (L80 H8 D128 bs16), per step store 32768 tokens to %s (one call) "
+                    "and compose them back as 4x8192-token slices with RoPE offsets 0/8192/16384/24576 (base %g) "
+                    "into a fresh table; random disjoint block tables in a pool of %d blocks; %d buffer sets cycled"
+                    % (args.fmt, w.rope_base, nb, n_sets),
+        "traffic": counter_traffic("70b_long") if args.fmt == "int8" else None,
     }
+    if not args.no_cpu_baseline and args.fmt == "int8":
+        res["cpu_baseline"] = cpu_baseline_70b(kdn, cache, sets[0], offsets, w.rope_base, T, args.cpu_layers)
+    return res
 
 
 def workload_batched(args, dev):
@@ -342,16 +411,21 @@ def workload_batched(args, dev):
     wall, ms = Timed(("compose_batch",), args.steps).run(step, args.warmup)
     tokens = n_req * per_req * Tc
     unique = int(len(np.unique(draws)))
+    # HBM bytes: every destination row written once, every DISTINCT chunk read once (a chunk that
+    # several requests draw is served from the caches after its first reader)
+    once = unique * Tc * sh.int8_bytes_per_token + tokens * sh.paged_bytes_per_token
+    naive = tokens * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)
     return {
         "tokens_per_step": tokens, "wall": wall, "ms": ms,
-        "bytes": {"compose_batch": tokens * (sh.paged_bytes_per_token + sh.int8_bytes_per_token)},
+        "bytes": {"compose_batch": once},
         "place_calls": ("compose_batch",),
-        "workload": "batched reuse (L32 H8 D128 bs16): 64 requests x 4 chunks of 1024 tokens drawn by "
+        "workload": "batched_reuse (L32 H8 D128 bs16): 64 requests x 4 chunks of 1024 tokens drawn by "
                     "Zipf(1.0) from a resident pool of 256 int8 chunks (%d distinct drawn), one batched "
                     "compose per step into 64 disjoint random tables" % unique,
         "extra": {"distinct_chunks": unique,
-                  "bytes_if_each_distinct_chunk_read_once":
-                      unique * Tc * sh.int8_bytes_per_token + tokens * sh.paged_bytes_per_token},
+                  "bytes_counted": "each distinct chunk read once + every destination row written",
+                  "bytes_if_every_draw_were_read_from_hbm": naive,
+                  "GBps_if_every_draw_were_read_from_hbm": naive / (ms["compose_batch"] * 1e-3) / 1e9},
         "traffic": None,
     }
 
@@ -770,89 +844,91 @@ def cpu_baseline(kdn, cache, buf_set, order, offsets, base, T, n_slices, steps):
             "parity_of_one_gpu_pass": parity}
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None)
-    ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", choices=("8b", "toy", "70b_long", "batched_reuse", "host_stream_int8",
-                             "host_stream_raw", "pool_trace", "pool_trace_tiered", "sweep"),
-                    default="8b")
-    ap.add_argument("--fmt", choices=("int8", "int4", "fp8", "raw"), default="int8",
-                    help="stored form used by the 8b and 70b_long workloads")
-    ap.add_argument("--layout", choices=("planes", "kv_pair", "block_major"), default="planes",
-                    help="paged cache layout of the 8b workload, all expressed through the "
-                         "descriptor's strides: separate K and V tensors [L][blocks][bs][H][D] "
-                         "(default), K and V of a block adjoining, or all layers of a block adjoining")
-    ap.add_argument("--tables", choices=("random", "consecutive"), default="random",
-                    help="block tables of the 8b workload: sampled without replacement from the pool "
-                         "(default, the stated workload) or runs of consecutive blocks")
-    ap.add_argument("--pool-blocks", type=int, default=0,
-                    help="blocks in the paged pool of the 8b workload (default 3072, the 12 tables of 256 blocks "
-                         "it uses); the distance between a block's tiles in neighbouring planes follows from it")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-steps", type=int, default=8)
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy, a dispatch of known size for "
-                         "scaling hardware byte counters")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this library runs on one GPU only; the path shards without any exchange "
-              "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
-        return 2
-    from paper_2409_13761_amd import build as lib_build
-    lib_build.ensure_built()
-    defaults = {"8b": (40, 8), "toy": (200, 20), "70b_long": (10, 3), "batched_reuse": (10, 3),
-                "host_stream_int8": (10, 3), "host_stream_raw": (10, 3), "pool_trace": (400, 100), "pool_trace_tiered": (400, 100), "sweep": (8, 0)}[args.workload]
-    args.steps = defaults[0] if args.steps is None else args.steps
-    args.warmup = defaults[1] if args.warmup is None else args.warmup
-
+def cpu_baseline_70b(kdn, cache, buf_set, offsets, base, T, n_layers):
+    """The oracle as it stands on the host cores, on a bounded sample of the same step: store
+    and compose of all 32768 tokens for n_layers of the 80 layers (evenly spaced), one layer
+    per task over the host threads; and, untimed, one coherent GPU pass (store -> compose of
+    this buffer set) compared with what the oracle computed for those layers from the same
+    source blocks."""
+    import numpy as np
     import torch
-    from paper_2409_13761_amd import kdn
+    from oracle import kdn_oracle as O
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU", file=sys.stderr)
-        return 3
-    kdn.lib()                                   # fail loudly if the HIP library is not built
-    torch.cuda.set_device(0)
-    dev = torch.device("cuda:0")
+    L, nb, bs, H, D = cache.shape
+    src, dst, gpu_chunk, gpu_slices = buf_set
+    blocks = T // bs
+    layers = [int(x) for x in np.linspace(0, L - 1, n_layers).round()]
+    Ls = len(layers)
+    hk = np.zeros((Ls, 2 * blocks, bs, H, D), dtype=np.uint16)      # source blocks, then zeroed destination blocks
+    hv = np.zeros_like(hk)
+    for i, l in enumerate(layers):
+        hk[i, :blocks] = cache.k[l, src.long()].view(torch.int16).cpu().numpy().view(np.uint16)
+        hv[i, :blocks] = cache.v[l, src.long()].view(torch.int16).cpu().numpy().view(np.uint16)
+    host = O.PagedCache(hk, hv)
+    t_src = np.arange(0, blocks, dtype=np.int32)
+    t_dst = np.arange(blocks, 2 * blocks, dtype=np.int32)
+    chunk = O.Chunk(np.zeros(O.chunk_bytes(Ls, H, D, T, O.FMT_INT8_ROWSCALE), dtype=np.uint8),
+                    O.FMT_INT8_ROWSCALE, Ls, H, D, T)
+    slices = [chunk.slice(i * (T // 4), T // 4) for i in range(4)]
+    cores = max(1, min(len(os.sched_getaffinity(0)), 16, Ls))
 
-    res = {"8b": workload_8b, "toy": workload_toy, "70b_long": workload_70b, "batched_reuse": workload_batched,
-           "host_stream_int8": lambda a, d: workload_host_stream(a, d, "int8"),
-           "host_stream_raw": lambda a, d: workload_host_stream(a, d, "raw"),
-           "pool_trace": workload_pool_trace, "pool_trace_tiered": workload_pool_trace_tiered, "sweep": workload_sweep}[args.workload](args, dev)
+    def work(i):
+        O.store(host, t_src, 0, T, O.FMT_INT8_ROWSCALE, layers=(i, i + 1), out=chunk)
+        O.compose(slices, offsets, host, t_dst, base, layers=(i, i + 1))
 
-    if args.calibration_copy:
-        a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
-        b = torch.empty_like(a)
-        torch.cuda.synchronize()
-        b.copy_(a)                              # 1 GiB read, 1 GiB written
-        torch.cuda.synchronize()
-        del a, b
+    from concurrent.futures import ThreadPoolExecutor
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(cores) as ex:
+        list(ex.map(work, range(Ls)))
+    dt = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    work(0)                                                          # one layer again, alone on one thread
+    dt1 = time.perf_counter() - t0
 
+    kdn.kdn_store_chunk(cache, src, 0, T, gpu_chunk)
+    kdn.kdn_compose(gpu_slices, offsets, cache, dst, base)
+    torch.cuda.synchronize()
+
+    def bits(t):
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+    def f64(b):
+        return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+    gc, gs = gpu_chunk.codes(), gpu_chunk.scales()
+    parity = {"layers_compared": layers, "stored_chunk_equal": True, "compose_v_equal": True,
+              "compose_k_differing_elements": 0, "compose_k_max_abs_diff": 0.0}
+    for i, l in enumerate(layers):
+        parity["stored_chunk_equal"] &= bool(np.array_equal(gc[l].cpu().numpy(), chunk.codes()[i])
+                                             and np.array_equal(gs[l].cpu().numpy(), chunk.scales()[i]))
+        gk, gv = bits(cache.k[l, dst.long()]), bits(cache.v[l, dst.long()])
+        parity["compose_v_equal"] &= bool(np.array_equal(gv, hv[i, blocks:]))
+        want_k = hk[i, blocks:]
+        parity["compose_k_differing_elements"] += int(np.count_nonzero(gk != want_k))
+        parity["compose_k_max_abs_diff"] = max(parity["compose_k_max_abs_diff"],
+                                               float(np.max(np.abs(f64(gk) - f64(want_k)))))
+    return {"value": T / (dt * L / Ls), "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "store + compose of all %d tokens for %d of the %d layers (layers %s), one layer per task on "
+                      "%d threads, %.2f s; value = tokens / (that time x %d/%d), i.e. the whole step at this rate"
+                      % (T, Ls, L, layers, cores, dt, L, Ls),
+            "seconds": dt, "single_thread_value": T / (dt1 * L),
+            "parity_of_one_gpu_pass": parity}
+
+
+def summarise(res, steps, warmup, fmt_note):
+    """The JSON fields of one workload's result."""
     ms, nbytes = res["ms"], res["bytes"]
     gbps = {n: nbytes[n] / (ms[n] * 1e-3) / 1e9 for n in ms}
     place = res["place_calls"]
     place_ms = sum(ms[n] for n in place) / len(place)
     achieved = nbytes[place[0]] / (place_ms * 1e-3) / 1e9
     out = {
-        "metric": METRIC,
-        "value": res["tokens_per_step"] * args.steps / res["wall"],
+        "value": res["tokens_per_step"] * steps / res["wall"],
         "unit": "tokens/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": res["wall"] / args.steps * 1e3,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16 KV, %s stored form, fp32 arithmetic" % (
-            "int8 codes + fp32 row scales" if args.fmt == "int8" or args.workload == "batched_reuse"
-            or args.workload == "host_stream_int8" else
-            "int4 codes + fp32 group scales" if args.fmt == "int4" else
-            "fp8 e4m3 codes + fp32 row scales" if args.fmt == "fp8" else "raw bf16"),
-        "data": "synthetic N(0,1) bf16 KV, seeded; %s block tables"
-                % ("consecutive-block" if args.workload == "8b" and args.tables == "consecutive" else "random disjoint"),
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": res["wall"] / steps * 1e3,
+        "dtype": fmt_note,
         "config": {
             "workload": res["workload"],
             "tokens_per_step": res["tokens_per_step"],
@@ -870,16 +946,137 @@ def main() -> int:
             "traffic": res["traffic"],
         },
     }
-    if args.workload == "8b":
-        ceiling = copy_ceiling(dev)
-        out["device_copy_ceiling"] = {
-            "GBps": ceiling, "what": "torch copy of 1 GiB bf16 buffers (1 GiB read + 1 GiB written), "
-                                     "3 rotating pairs, HIP events",
-            "frac_of_ceiling": {n: gbps[n] / ceiling for n in ms}}
     if "extra" in res:
         out["config"].update(res["extra"])
     if "cpu_baseline" in res:
         out["cpu_baseline"] = res["cpu_baseline"]
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", choices=("70b_long", "8b", "toy", "batched_reuse", "host_stream_int8",
+                             "host_stream_raw", "pool_trace", "pool_trace_tiered", "sweep", "stream_probe"),
+                    default="70b_long")
+    ap.add_argument("--only", action="store_true",
+                    help="the named workload alone: the default run's shorter 8b and batched_reuse passes and the "
+                         "streaming yardstick are left out (for profiling)")
+    ap.add_argument("--fmt", choices=("int8", "int4", "fp8", "raw"), default="int8",
+                    help="stored form used by the 8b and 70b_long workloads")
+    ap.add_argument("--layout", choices=("planes", "kv_pair", "block_major"), default="planes",
+                    help="paged cache layout of the 8b workload, all expressed through the "
+                         "descriptor's strides: separate K and V tensors [L][blocks][bs][H][D] "
+                         "(default), K and V of a block adjoining, or all layers of a block adjoining")
+    ap.add_argument("--tables", choices=("random", "consecutive"), default="random",
+                    help="block tables of the 8b workload: sampled without replacement from the pool "
+                         "(default, the stated workload) or runs of consecutive blocks")
+    ap.add_argument("--pool-blocks", type=int, default=0,
+                    help="blocks in the paged pool of the 8b workload (default 3072, the 12 tables of 256 blocks "
+                         "it uses); the distance between a block's tiles in neighbouring planes follows from it")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-steps", type=int, default=8, help="oracle steps of the 8b workload's CPU baseline")
+    ap.add_argument("--cpu-layers", type=int, default=20,
+                    help="layers (of 80) the 70b_long workload's CPU baseline runs the oracle on")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy, a dispatch of known size for "
+                         "scaling hardware byte counters")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this library runs on one GPU only; the path shards without any exchange "
+              "(by KV head, layer or request), so --gpus N > 1 is not measured", file=sys.stderr)
+        return 2
+    from paper_2409_13761_amd import build as lib_build
+    lib_build.ensure_built()
+    defaults_of = {"8b": (40, 8), "toy": (200, 20), "70b_long": (12, 3), "batched_reuse": (10, 3),
+                   "host_stream_int8": (10, 3), "host_stream_raw": (10, 3), "pool_trace": (400, 100),
+                   "pool_trace_tiered": (400, 100), "sweep": (8, 0), "stream_probe": (12, 0)}
+    defaults = defaults_of[args.workload]
+    args.steps = defaults[0] if args.steps is None else args.steps
+    args.warmup = defaults[1] if args.warmup is None else args.warmup
+
+    import torch
+    from paper_2409_13761_amd import kdn
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        return 3
+    kdn.lib()                                   # fail loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    runners = {"8b": workload_8b, "toy": workload_toy, "70b_long": workload_70b, "batched_reuse": workload_batched,
+               "host_stream_int8": lambda a, d: workload_host_stream(a, d, "int8"),
+               "host_stream_raw": lambda a, d: workload_host_stream(a, d, "raw"),
+               "pool_trace": workload_pool_trace, "pool_trace_tiered": workload_pool_trace_tiered,
+               "sweep": workload_sweep, "stream_probe": workload_stream_probe}
+
+    def fmt_note(workload):
+        f = ("int8" if workload in ("batched_reuse", "host_stream_int8", "pool_trace", "pool_trace_tiered")
+             else "raw" if workload == "host_stream_raw" else args.fmt)
+        return "bf16 KV, %s stored form, fp32 arithmetic" % {
+            "int8": "int8 codes + fp32 row scales", "int4": "int4 codes + fp32 group scales",
+            "fp8": "fp8 e4m3 codes + fp32 row scales", "raw": "raw bf16"}[f]
+
+    res = runners[args.workload](args, dev)
+
+    if args.calibration_copy:
+        a = torch.empty(1 << 29, dtype=torch.bfloat16, device=dev).normal_()
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                              # 1 GiB read, 1 GiB written
+        torch.cuda.synchronize()
+        del a, b
+
+    body = summarise(res, args.steps, args.warmup, fmt_note(args.workload))
+    out = {
+        "metric": METRIC,
+        "value": body.pop("value"),
+        "unit": body.pop("unit"),
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": body.pop("ms_per_step"),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": body.pop("dtype"),
+        "data": "synthetic N(0,1) bf16 KV, seeded; %s block tables"
+                % ("consecutive-block" if args.workload == "8b" and args.tables == "consecutive" else "random disjoint"),
+    }
+    body.pop("steps")
+    body.pop("warmup")
+    out.update(body)
+    out["library"] = kdn.kdn_version()
+    if out["roofline"]["traffic"] is not None:
+        out["roofline"]["traffic_from"] = COUNTER_TRAFFIC[args.workload]["profile"]
+    del res
+    torch.cuda.empty_cache()
+
+    if args.workload in ("70b_long", "8b") and not args.only:
+        ceiling = stream_ceiling(dev)
+        torch.cuda.empty_cache()
+        # load and compose write through random block tables and store reads through one, so the
+        # scattered figures are their yardsticks
+        ceiling["frac_of_ceiling"] = {
+            n: v["GBps"] / ceiling["store_pattern_scattered_GBps" if n == "store" else "place_pattern_scattered_GBps"]
+            for n, v in out["breakdown"].items()}
+        ceiling["k_place_frac_of_contiguous_ceiling"] = out["roofline"]["achieved"] / ceiling["place_pattern_contiguous_GBps"]
+        out["stream_ceiling"] = ceiling
+    if args.workload == "70b_long" and not args.only:
+        import copy
+        others = {}
+        for name in ("8b", "batched_reuse"):
+            a2 = copy.copy(args)
+            a2.workload, a2.no_cpu_baseline = name, True
+            a2.steps, a2.warmup = defaults_of[name]
+            r2 = runners[name](a2, dev)
+            others[name] = summarise(r2, a2.steps, a2.warmup, fmt_note(name))
+            del r2
+            torch.cuda.empty_cache()
+        out["other_workloads"] = others
     print(json.dumps(out))
     return 0
 

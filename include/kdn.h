@@ -4,15 +4,15 @@
  * The library moves precomputed KV caches between an inference engine's paged
  * KV memory and a compact stored form, the data-parallel core of the paper's
  * Knowledge Delivery Network:
- *   - kdn_store_chunk   : the engine "stores the KV cache" (Sec. 3.2, interface (i));
+ *   - kdn_store_chunk   : the engine hands a KV cache to the KDN (Sec. 3.2, interface (i));
  *                         the stored form is the compressed KV of the delivery
  *                         module (Sec. 3.1).
- *   - kdn_load_chunk    : the engine "retrieves the KV cache" (Sec. 3.2, interface
- *                         (ii)); the KV is decompressed on the GPU (Sec. 3.1).
+ *   - kdn_load_chunk    : the engine gets a KV cache back (Sec. 3.2, interface (ii));
+ *                         it is decompressed on the GPU (Sec. 3.1).
  *   - kdn_compose[_batch]: the blending module puts several independently
  *                         precomputed KV caches together in one context (Sec. 3.1),
- *                         at positions other than the prefix (Sec. 3, limitation
- *                         "prefix-only reusing"; Sec. 3.2 "KV-cache blending").
+ *                         at positions other than the prefix (Sec. 3, the limitation
+ *                         on prefix-only reuse; Sec. 3.2, KV-cache blending).
  * The paper defines no data format or arithmetic; the formats and rules below
  * are this library's definitions.
  *
@@ -421,6 +421,19 @@ kdn_status kdn_rope_release(void);
  * block_table_dev [device] is outside [0, num_blocks) or occurs twice. */
 kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t table_len,
                                     int32_t num_blocks, void *stream);
+
+/* A measuring aid, not a step of the path: moves bytes in the patterns of this library with no
+ * arithmetic and no table walk, as the yardstick its kernels are held against.  A tile is
+ * tile_kib KiB of big_dev and tile_kib/2 KiB of small_dev (tile_kib a multiple of 8, at most
+ * 4096; 32 is the tile of the Llama shapes at block size 16).  direction 0, the pattern of load
+ * and compose: a workgroup reads tile i of small_dev and writes tile i of big_dev, or, with
+ * tile_ids_dev [device, `tiles` distinct int32], tile tile_ids_dev[i] (destination tiles
+ * scattered like the blocks of a random block table).  direction 1, the pattern of store: reads
+ * that tile of big_dev, writes tile i of small_dev.  max_workgroups > 0 caps the launch (the
+ * workgroups then stride over the tiles).  small_dev: [device] tiles * tile_kib/2 KiB; big_dev:
+ * [device], holds every tile that is named.  Ids are not checked. */
+kdn_status kdn_probe_stream(void *small_dev, void *big_dev, const int32_t *tile_ids_dev, uint32_t tiles,
+                            int32_t tile_kib, int32_t direction, int32_t max_workgroups, void *stream);
 
 /* fp32 -> bf16, round to nearest even, n elements, in_dev/out_dev [device], the
  * conversion every load and compose ends with. */

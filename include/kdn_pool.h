@@ -1,10 +1,9 @@
 /*
  * kdn_pool.h -- the text-keyed index of stored KV chunks.
  *
- * The paper's storage module "stores the KV caches keyed by various texts" (Sec. 3.1),
- * and the engine-facing interface stores a KV cache "with the associated text" and
- * retrieves it "using some text" (Sec. 3.2, interface (i) and (ii)).  This is that
- * index: a host-side map from a token-id sequence to the descriptor of a stored chunk,
+ * The paper's storage module keeps KV caches under the texts they belong to (Sec. 3.1),
+ * and the engine-facing interface names a KV cache by its text both when it hands one in
+ * and when it asks for one (Sec. 3.2, interface (i) and (ii)).  This is that index: a host-side map from a token-id sequence to the descriptor of a stored chunk,
  * bounded by a byte capacity, with recency- or frequency-based eviction (the paper
  * argues that a small part of the knowledge serves most requests, Sec. 2.2).
  *

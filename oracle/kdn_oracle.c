@@ -268,7 +268,8 @@ void kdno_dequantise_row_fp8(const uint8_t *q, float scale, int32_t D, float *y)
 }
 
 /* ---- RoPE shift -------------------------------------------------------------
- * READING (reuse of a chunk "at different positions", Sec. 3.2 blending): keys
+ * READING (a chunk reused at a position other than the one it was computed at,
+ * Sec. 3.2 blending): keys
  * carry rotary position embedding; moving a chunk by d positions multiplies
  * each pair (j, j + D/2) by the rotation of angle d * theta_j,
  * theta_j = base^(-2j/D).  theta, the angle, cos and sin are evaluated in
@@ -285,8 +286,8 @@ void kdno_rope_table(double base, int32_t D, int32_t d, float *cs)
 }
 
 /* ---- RoPE variants ------------------------------------------------------------
- * READING (what real models need before a chunk can be reused "at different
- * positions", Sec. 3.2 blending): only the first rot_dim elements of a row may be
+ * READING (what real models need before a chunk can be reused at another
+ * position, Sec. 3.2 blending): only the first rot_dim elements of a row may be
  * rotary (partial rotary; rot_dim == D is the plain case), pairs may be half-split
  * (j, j + rot_dim/2) or interleaved (2j, 2j + 1), and the rot_dim/2 frequencies may
  * be given explicitly (for rescaled-frequency models) instead of base^(-2j/rot_dim).
@@ -474,7 +475,7 @@ static int place(const void *data, int32_t fmt, int32_t Tp, int32_t tok_start,
     return 0;
 }
 
-/* ---- load (the "retrieve" API, Sec. 3.2; "decompresses them in GPU", Sec. 3.1)
+/* ---- load (the retrieve API, Sec. 3.2; decompression on the GPU, Sec. 3.1)
  * Dequantise and scatter a chunk view into the request's blocks; never rotates. */
 int kdno_load(const void *data, int32_t fmt, int32_t Tp, int32_t tok_start,
               int32_t T, const kdno_cache *c, const int32_t *bt,

@@ -817,6 +817,31 @@ kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t tabl
     return flags ? KDN_ERANGE : KDN_OK;
 }
 
+kdn_status kdn_probe_stream(void *small_dev, void *big_dev, const int32_t *tile_ids_dev, uint32_t tiles,
+                            int32_t tile_kib, int32_t direction, int32_t max_workgroups, void *stream)
+{
+    if (!small_dev || !big_dev || tiles == 0 || max_workgroups < 0 || (direction != 0 && direction != 1))
+        return KDN_EINVAL;
+    if (tile_kib < 8 || tile_kib > 4096 || tile_kib % 8 != 0)
+        return KDN_EINVAL;
+    if (!aligned16(small_dev) || !aligned16(big_dev))
+        return KDN_EALIGN;
+    const uint32_t chunks = (uint32_t)tile_kib / 8;
+    const uint32_t grid = max_workgroups > 0 ? std::min<uint32_t>(tiles, (uint32_t)max_workgroups) : tiles;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    u32x4 *sm = static_cast<u32x4 *>(small_dev), *bg = static_cast<u32x4 *>(big_dev);
+    const dim3 g(grid), b(kThreads);
+    if (direction == 0 && chunks % 4 == 0)
+        hipLaunchKernelGGL((k_probe_stream<0, true>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
+    else if (direction == 0)
+        hipLaunchKernelGGL((k_probe_stream<0, false>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
+    else if (chunks % 4 == 0)
+        hipLaunchKernelGGL((k_probe_stream<1, true>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
+    else
+        hipLaunchKernelGGL((k_probe_stream<1, false>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
+    return hip_status(hipGetLastError());
+}
+
 kdn_status kdn_f32_to_bf16(const float *in_dev, uint16_t *out_dev, uint64_t n, void *stream)
 {
     if (!in_dev || !out_dev)

@@ -863,6 +863,52 @@ __global__ void k_f32_to_bf16(const float *__restrict__ in, uint16_t *__restrict
         out[n - 1] = (uint16_t)pack_bf16(in[n - 1], 0.0f);
 }
 
+// Bandwidth yardstick with the byte patterns of this library and none of its work.  A tile is
+// `chunks` * 8 KiB of the big buffer and half that of the small one.  DIR 0 (the pattern of load
+// and compose): a workgroup reads tile t of `small` (contiguous, in order) and writes tile
+// ids[t] of `big` (tile t when ids is null): with ids, destination tiles scattered like the
+// blocks of a random block table.  DIR 1 (the pattern of store): reads tile ids[t] of `big`,
+// writes tile t of `small`.  16 bytes per lane and instruction, up to four 4 KiB loads of a
+// thread issued before its first store, everything streamed; fewer workgroups than tiles
+// stride over them.
+template <int DIR, bool FULL> // FULL: chunks is a multiple of 4, so no load or store is predicated
+__global__ __launch_bounds__(kThreads) void k_probe_stream(u32x4 *__restrict__ small, u32x4 *__restrict__ big,
+                                                          const int32_t *__restrict__ ids, uint32_t tiles,
+                                                          uint32_t chunks)
+{
+    for (uint32_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+        u32x4 *s = small + (size_t)t * chunks * kThreads;
+        u32x4 *b = big + (size_t)(ids ? (uint32_t)ids[t] : t) * chunks * (2 * kThreads);
+        for (uint32_t c0 = 0; c0 < chunks; c0 += 4) {
+            u32x4 v[4], w[4];
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                if (FULL || c0 + u < chunks) {
+                    if (DIR == 0) {
+                        v[u] = __builtin_nontemporal_load(s + (c0 + u) * kThreads + threadIdx.x);
+                    } else {
+                        v[u] = __builtin_nontemporal_load(b + (2 * (c0 + u)) * kThreads + threadIdx.x);
+                        w[u] = __builtin_nontemporal_load(b + (2 * (c0 + u) + 1) * kThreads + threadIdx.x);
+                    }
+                }
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < 4; ++u) {
+                if (FULL || c0 + u < chunks) {
+                    if (DIR == 0) {
+                        u32x4 x = v[u];
+                        x.x ^= 0x80008000u; // the second vector differs from the first, as an upper half row would
+                        __builtin_nontemporal_store(v[u], b + (2 * (c0 + u)) * kThreads + threadIdx.x);
+                        __builtin_nontemporal_store(x, b + (2 * (c0 + u) + 1) * kThreads + threadIdx.x);
+                    } else {
+                        __builtin_nontemporal_store(v[u] ^ w[u], s + (c0 + u) * kThreads + threadIdx.x);
+                    }
+                }
+            }
+        }
+    }
+}
+
 // Writes up to kScratchWords 32-bit words that travel in the kernel arguments to
 // dst[first .. first + n): how small host tables reach device memory with no copy call.
 constexpr int kScratchWords = 960;

@@ -1,6 +1,5 @@
-// Text-keyed index of stored KV chunks (include/kdn_pool.h): the storage module's
-// "KV caches keyed by various texts" (Sec. 3.1) behind the store / retrieve interface
-// (Sec. 3.2).  Host code only: a hash map from token-id sequences to chunk descriptors,
+// Text-keyed index of stored KV chunks (include/kdn_pool.h): the storage module's map
+// from a text to its KV cache (Sec. 3.1) behind the store / retrieve interface (Sec. 3.2).  Host code only: a hash map from token-id sequences to chunk descriptors,
 // a recency list, use counters, and eviction to a byte capacity.
 #include <cstdint>
 #include <cstring>

@@ -158,6 +158,8 @@ def lib() -> C.CDLL:
         L.kdn_rope_release.argtypes = []
         L.kdn_validate_block_table.restype = C.c_int
         L.kdn_validate_block_table.argtypes = [vp, i32, i32, vp]
+        L.kdn_probe_stream.restype = C.c_int
+        L.kdn_probe_stream.argtypes = [vp, vp, vp, C.c_uint32, i32, i32, i32, vp]
         L.kdn_f32_to_bf16.restype = C.c_int
         L.kdn_f32_to_bf16.argtypes = [vp, vp, u64, vp]
         L.kdn_shutdown.restype = C.c_int
@@ -180,7 +182,7 @@ EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_ch
            "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_batch_static", "kdn_compose_rope",
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host", "kdn_compose_from_host_staged",
            "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec", "kdn_rope_release",
-           "kdn_validate_block_table", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
+           "kdn_validate_block_table", "kdn_probe_stream", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version", "kdn_pool_create", "kdn_pool_destroy", "kdn_pool_hash", "kdn_pool_lookup",
            "kdn_pool_insert", "kdn_pool_remove", "kdn_pool_get_stats"]
 
@@ -573,6 +575,22 @@ def kdn_validate_block_table(block_table: torch.Tensor, num_blocks: int, stream=
     """Returns the status (OK or ERANGE) instead of raising."""
     return int(lib().kdn_validate_block_table(block_table.data_ptr(), block_table.numel(),
                                               num_blocks, _stream(stream)))
+
+
+def kdn_probe_stream(small: torch.Tensor, big: torch.Tensor, tiles: int, tile_ids: torch.Tensor | None = None,
+                     tile_kib: int = 32, direction: int = 0, max_workgroups: int = 0, stream=None) -> None:
+    """The streaming yardstick: per tile, tile_kib/2 KiB of `small` and tile_kib KiB of `big`
+    (tile i of `small` with tile tile_ids[i] of `big` when ids are given; the ids are the caller's
+    to keep inside `big`: nothing here reads them back, a call only enqueues).  direction 0 reads
+    `small` and writes `big` (load, compose), direction 1 the reverse (store)."""
+    assert small.is_cuda and big.is_cuda and small.is_contiguous() and big.is_contiguous()
+    assert small.numel() * small.element_size() >= tiles * tile_kib * 512
+    if tile_ids is None:
+        assert big.numel() * big.element_size() >= tiles * tile_kib * 1024
+    else:
+        assert tile_ids.dtype == torch.int32 and tile_ids.is_cuda and tile_ids.numel() >= tiles
+    _check(lib().kdn_probe_stream(small.data_ptr(), big.data_ptr(), tile_ids.data_ptr() if tile_ids is not None else None,
+                                  tiles, tile_kib, direction, max_workgroups, _stream(stream)), "kdn_probe_stream")
 
 
 def kdn_f32_to_bf16(x: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:

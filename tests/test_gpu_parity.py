@@ -968,3 +968,41 @@ def lib_store_to_host_with_device_chunk(dc, a, fmt, staging, layers_per_stage):
                                      staging.data_ptr(), staging.numel(), layers_per_stage, None)
     if st != kdn.OK:
         raise kdn.KdnError(st, "kdn_store_to_host")
+
+
+# ------------------------------------------------------------------ the streaming yardstick
+@pytest.mark.parametrize("tile_kib,cap", [(8, 0), (32, 0), (32, 5), (72, 3), (256, 0)])
+def test_probe_stream_moves_the_bytes_it_is_timed_for(tile_kib, cap):
+    """The yardstick kernel is only worth timing if it moves what it says: every tile of the
+    small buffer lands in the tile of the big one that the id names (each 4 KiB run twice, the
+    second copy with one bit pattern flipped per 16 bytes), nothing else is written, and the
+    reverse direction folds the two copies back."""
+    tiles = 37
+    rng = np.random.default_rng(500 + tile_kib)
+    ids_h = rng.permutation(64)[:tiles].astype(np.int32)
+    small_h = rng.integers(0, 256, size=tiles * tile_kib * 512, dtype=np.uint8)
+    small = torch.from_numpy(small_h).cuda()
+    big = torch.full((64 * tile_kib * 1024,), 0xA5, dtype=torch.uint8, device="cuda")
+    ids = torch.from_numpy(ids_h).cuda()
+    kdn.kdn_probe_stream(small, big, tiles, ids, tile_kib, 0, cap)
+    torch.cuda.synchronize()
+    got = big.cpu().numpy().reshape(64, tile_kib // 8, 2, 4096)
+    src = small_h.reshape(tiles, tile_kib // 8, 4096)
+    flipped = src.copy().view(np.uint32).reshape(tiles, tile_kib // 8, 256, 4)
+    flipped[..., 0] ^= np.uint32(0x80008000)
+    flipped = flipped.view(np.uint8).reshape(tiles, tile_kib // 8, 4096)
+    assert np.array_equal(got[ids_h, :, 0], src) and np.array_equal(got[ids_h, :, 1], flipped)
+    untouched = np.setdiff1d(np.arange(64), ids_h)
+    assert np.all(got[untouched] == 0xA5)
+    back = torch.zeros_like(small)
+    kdn.kdn_probe_stream(back, big, tiles, ids, tile_kib, 1, cap)
+    torch.cuda.synchronize()
+    assert np.array_equal(back.cpu().numpy().reshape(src.shape), src ^ flipped)
+    # without ids tile i goes to tile i
+    big.fill_(0)
+    kdn.kdn_probe_stream(small, big, tiles, None, tile_kib, 0, cap)
+    torch.cuda.synchronize()
+    assert np.array_equal(big.cpu().numpy().reshape(64, tile_kib // 8, 2, 4096)[:tiles, :, 0], src)
+    with pytest.raises(kdn.KdnError) as e:
+        kdn.kdn_probe_stream(small, big, tiles, ids, 4, 0, 0)      # below the smallest tile
+    assert e.value.status == kdn.EINVAL

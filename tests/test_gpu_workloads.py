@@ -1,11 +1,15 @@
 """GPU parity on the five workloads at their full sizes.
 
-Workloads 1-3 are compared element by element with the oracle.  Workloads 4 and 5
-are too large for that: there the oracle recomputes sampled layers / requests in
-full (from the same seeded inputs, never from anything the HIP path wrote), and
-properties that hold at any size are checked over everything with plain torch ops.
+All five are compared element by element with the oracle.  Workloads 4 and 5 do not
+fit a host copy, so there the comparison is streamed: one layer (workload 4) or one
+layer of every request (workload 5) at a time on 16 host threads, the oracle
+recomputing everything from the same seeded inputs, never from anything the HIP path
+wrote.  Properties that hold at any size are checked over everything with plain torch
+ops as well.
 """
 import threading
+import time
+from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 import pytest
@@ -187,25 +191,45 @@ def test_llama70b_long_context_store_once_compose_four_slices(value_pool):
                 n0 = torch.hypot(deq[8192:, :, :64], deq[8192:, :, 64:])
                 n1 = torch.hypot(got[8192:, :, :64].float(), got[8192:, :, 64:].float())
                 assert bool(((n0 - n1).abs() <= 0.012 * n0 + 1e-3).all()), "pair norms, layer %d" % l
-    for l in (0, 41, 79):                                   # the oracle, sampled layers in full
-        _say("70b_long: oracle on layer %d" % l)
+    # source blocks and the stored chunk are what they were before the compose
+    for l in range(sh.L):
+        for side, t in enumerate((k, v)):
+            o = _window(2 * l + side + 1, per_layer)
+            assert torch.equal(t[l, src_d].reshape(-1), dpool[o:o + per_layer]), "source blocks, layer %d" % l
+
+    # the oracle, every layer in full, one layer per task on 16 host threads
+    a, b = np.arange(blocks, dtype=np.int32), np.arange(blocks, 2 * blocks, dtype=np.int32)
+    offsets = list(w.offsets)
+
+    def check_layer(l):
         hk = np.zeros((1, 2 * blocks, sh.bs, sh.H, sh.D), dtype=np.uint16)
         hv = np.zeros_like(hk)
         for side, t in enumerate((hk, hv)):
             o = _window(2 * l + side + 1, per_layer)
             t[0, :blocks] = hpool[o:o + per_layer].reshape(blocks, sh.bs, sh.H, sh.D)
         h1 = O.PagedCache(hk, hv)
-        a, b = np.arange(blocks, dtype=np.int32), np.arange(blocks, 2 * blocks, dtype=np.int32)
         hc = O.store(h1, a, 0, T, INT8)
-        assert np.array_equal(codes[l].cpu().numpy(), hc.codes()[0])
-        assert np.array_equal(scales[l].cpu().numpy(), hc.scales()[0])
-        O.compose([hc.slice(i * 8192, 8192) for i in range(4)], list(w.offsets), h1, b, w.rope_base)
+        assert np.array_equal(codes[l].cpu().numpy(), hc.codes()[0]), "codes, layer %d" % l
+        assert np.array_equal(scales[l].cpu().numpy(), hc.scales()[0]), "scales, layer %d" % l
+        O.compose([hc.slice(i * 8192, 8192) for i in range(4)], offsets, h1, b, w.rope_base)
         gk, gv = bits_of(k[l, dst_d]), bits_of(v[l, dst_d])
-        assert np.array_equal(gv, h1.v[0, blocks:])
+        assert np.array_equal(gv, h1.v[0, blocks:]), "V, layer %d" % l
         if not np.array_equal(gk, h1.k[0, blocks:]):
             d = np.abs(f32_of_bits(gk).astype(np.float64) - f32_of_bits(h1.k[0, blocks:]))
             raise AssertionError("K layer %d: max diff %g (tolerance %g), %d elements"
                                  % (l, d.max(), K_TOL, np.count_nonzero(d)))
+        return l
+
+    t_start = time.perf_counter()
+    done = 0
+    with ThreadPoolExecutor(16) as ex:
+        for l in ex.map(check_layer, range(sh.L)):
+            done += 1
+            if done % 10 == 0:
+                _say("70b_long: oracle parity, %d layers done" % done)
+    _say("70b_long: layers checked %d/%d against the oracle, every element (codes, scales, K, V), in %.1f s"
+         % (done, sh.L, time.perf_counter() - t_start))
+    assert done == sh.L
 
 
 @pytest.mark.timeout(1200)
@@ -267,31 +291,49 @@ def test_batched_reuse_pool_of_256_chunks_64_requests(value_pool):
                 if offsets[j] == 0:
                     assert torch.equal(dk[l, blk].reshape(Tc, sh.H, sh.D), deq[0].to(torch.bfloat16))
 
-    # the oracle on sampled (request, layer) pairs, from the seeded source values
-    for r, l in ((0, 0), (17, 5), (63, 31), (40, 16), (5, 30)):
-        _say("batched_reuse: oracle on request %d layer %d" % (r, l))
-        hk = np.zeros((1, 2 * blocks_req, sh.bs, sh.H, sh.D), dtype=np.uint16)
-        hv = np.zeros_like(hk)
-        hch = []
-        for j, c in enumerate(draws[r]):
-            g, i = int(c) // round_chunks, int(c) % round_chunks
-            perm = src_perm(g)[i * cb:(i + 1) * cb]
+    # the oracle on every (request, layer) pair and on every stored chunk of the pool, from the
+    # seeded source values; one layer per task on 16 host threads.  The pool is checked after
+    # the compose, so a compose that damaged a stored chunk would show here too.
+    perms = [src_perm(g) for g in range(n_pool // round_chunks)]
+    one = np.arange(cb, dtype=np.int32)
+    dst_a = np.arange(blocks_req, dtype=np.int32)
+    bts = [torch.from_numpy(tables[r]).long().cuda() for r in range(n_req)]
+
+    def check_layer(l):
+        stored = []
+        for c in range(n_pool):
+            g, i = c // round_chunks, c % round_chunks
+            hk = np.empty((1, cb, sh.bs, sh.H, sh.D), dtype=np.uint16)
+            hv = np.empty_like(hk)
             for side, t in enumerate((hk, hv)):
                 o = _window(1000 * (g + 1) + 2 * l + side, per_layer)
-                full = hpool[o:o + per_layer].reshape(rb, sh.bs, sh.H, sh.D)
-                t[0, j * cb:(j + 1) * cb] = full[perm]
-        h1 = O.PagedCache(hk, hv)
-        for j, c in enumerate(draws[r]):
-            hc = O.store(h1, np.arange(j * cb, (j + 1) * cb, dtype=np.int32), 0, Tc, INT8)
-            assert np.array_equal(pool[int(c)].codes()[l].cpu().numpy(), hc.codes()[0])
-            assert np.array_equal(pool[int(c)].scales()[l].cpu().numpy(), hc.scales()[0])
-            hch.append(hc)
-        b = np.arange(blocks_req, 2 * blocks_req, dtype=np.int32)
-        O.compose(hch, offsets, h1, b, w.rope_base)
-        bt = torch.from_numpy(tables[r]).long().cuda()
-        gk, gv = bits_of(dk[l, bt]), bits_of(dv[l, bt])
-        assert np.array_equal(gv, h1.v[0, blocks_req:])
-        if not np.array_equal(gk, h1.k[0, blocks_req:]):
-            d = np.abs(f32_of_bits(gk).astype(np.float64) - f32_of_bits(h1.k[0, blocks_req:]))
-            raise AssertionError("K request %d layer %d: max diff %g (tolerance %g), %d elements"
-                                 % (r, l, d.max(), K_TOL, np.count_nonzero(d)))
+                t[0] = hpool[o:o + per_layer].reshape(rb, sh.bs, sh.H, sh.D)[perms[g][i * cb:(i + 1) * cb]]
+            hc = O.store(O.PagedCache(hk, hv), one, 0, Tc, INT8)
+            assert np.array_equal(pool[c].codes()[l].cpu().numpy(), hc.codes()[0]), "codes, chunk %d layer %d" % (c, l)
+            assert np.array_equal(pool[c].scales()[l].cpu().numpy(), hc.scales()[0]), "scales, chunk %d layer %d" % (c, l)
+            stored.append(hc)
+        hd = O.PagedCache(np.empty((1, blocks_req, sh.bs, sh.H, sh.D), dtype=np.uint16),
+                          np.empty((1, blocks_req, sh.bs, sh.H, sh.D), dtype=np.uint16))
+        for r in range(n_req):
+            hd.k.fill(0x7FC1)
+            hd.v.fill(0x7FC2)
+            O.compose([stored[int(c)] for c in draws[r]], offsets, hd, dst_a, w.rope_base)
+            gk, gv = bits_of(dk[l, bts[r]]), bits_of(dv[l, bts[r]])
+            assert np.array_equal(gv, hd.v[0]), "V, request %d layer %d" % (r, l)
+            if not np.array_equal(gk, hd.k[0]):
+                d = np.abs(f32_of_bits(gk).astype(np.float64) - f32_of_bits(hd.k[0]))
+                raise AssertionError("K request %d layer %d: max diff %g (tolerance %g), %d elements"
+                                     % (r, l, d.max(), K_TOL, np.count_nonzero(d)))
+        return l
+
+    t_start = time.perf_counter()
+    done = 0
+    with ThreadPoolExecutor(16) as ex:
+        for l in ex.map(check_layer, range(sh.L)):
+            done += 1
+            if done % 4 == 0:
+                _say("batched_reuse: oracle parity, %d layers done" % done)
+    _say("batched_reuse: pairs checked %d/%d (request, layer) against the oracle, every element; stored chunks "
+         "checked %d/%d x %d layers; in %.1f s"
+         % (done * n_req, n_req * sh.L, n_pool, n_pool, done, time.perf_counter() - t_start))
+    assert done == sh.L

@@ -41,6 +41,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
+POOL_GIB_DEFAULT = 96.0     # size of each of the paged pool's K and V tensors in the default runs
 METRIC = "KV tokens composed/sec (store+load+RoPE shift) and achieved HBM GB/s"
 FMT_IDS = {"raw": 0, "int8": 1, "int4": 2, "fp8": 3}
 
@@ -70,6 +71,17 @@ def fill_normal(t, gen):
     import torch
     for i in range(t.shape[0]):
         t[i].copy_(torch.randn(t.shape[1:], generator=gen, device=t.device, dtype=torch.float32))
+
+
+def pool_blocks_for(args, need, plane_bytes_per_block):
+    """Blocks per (layer, side) plane of the paged pool.  --pool-blocks names it directly;
+    otherwise --pool-gib sizes each of the K and V tensors (all layers) to that many GiB, as an
+    engine does that gives most of HBM to its KV pool; never fewer than the step's tables use."""
+    if args.pool_blocks:
+        if args.pool_blocks < need:
+            raise SystemExit("bench.py: --pool-blocks must be at least %d" % need)
+        return args.pool_blocks
+    return max(need, int(args.pool_gib * (1 << 30)) // plane_bytes_per_block)
 
 
 class Timed:
@@ -123,26 +135,33 @@ def _probe_rate(kdn, torch, small, big, tiles, ids, tile_kib, direction, cap, re
     return tiles * tile_kib * 1536 / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
 
 
-def stream_ceiling(dev):
+def stream_ceiling(dev, pool_gib):
     """The box's own yardstick: the library's plain streaming kernel (kdn_probe_stream: per
     workgroup one 32 KiB tile of the big buffer and 16 KiB of the small one, no arithmetic, no
-    table walk), 32768 tiles = 1.61 GB per launch, over 3 rotating buffer sets.  In the pattern of
-    load and compose (small -> big) with the destination tiles in order and scattered by a seeded
-    permutation, as the blocks of a random block table are; and in the pattern of store
-    (big -> small) with the source tiles scattered."""
+    table walk), 32768 tiles = 1.61 GB per launch.  The big buffer is as large as the paged
+    pool's two tensors; in the pattern of load and compose (small -> big) the written tiles
+    are taken in order, scattered over the whole of it (as the blocks of a random table over an
+    engine-sized pool are) and scattered inside 16 GiB of it; in the pattern of store
+    (big -> small) the read tiles are scattered over the whole of it."""
+    import numpy as np
     import torch
     from paper_2409_13761_amd import kdn, synth
     tiles, sets, reps = 32768, 3, 12
+    big_gib = max(16, int(2 * pool_gib))
     small = [torch.empty(tiles * 16384, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(sets)]
-    big = [torch.empty(tiles * 32768, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(sets)]
-    ids = torch.from_numpy(synth.permutation(4242, tiles).astype("int32")).to(dev)
+    big = [torch.empty(big_gib << 30, dtype=torch.uint8, device=dev)] * sets
+    rng = synth._rng(4242, 1)
+    wide = torch.from_numpy(rng.permutation(big_gib * 32768)[:tiles].astype(np.int32)).to(dev)
+    narrow = torch.from_numpy(rng.permutation(16 * 32768)[:tiles].astype(np.int32)).to(dev)
     out = {"place_pattern_contiguous_GBps": _probe_rate(kdn, torch, small, big, tiles, None, 32, 0, 0, reps),
-           "place_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, ids, 32, 0, 0, reps),
-           "store_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, ids, 32, 1, 0, reps)}
+           "place_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, wide, 32, 0, 0, reps),
+           "place_pattern_scattered_within_16GiB_GBps": _probe_rate(kdn, torch, small, big, tiles, narrow, 32, 0, 0, reps),
+           "store_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, wide, 32, 1, 0, reps)}
     out["what"] = ("kdn_probe_stream, one workgroup per tile (32 KiB of the big buffer, 16 KiB of the small one), streamed, "
-                   "no arithmetic; %d tiles (%.2f GB) per launch, %d buffer sets, HIP events. place pattern = read small, "
-                   "write big (load, compose); store pattern = read big, write small; scattered = the big buffer's tiles "
-                   "permuted like the blocks of a random table" % (tiles, tiles * 49152 / 1e9, sets))
+                   "no arithmetic; %d tiles (%.2f GB) per launch, HIP events; big buffer of %d GiB (the size of the paged "
+                   "pool). place pattern = read small, write big (load, compose); store pattern = read big, write small; "
+                   "scattered = the big buffer's tiles drawn at random from all of it (or from its first 16 GiB), like "
+                   "the blocks of a random table" % (tiles, tiles * 49152 / 1e9, big_gib))
     return out
 
 
@@ -179,6 +198,24 @@ def workload_stream_probe(args, dev):
         local_ids = torch.from_numpy(local.astype(np.int32)).to(dev)
         windows.append({"window_MiB": w_tiles / 32,
                         "place_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, local_ids, 32, 0, 0, reps)})
+    # where in the device memory the scattered tiles lie: one 200 GiB allocation, tiles drawn from parts of it
+    spans = []
+    del big
+    torch.cuda.empty_cache()
+    huge = torch.empty(200 << 30, dtype=torch.uint8, device=dev)
+    per_gib = (1 << 30) // 32768
+    for what, parts in (("16 GiB at the start", [(0, 16)]), ("16 GiB, 100 GiB in", [(100, 16)]),
+                        ("8 GiB at the start + 8 GiB, 104 GiB in", [(0, 8), (104, 8)]),
+                        ("8 GiB at 40 GiB + 8 GiB at 72 GiB", [(40, 8), (72, 8)]),
+                        ("three times 5 GiB, 96 GiB apart", [(0, 5), (96, 5), (192, 5)]),
+                        ("all 200 GiB", [(0, 200)])):
+        pool_ids = np.concatenate([np.arange(a * per_gib, (a + n) * per_gib) for a, n in parts])
+        pick = rng.permutation(pool_ids.size)[:tiles]
+        span_ids = torch.from_numpy(pool_ids[pick].astype(np.int32)).to(dev)
+        spans.append({"tiles_drawn_from": what,
+                      "place_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 0, 0, reps),
+                      "store_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 1, 0, reps)})
+    del huge
     r32 = rows[2]
     ms = {"place_scattered": 1.5 * (1 << 30) / r32["place_scattered_GBps"] / 1e6}
     return {
@@ -189,7 +226,8 @@ def workload_stream_probe(args, dev):
                     "of a big one per launch, by tile size and by launch width; the headline fields are the 32 KiB-tile, "
                     "scattered, place-pattern row (no tokens are moved: value is 0)",
         "extra": {"by_tile_size": rows, "by_launch_width_at_32KiB_tiles": caps,
-                  "by_scatter_window_at_32KiB_tiles": windows},
+                  "by_scatter_window_at_32KiB_tiles": windows,
+                  "by_span_of_device_memory_at_32KiB_tiles": spans},
         "traffic": None,
     }
 
@@ -203,11 +241,7 @@ def workload_8b(args, dev):
     w = synth.WORKLOADS["rag_compose"]
     blocks = T // sh.bs
     n_sets = 4
-    nb = n_sets * 3 * blocks
-    if args.pool_blocks:
-        if args.pool_blocks < nb:
-            raise SystemExit("bench.py: --pool-blocks must be at least %d" % nb)
-        nb = args.pool_blocks
+    nb = pool_blocks_for(args, n_sets * 3 * blocks, sh.L * sh.bs * sh.H * sh.D * 2)
     g = torch.Generator(device=dev)
     g.manual_seed(w.seed)
     if args.layout == "planes":         # K and V tensors [L][num_blocks][bs][H][D]
@@ -261,7 +295,7 @@ def workload_8b(args, dev):
                     % (args.fmt, w.rope_base, n_sets, args.layout, nb,
                        "random disjoint" if args.tables == "random" else "consecutive-block"),
         "traffic": counter_traffic("8b") if args.fmt == "int8" and args.tables == "random" and args.layout == "planes"
-        and not args.pool_blocks else None,
+        and not args.pool_blocks and args.pool_gib == POOL_GIB_DEFAULT else None,
     }
     if not args.no_cpu_baseline and args.fmt == "int8":
         res["cpu_baseline"] = cpu_baseline(kdn, cache, sets[0], order, offsets, w.rope_base, T, n_slices,
@@ -329,7 +363,7 @@ def workload_70b(args, dev):
     sh, T = w.shape, 32768
     blocks = T // sh.bs
     n_sets = 2
-    nb = n_sets * 2 * blocks
+    nb = pool_blocks_for(args, n_sets * 2 * blocks, sh.L * sh.bs * sh.H * sh.D * 2)
     g = torch.Generator(device=dev)
     g.manual_seed(w.seed)
     k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
@@ -358,9 +392,11 @@ def workload_70b(args, dev):
         "place_calls": ("compose",),
         "workload": "70b_long: Llama-3-70B-shaped KV (L80 H8 D128 bs16), per step store 32768 tokens to %s (one call) "
                     "and compose them back as 4x8192-token slices with RoPE offsets 0/8192/16384/24576 (base %g) "
-                    "into a fresh table; random disjoint block tables in a pool of %d blocks; %d buffer sets cycled"
-                    % (args.fmt, w.rope_base, nb, n_sets),
-        "traffic": counter_traffic("70b_long") if args.fmt == "int8" else None,
+                    "into a fresh table; random disjoint block tables in a paged pool of %d blocks (K and V tensors of "
+                    "%.1f GiB each); %d buffer sets cycled"
+                    % (args.fmt, w.rope_base, nb, nb * sh.L * sh.bs * sh.H * sh.D * 2 / 2 ** 30, n_sets),
+        "traffic": counter_traffic("70b_long") if args.fmt == "int8" and not args.pool_blocks
+        and args.pool_gib == POOL_GIB_DEFAULT else None,
     }
     if not args.no_cpu_baseline and args.fmt == "int8":
         res["cpu_baseline"] = cpu_baseline_70b(kdn, cache, sets[0], offsets, w.rope_base, T, args.cpu_layers)
@@ -396,7 +432,7 @@ def workload_batched(args, dev):
     del k, v, src_cache
     draws = synth.zipf_distinct_draws(w.seed, n_req, per_req, n_pool, w.extra["alpha"])
     blocks_req = per_req * cb
-    nb = n_req * blocks_req
+    nb = pool_blocks_for(args, n_req * blocks_req, sh.L * sh.bs * sh.H * sh.D * 2)
     tables = synth.disjoint_block_tables(w.seed, nb, [blocks_req] * n_req)
     dst = kdn.PagedCache(torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16),
                          torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16))
@@ -421,7 +457,8 @@ def workload_batched(args, dev):
         "place_calls": ("compose_batch",),
         "workload": "batched_reuse (L32 H8 D128 bs16): 64 requests x 4 chunks of 1024 tokens drawn by "
                     "Zipf(1.0) from a resident pool of 256 int8 chunks (%d distinct drawn), one batched "
-                    "compose per step into 64 disjoint random tables" % unique,
+                    "compose per step into 64 disjoint random tables in a paged pool of %d blocks (K and V tensors of "
+                    "%.1f GiB each)" % (unique, nb, nb * sh.L * sh.bs * sh.H * sh.D * 2 / 2 ** 30),
         "extra": {"distinct_chunks": unique,
                   "bytes_counted": "each distinct chunk read once + every destination row written",
                   "bytes_if_every_draw_were_read_from_hbm": naive,
@@ -973,9 +1010,12 @@ def main() -> int:
     ap.add_argument("--tables", choices=("random", "consecutive"), default="random",
                     help="block tables of the 8b workload: sampled without replacement from the pool "
                          "(default, the stated workload) or runs of consecutive blocks")
+    ap.add_argument("--pool-gib", type=float, default=POOL_GIB_DEFAULT,
+                    help="size in GiB of each of the paged pool's K and V tensors (8b, 70b_long, batched_reuse): an "
+                         "engine gives most of HBM to its KV pool, and the block tables are drawn from all of it; 0 "
+                         "makes the pool only as large as the tables the step uses")
     ap.add_argument("--pool-blocks", type=int, default=0,
-                    help="blocks in the paged pool of the 8b workload (default 3072, the 12 tables of 256 blocks "
-                         "it uses); the distance between a block's tiles in neighbouring planes follows from it")
+                    help="blocks per (layer, side) plane of the paged pool, instead of --pool-gib")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=8, help="oracle steps of the 8b workload's CPU baseline")
     ap.add_argument("--cpu-layers", type=int, default=20,
@@ -1056,7 +1096,7 @@ def main() -> int:
     torch.cuda.empty_cache()
 
     if args.workload in ("70b_long", "8b") and not args.only:
-        ceiling = stream_ceiling(dev)
+        ceiling = stream_ceiling(dev, args.pool_gib if not args.pool_blocks else 8)
         torch.cuda.empty_cache()
         # load and compose write through random block tables and store reads through one, so the
         # scattered figures are their yardsticks

@@ -831,14 +831,14 @@ kdn_status kdn_probe_stream(void *small_dev, void *big_dev, const int32_t *tile_
     hipStream_t hs = static_cast<hipStream_t>(stream);
     u32x4 *sm = static_cast<u32x4 *>(small_dev), *bg = static_cast<u32x4 *>(big_dev);
     const dim3 g(grid), b(kThreads);
-    if (direction == 0 && chunks % 4 == 0)
-        hipLaunchKernelGGL((k_probe_stream<0, true>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
+    if (direction == 0 && chunks == 4)
+        hipLaunchKernelGGL((k_probe_stream<0, 4>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
     else if (direction == 0)
-        hipLaunchKernelGGL((k_probe_stream<0, false>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
-    else if (chunks % 4 == 0)
-        hipLaunchKernelGGL((k_probe_stream<1, true>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
+        hipLaunchKernelGGL((k_probe_stream<0, 0>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
+    else if (chunks == 4)
+        hipLaunchKernelGGL((k_probe_stream<1, 4>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
     else
-        hipLaunchKernelGGL((k_probe_stream<1, false>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
+        hipLaunchKernelGGL((k_probe_stream<1, 0>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
     return hip_status(hipGetLastError());
 }
 

@@ -871,11 +871,13 @@ __global__ void k_f32_to_bf16(const float *__restrict__ in, uint16_t *__restrict
 // writes tile t of `small`.  16 bytes per lane and instruction, up to four 4 KiB loads of a
 // thread issued before its first store, everything streamed; fewer workgroups than tiles
 // stride over them.
-template <int DIR, bool FULL> // FULL: chunks is a multiple of 4, so no load or store is predicated
+template <int DIR, int CH> // CH: chunks of 4 KiB per small tile when known at compile time (4: the 32 KiB tile), else 0
 __global__ __launch_bounds__(kThreads) void k_probe_stream(u32x4 *__restrict__ small, u32x4 *__restrict__ big,
                                                           const int32_t *__restrict__ ids, uint32_t tiles,
-                                                          uint32_t chunks)
+                                                          uint32_t chunks_arg)
 {
+    constexpr bool FULL = CH > 0; // nothing is predicated
+    const uint32_t chunks = CH ? CH : chunks_arg;
     for (uint32_t t = blockIdx.x; t < tiles; t += gridDim.x) {
         u32x4 *s = small + (size_t)t * chunks * kThreads;
         u32x4 *b = big + (size_t)(ids ? (uint32_t)ids[t] : t) * chunks * (2 * kThreads);

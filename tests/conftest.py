@@ -12,6 +12,14 @@ def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run through the C-ABI library)")
 
 
+def pytest_terminal_summary(terminalreporter):
+    import notes
+    if notes.LINES:
+        terminalreporter.section("coverage notes")
+        for line in notes.LINES:
+            terminalreporter.write_line(line)
+
+
 @pytest.fixture(scope="session")
 def oracle():
     from oracle import kdn_oracle
@@ -21,7 +29,7 @@ def oracle():
 
 @pytest.fixture(scope="session", autouse=True)
 def _library_present():
-    """A fresh checkout holds no built library: build it once (hipcc cross-compiles without a
-    GPU).  A library that is there is used as it is."""
+    """The library must match the sources beside it: a fresh checkout builds it once (hipcc
+    cross-compiles without a GPU), a stale binary is built again, a failing build raises."""
     from paper_2409_13761_amd import build
     build.ensure_built()

@@ -11,6 +11,7 @@ import numpy as np
 import pytest
 import torch
 
+import notes
 from helpers import INT8, assert_cache_equal, dev_cache, dev_table, host_cache
 from oracle import kdn_oracle as O
 from oracle.pool_oracle import LFU, LRU, PoolOracle
@@ -82,5 +83,6 @@ def test_store_on_miss_compose_on_hit_over_a_zipf_trace(policy):
     assert st.entries == len(model.entries) <= resident and st.bytes == model.bytes
     assert len(free) + len(text_in) == resident + per_req
     rate = st.hits / (st.hits + st.misses)
-    print("[serving] policy %d: hit rate %.3f, %d evictions" % (policy, rate, st.evictions), flush=True)
+    notes.note("[serving] policy %d: %d requests, hit rate %.3f, %d evictions: every decision equal to the reference "
+               "model's, paged cache equal to the oracle's replay" % (policy, n_req, rate, st.evictions))
     assert 0.2 < rate < 0.95                                    # the trace exercises both branches

@@ -23,6 +23,9 @@ from paper_2409_13761_amd import kdn, synth
 pytestmark = pytest.mark.gpu
 
 
+import notes
+
+
 def _say(msg):
     print("[workload] " + msg, flush=True)
 
@@ -126,6 +129,20 @@ def test_rag_compose_eight_chunks_in_seeded_order():
 
 # ----------------------------------------------------------------- large workloads
 POOL_ELEMS = 1 << 26
+POOL_BYTES = 96 << 30           # each of the K and V tensors of the large workloads' paged pool, as in bench.py
+SENTINEL = 0x7FC1               # a NaN pattern that neither N(0,1) values nor the kernels produce
+
+
+@pytest.fixture(autouse=True)
+def _release_device_memory():
+    """The large workloads take most of the device: what the previous test held (also through
+    reference cycles of its closures) goes back to the driver first."""
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    yield
+    gc.collect()
+    torch.cuda.empty_cache()
 
 
 @pytest.fixture(scope="module")
@@ -153,14 +170,17 @@ def _property_checks_store(src_rows: torch.Tensor, codes: torch.Tensor, scales: 
 @pytest.mark.timeout(900)
 def test_llama70b_long_context_store_once_compose_four_slices(value_pool):
     w = synth.WORKLOADS["70b_long"]
-    sh, T, nb = w.shape, 32768, 4096
+    sh, T = w.shape, 32768
+    nb = POOL_BYTES // (sh.L * sh.bs * sh.H * sh.D * 2)     # the pool bench.py times: K and V tensors of 96 GiB
     hpool, dpool = value_pool
     blocks = T // sh.bs
     src, dst = synth.disjoint_block_tables(w.seed, nb, [blocks, blocks])
     per_layer = blocks * sh.bs * sh.H * sh.D
-    _say("70b_long: building the paged cache on the device")
+    _say("70b_long: building the paged cache on the device, %d blocks per plane" % nb)
     k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), dtype=torch.bfloat16, device="cuda")
     v = torch.empty_like(k)
+    k.view(torch.int16).fill_(SENTINEL)
+    v.view(torch.int16).fill_(SENTINEL)
     src_d = torch.from_numpy(src).long().cuda()
     for l in range(sh.L):
         for side, t in enumerate((k, v)):
@@ -191,11 +211,15 @@ def test_llama70b_long_context_store_once_compose_four_slices(value_pool):
                 n0 = torch.hypot(deq[8192:, :, :64], deq[8192:, :, 64:])
                 n1 = torch.hypot(got[8192:, :, :64].float(), got[8192:, :, 64:].float())
                 assert bool(((n0 - n1).abs() <= 0.012 * n0 + 1e-3).all()), "pair norms, layer %d" % l
-    # source blocks and the stored chunk are what they were before the compose
+    # source blocks are what they were before the compose, and no block outside the two tables was written
+    outside = torch.ones(nb, dtype=torch.bool, device="cuda")
+    outside[src_d] = False
+    outside[dst_d] = False
     for l in range(sh.L):
         for side, t in enumerate((k, v)):
             o = _window(2 * l + side + 1, per_layer)
             assert torch.equal(t[l, src_d].reshape(-1), dpool[o:o + per_layer]), "source blocks, layer %d" % l
+            assert bool((t[l].view(torch.int16)[outside] == SENTINEL).all()), "a block outside the tables, layer %d" % l
 
     # the oracle, every layer in full, one layer per task on 16 host threads
     a, b = np.arange(blocks, dtype=np.int32), np.arange(blocks, 2 * blocks, dtype=np.int32)
@@ -227,8 +251,8 @@ def test_llama70b_long_context_store_once_compose_four_slices(value_pool):
             done += 1
             if done % 10 == 0:
                 _say("70b_long: oracle parity, %d layers done" % done)
-    _say("70b_long: layers checked %d/%d against the oracle, every element (codes, scales, K, V), in %.1f s"
-         % (done, sh.L, time.perf_counter() - t_start))
+    notes.note("[workload] 70b_long: layers checked %d/%d against the oracle, every element (codes, scales, K, V), "
+               "in %.1f s" % (done, sh.L, time.perf_counter() - t_start))
     assert done == sh.L
 
 
@@ -266,11 +290,14 @@ def test_batched_reuse_pool_of_256_chunks_64_requests(value_pool):
 
     draws = synth.zipf_distinct_draws(w.seed, n_req, per_req, n_pool, w.extra["alpha"])
     blocks_req = per_req * cb
-    nb = n_req * blocks_req
+    nb = POOL_BYTES // (sh.L * sh.bs * sh.H * sh.D * 2)     # the pool bench.py times: K and V tensors of 96 GiB
     tables = synth.disjoint_block_tables(w.seed, nb, [blocks_req] * n_req)
-    _say("batched_reuse: %d distinct chunks drawn; destination %d blocks" % (len(np.unique(draws)), nb))
+    _say("batched_reuse: %d distinct chunks drawn; destination tables of %d blocks in a pool of %d"
+         % (len(np.unique(draws)), n_req * blocks_req, nb))
     dk = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), dtype=torch.bfloat16, device="cuda")
     dv = torch.empty_like(dk)
+    dk.view(torch.int16).fill_(SENTINEL)
+    dv.view(torch.int16).fill_(SENTINEL)
     dst = kdn.PagedCache(dk, dv)
     offsets = list(w.offsets)
     reqs = [([pool[int(c)] for c in draws[r]], offsets, dev_table(tables[r]), 0) for r in range(n_req)]
@@ -290,6 +317,13 @@ def test_batched_reuse_pool_of_256_chunks_64_requests(value_pool):
                 assert torch.equal(dv[l, blk].reshape(Tc, sh.H, sh.D), deq[1].to(torch.bfloat16))
                 if offsets[j] == 0:
                     assert torch.equal(dk[l, blk].reshape(Tc, sh.H, sh.D), deq[0].to(torch.bfloat16))
+
+    # no block outside the requests' tables was written
+    outside = torch.ones(nb, dtype=torch.bool, device="cuda")
+    outside[torch.from_numpy(np.concatenate(tables)).long().cuda()] = False
+    for l in range(sh.L):
+        for t in (dk, dv):
+            assert bool((t[l].view(torch.int16)[outside] == SENTINEL).all()), "a block outside the tables, layer %d" % l
 
     # the oracle on every (request, layer) pair and on every stored chunk of the pool, from the
     # seeded source values; one layer per task on 16 host threads.  The pool is checked after
@@ -333,7 +367,7 @@ def test_batched_reuse_pool_of_256_chunks_64_requests(value_pool):
             done += 1
             if done % 4 == 0:
                 _say("batched_reuse: oracle parity, %d layers done" % done)
-    _say("batched_reuse: pairs checked %d/%d (request, layer) against the oracle, every element; stored chunks "
-         "checked %d/%d x %d layers; in %.1f s"
-         % (done * n_req, n_req * sh.L, n_pool, n_pool, done, time.perf_counter() - t_start))
+    notes.note("[workload] batched_reuse: pairs checked %d/%d (request, layer) against the oracle, every element; "
+               "stored chunks checked %d/%d x %d layers; in %.1f s"
+               % (done * n_req, n_req * sh.L, n_pool, n_pool, done, time.perf_counter() - t_start))
     assert done == sh.L

@@ -746,7 +746,7 @@ def workload_sweep(args, dev):
         if args.fmt == "int4" and D % 32:
             continue
         blocks = T // bs
-        nb = blocks * 2 * n_sets
+        nb = pool_blocks_for(args, blocks * 2 * n_sets, L * bs * H * D * 2)
         g = torch.Generator(device=dev)
         g.manual_seed(1002)
         k = torch.empty((L, nb, bs, H, D), device=dev, dtype=torch.bfloat16)

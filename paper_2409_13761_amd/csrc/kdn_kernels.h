@@ -378,7 +378,8 @@ __global__ __launch_bounds__(kThreads) void k_store(StoreP p)
 // Grid: x = group * 2L + (layer, side), so that neighbouring workgroups write to
 // different (layer, side) planes; y = segment.
 // Serves head dims that are multiples of 128, where each of the two stores of a lane group
-// fills whole 128-byte lines; k_place_c below serves the others.
+// fills whole 128-byte lines: raw bf16 and per-token block lookup at 128, everything at 256
+// and 512; k_place_c below serves the others (the host planner holds the measurements).
 // Stored rows are streamed past the caches unless several segments read the same rows
 // (a popular chunk in a batched compose): then they are loaded normally, so that the
 // first reader leaves them in L2 and the last-level cache for the others.
@@ -633,8 +634,10 @@ __device__ __forceinline__ void dequantise8(const uint32_t *w, float scale, floa
     }
 }
 
-// place with row-contiguous ownership, for head dims where half a row is not a whole
-// number of 128-byte lines (head_dim not a multiple of 128; k_place serves the others).
+// place with row-contiguous ownership: for head dims where half a row is not a whole
+// number of 128-byte lines (head_dim not a multiple of 128), and for the quantised forms at
+// head_dim 128, where its loads (a wavefront reads 512 contiguous bytes of codes instead of
+// 64-byte pieces of 8 rows) make it the faster one on pools that span the device memory.
 // D/8 lanes own a row, 8 consecutive elements each, and a wavefront takes 64/(D/8) whole
 // rows at a time, so every load and store instruction covers rows back to back.  A lane
 // of a half-split rotary pair fetches the stored words of its partner, the lane rot/16

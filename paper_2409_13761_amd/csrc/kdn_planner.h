@@ -474,12 +474,20 @@ void launch_place_c(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs
     }
 }
 
-// k_place where half a row is a whole number of 128-byte lines, k_place_c elsewhere
+// Which place kernel serves a head_dim, by measurement on pools that span the device memory
+// (4096 tokens, 32 layers, TB/s of algorithmic bytes, k_place / k_place_c): the row-contiguous
+// kernel wins at head_dim 128 for the quantised forms (int8 5.75 / 6.0-6.3, int4 5.6 / 6.1),
+// ties for raw bf16 (6.35), and loses where every row looks its own block up (blocks of one to
+// three tokens: 5.65 / 4.8); at 256 and 512 the pair-owning kernel is ahead for int8
+// (6.13 / 6.03, 5.87 / 5.70).  Head dims that are not a multiple of 128 always take k_place_c
+// (there a pair-owning lane would write runs that are not whole 128-byte lines).
 template <int FMT>
 void launch_place_d(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs_dev, dim3 grid,
                     hipStream_t st)
 {
-    if (p.c.D == 128)
+    if (p.c.D == 128 && !p.c.per_token && FMT != KDN_FMT_RAW_BF16)
+        launch_place_c<128, FMT>(p, segs, n, segs_dev, grid, st);
+    else if (p.c.D == 128)
         launch_place<128, FMT>(p, segs, n, segs_dev, grid, st);
     else if (p.c.D % 128 == 0)
         launch_place<0, FMT>(p, segs, n, segs_dev, grid, st);

@@ -7,7 +7,9 @@ head_dim 128, bf16, paged in blocks of 16 tokens, random block tables) through t
   store    paged KV -> one stored int8 chunk (15.2 GiB moved)      (kdn_store_chunk)
   compose  the chunk as 4 slices of 8192 tokens, shifted by RoPE offsets
            0 / 8192 / 16384 / 24576, into a fresh table (15.2 GiB)  (kdn_compose)
-Inputs are resident in HBM before the timed region; two disjoint buffer sets alternate.
+Inputs are resident in HBM before the timed region; two disjoint buffer sets alternate.  The
+paged pool is sized as an engine sizes it (K and V tensors of 96 GiB each, --pool-gib) and the
+block tables are drawn from all of it.
 The default run then also times, more briefly, the "8b" step (4096 tokens of Llama-3-8B
 shape: store, load at offset 0, compose of 8 shifted 512-token slices; four buffer sets
 cycled so that the 256 MB last-level cache serves no repeat) and the "batched_reuse"
@@ -49,9 +51,9 @@ FMT_IDS = {"raw": 0, "int8": 1, "int4": 2, "fp8": 3}
 # under profiles/ (the file named here), per workload; valid only for the library sources
 # they were taken with, whose fingerprint the library itself carries.
 COUNTER_TRAFFIC = {
-    "source_fingerprint": "",
-    "70b_long": {"k_place_bytes_per_launch": None, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
-    "8b": {"k_place_bytes_per_launch": None, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
+    "source_fingerprint": "f8eb94d3943926ed",
+    "70b_long": {"k_place_bytes_per_launch": 16276755546, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
+    "8b": {"k_place_bytes_per_launch": 814054503, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
 }
 
 
@@ -511,6 +513,9 @@ def workload_host_stream(args, dev, fmt_name):
         rec("store_to_host", lambda: kdn.kdn_store_to_host(cache, src, 0, T, host, staging, lps))
         rec("compose_from_host", lambda: kdn.kdn_compose_from_host(
             slices, offsets, cache, dsts[i % 2], w.rope_base, staging, lps))
+        # one step at a time: with hundreds of staged copies queued ahead the runtime now and then runs
+        # a call's copies several times slower (seen with any copy path, not with the kernels)
+        torch.cuda.current_stream().synchronize()
 
     names = ("store_direct", "compose_direct", "store_to_host", "compose_from_host")
     wall, ms = Timed(names, args.steps).run(step, args.warmup)

@@ -32,6 +32,7 @@ kernel (the place kernel behind load and compose) from HIP-event timings, and th
 CPU oracle's throughput on the host cores as a reported baseline.
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -73,6 +74,14 @@ def fill_normal(t, gen):
     import torch
     for i in range(t.shape[0]):
         t[i].copy_(torch.randn(t.shape[1:], generator=gen, device=t.device, dtype=torch.float32))
+
+
+ARENA = None                # what kdn_arena_create reported, when the run keeps its stored chunks in the striped arena
+
+
+def chunk_alloc(kdn, cache, T, fmt):
+    """A chunk buffer: from the striped arena when the run has one, else from torch."""
+    return kdn.alloc_chunk(cache, T, fmt, arena=ARENA is not None)
 
 
 def pool_blocks_for(args, need, plane_bytes_per_block):
@@ -150,7 +159,12 @@ def stream_ceiling(dev, pool_gib):
     from paper_2409_13761_amd import kdn, synth
     tiles, sets, reps = 32768, 3, 12
     big_gib = max(16, int(2 * pool_gib))
-    small = [torch.empty(tiles * 16384, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(sets)]
+    plain = [torch.empty(tiles * 16384, dtype=torch.uint8, device=dev).random_(0, 255) for _ in range(sets)]
+    small = plain
+    if ARENA is not None:       # the small buffers stand for the stored chunks: they lie where the chunks lie
+        small = [kdn.arena_tensor(tiles * 16384) for _ in range(sets)]
+        for a, b in zip(small, plain):
+            a.copy_(b)
     big = [torch.empty(big_gib << 30, dtype=torch.uint8, device=dev)] * sets
     rng = synth._rng(4242, 1)
     wide = torch.from_numpy(rng.permutation(big_gib * 32768)[:tiles].astype(np.int32)).to(dev)
@@ -159,11 +173,18 @@ def stream_ceiling(dev, pool_gib):
            "place_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, wide, 32, 0, 0, reps),
            "place_pattern_scattered_within_16GiB_GBps": _probe_rate(kdn, torch, small, big, tiles, narrow, 32, 0, 0, reps),
            "store_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, wide, 32, 1, 0, reps)}
+    if ARENA is not None:
+        out["store_pattern_scattered_small_buffer_in_plain_memory_GBps"] = _probe_rate(kdn, torch, plain, big, tiles, wide,
+                                                                                       32, 1, 0, reps)
+        out["place_pattern_scattered_small_buffer_in_plain_memory_GBps"] = _probe_rate(kdn, torch, plain, big, tiles, wide,
+                                                                                       32, 0, 0, reps)
     out["what"] = ("kdn_probe_stream, one workgroup per tile (32 KiB of the big buffer, 16 KiB of the small one), streamed, "
                    "no arithmetic; %d tiles (%.2f GB) per launch, HIP events; big buffer of %d GiB (the size of the paged "
                    "pool). place pattern = read small, write big (load, compose); store pattern = read big, write small; "
                    "scattered = the big buffer's tiles drawn at random from all of it (or from its first 16 GiB), like "
-                   "the blocks of a random table" % (tiles, tiles * 49152 / 1e9, big_gib))
+                   "the blocks of a random table; the small buffers lie in %s"
+                   % (tiles, tiles * 49152 / 1e9, big_gib, "the striped arena, as the stored chunks do" if ARENA is not None
+                      else "plain device memory"))
     return out
 
 
@@ -268,7 +289,7 @@ def workload_8b(args, dev):
     sets = []
     for s in range(n_sets):
         src, dst_a, dst_b = (torch.from_numpy(tables[3 * s + i]).to(dev) for i in range(3))
-        chunk = kdn.alloc_chunk(cache, T, FMT_IDS[args.fmt])
+        chunk = chunk_alloc(kdn, cache, T, FMT_IDS[args.fmt])
         slices = [chunk.slice(int(i) * (T // n_slices), T // n_slices) for i in order]
         sets.append((src, dst_a, dst_b, chunk, slices))
     kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
@@ -378,7 +399,7 @@ def workload_70b(args, dev):
     sets = []
     for s in range(n_sets):
         src, dst = (torch.from_numpy(tables[2 * s + i]).to(dev) for i in range(2))
-        chunk = kdn.alloc_chunk(cache, T, FMT_IDS[args.fmt])
+        chunk = chunk_alloc(kdn, cache, T, FMT_IDS[args.fmt])
         sets.append((src, dst, chunk, [chunk.slice(i * 8192, 8192) for i in range(4)]))
     kdn.kdn_rope_prepare(w.rope_base, sh.D, offsets)
 
@@ -389,14 +410,30 @@ def workload_70b(args, dev):
 
     wall, ms = Timed(("store", "compose"), args.steps).run(step, args.warmup)
     bytes_call = T * (sh.paged_bytes_per_token + sh.stored_bytes_per_token(args.fmt))
+    extra = {}
+    if ARENA is not None:       # the same two calls with the chunk in plain device memory, for the difference
+        plain = kdn.alloc_chunk(cache, T, FMT_IDS[args.fmt])
+        plain_slices = [plain.slice(i * 8192, 8192) for i in range(4)]
+
+        def plain_step(i, rec):
+            src, dst = sets[i % n_sets][:2]
+            rec("store", lambda: kdn.kdn_store_chunk(cache, src, 0, T, plain))
+            rec("compose", lambda: kdn.kdn_compose(plain_slices, offsets, cache, dst, w.rope_base))
+
+        _, plain_ms = Timed(("store", "compose"), max(4, args.steps // 2)).run(plain_step, 2)
+        extra["GBps_with_the_chunk_in_plain_device_memory"] = {n: bytes_call / (plain_ms[n] * 1e-3) / 1e9
+                                                               for n in plain_ms}
+        del plain, plain_slices
     res = {
         "tokens_per_step": T, "wall": wall, "ms": ms, "bytes": {n: bytes_call for n in ms},
         "place_calls": ("compose",),
         "workload": "70b_long: Llama-3-70B-shaped KV (L80 H8 D128 bs16), per step store 32768 tokens to %s (one call) "
                     "and compose them back as 4x8192-token slices with RoPE offsets 0/8192/16384/24576 (base %g) "
                     "into a fresh table; random disjoint block tables in a paged pool of %d blocks (K and V tensors of "
-                    "%.1f GiB each); %d buffer sets cycled"
-                    % (args.fmt, w.rope_base, nb, nb * sh.L * sh.bs * sh.H * sh.D * 2 / 2 ** 30, n_sets),
+                    "%.1f GiB each); %d buffer sets cycled; chunk buffers in %s"
+                    % (args.fmt, w.rope_base, nb, nb * sh.L * sh.bs * sh.H * sh.D * 2 / 2 ** 30, n_sets,
+                       "the striped arena" if ARENA is not None else "plain device memory"),
+        "extra": extra,
         "traffic": counter_traffic("70b_long") if args.fmt == "int8" and not args.pool_blocks
         and args.pool_gib == POOL_GIB_DEFAULT else None,
     }
@@ -427,7 +464,7 @@ def workload_batched(args, dev):
         fill_normal(v, g)
         perm = synth.permutation(w.seed + 100 + rnd, rb)
         for i in range(16):
-            out = kdn.alloc_chunk(src_cache, Tc, kdn.FMT_INT8_ROWSCALE)
+            out = chunk_alloc(kdn, src_cache, Tc, kdn.FMT_INT8_ROWSCALE)
             kdn.kdn_store_chunk(src_cache, torch.from_numpy(perm[i * cb:(i + 1) * cb].copy()).to(dev), 0, Tc, out)
             pool.append(out)
         torch.cuda.synchronize()
@@ -562,7 +599,7 @@ def workload_pool_trace(args, dev):
     src_tabs = [torch.from_numpy(t).to(dev) for t in tabs[:n_src]]
     dst_tabs = [torch.from_numpy(t).to(dev) for t in tabs[n_src:]]
     chunk_bytes = kdn.kdn_chunk_bytes(sh.L, sh.H, sh.D, Tc, kdn.FMT_INT8_ROWSCALE)
-    free = [kdn.alloc_chunk(cache, Tc, kdn.FMT_INT8_ROWSCALE) for _ in range(resident + per_req)]
+    free = [chunk_alloc(kdn, cache, Tc, kdn.FMT_INT8_ROWSCALE) for _ in range(resident + per_req)]
     by_ptr = {c.data.data_ptr(): c for c in free}
     pool = kdn.Pool(resident * chunk_bytes, 0)
     total = args.warmup + args.steps
@@ -637,7 +674,7 @@ def workload_pool_trace_tiered(args, dev):
     dst_tabs = [torch.from_numpy(t).to(dev) for t in tabs[n_src:]]
     fmt = kdn.FMT_INT8_ROWSCALE
     chunk_bytes = kdn.kdn_chunk_bytes(sh.L, sh.H, sh.D, Tc, fmt)
-    dev_free = [kdn.alloc_chunk(cache, Tc, fmt) for _ in range(in_hbm + per_req)]
+    dev_free = [chunk_alloc(kdn, cache, Tc, fmt) for _ in range(in_hbm + per_req)]
     host_free = [kdn.alloc_host_chunk(cache, Tc, fmt) for _ in range(in_host + per_req)]
     by_ptr = {c.data.data_ptr(): c for c in dev_free + host_free}
     text_of = {}                                  # buffer address -> text it holds
@@ -760,7 +797,7 @@ def workload_sweep(args, dev):
         fill_normal(v, g)
         cache = kdn.PagedCache(k, v)
         tabs = [torch.from_numpy(t).to(dev) for t in synth.disjoint_block_tables(1002, nb, [blocks] * (2 * n_sets))]
-        chunks = [kdn.alloc_chunk(cache, T, fmt) for _ in range(n_sets)]
+        chunks = [chunk_alloc(kdn, cache, T, fmt) for _ in range(n_sets)]
         kdn.kdn_rope_prepare(500000.0, D, offsets)
         per_tok = L * 2 * H * D * 2 + kdn.kdn_chunk_bytes(L, H, D, 1, fmt)
         row = {"L": L, "H": H, "D": D, "block_size": bs, "note": note, "bytes_per_call": T * per_tok}
@@ -1021,6 +1058,11 @@ def main() -> int:
                          "makes the pool only as large as the tables the step uses")
     ap.add_argument("--pool-blocks", type=int, default=0,
                     help="blocks per (layer, side) plane of the paged pool, instead of --pool-gib")
+    ap.add_argument("--chunk-memory", choices=("arena", "plain"), default="arena",
+                    help="where the stored chunks lie: in the library's arena, whose 16 MiB granules alternate "
+                         "between the regions of the device memory (created first, before the pool), or in plain "
+                         "torch allocations")
+    ap.add_argument("--arena-gib", type=float, default=24.0, help="size of the arena")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=8, help="oracle steps of the 8b workload's CPU baseline")
     ap.add_argument("--cpu-layers", type=int, default=20,
@@ -1065,6 +1107,12 @@ def main() -> int:
             "int8": "int8 codes + fp32 row scales", "int4": "int4 codes + fp32 group scales",
             "fp8": "fp8 e4m3 codes + fp32 row scales", "raw": "raw bf16"}[f]
 
+    global ARENA
+    if args.chunk_memory == "arena" and args.workload not in ("stream_probe", "toy", "host_stream_int8",
+                                                              "host_stream_raw"):
+        torch.zeros(1, device=dev)
+        ARENA = kdn.kdn_arena_create(int(args.arena_gib * (1 << 30)))
+
     res = runners[args.workload](args, dev)
 
     if args.calibration_copy:
@@ -1095,9 +1143,13 @@ def main() -> int:
     body.pop("warmup")
     out.update(body)
     out["library"] = kdn.kdn_version()
+    if ARENA is not None:
+        out["arena"] = dict(ARENA, what="stored chunks lie in kdn_arena memory: granules taken in turn from the "
+                                        "regions of the device memory that kdn_arena_create found by measurement")
     if out["roofline"]["traffic"] is not None:
         out["roofline"]["traffic_from"] = COUNTER_TRAFFIC[args.workload]["profile"]
     del res
+    gc.collect()                                # chunk buffers go back to the arena, pools to torch
     torch.cuda.empty_cache()
 
     if args.workload in ("70b_long", "8b") and not args.only:
@@ -1120,6 +1172,7 @@ def main() -> int:
             r2 = runners[name](a2, dev)
             others[name] = summarise(r2, a2.steps, a2.warmup, fmt_note(name))
             del r2
+            gc.collect()
             torch.cuda.empty_cache()
         out["other_workloads"] = others
     print(json.dumps(out))

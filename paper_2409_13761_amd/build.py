@@ -8,8 +8,10 @@ import subprocess
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
-SOURCES = [os.path.join(_PKG, "csrc", "kdn.hip"), os.path.join(_PKG, "csrc", "kdn_pool.cpp")]
+SOURCES = [os.path.join(_PKG, "csrc", "kdn.hip"), os.path.join(_PKG, "csrc", "kdn_arena.hip"),
+           os.path.join(_PKG, "csrc", "kdn_pool.cpp")]
 HEADERS = [os.path.join(_ROOT, "include", "kdn.h"), os.path.join(_ROOT, "include", "kdn_pool.h"),
+           os.path.join(_ROOT, "include", "kdn_arena.h"),
            os.path.join(_PKG, "csrc", "kdn_kernels.h"), os.path.join(_PKG, "csrc", "kdn_planner.h")]
 LIB_PATH = os.path.join(_PKG, "libkdn.so")
 

@@ -57,6 +57,20 @@ class LaunchOpts(C.Structure):
     _fields_ = [("max_workgroups", C.c_int32)]
 
 
+class ArenaInfo(C.Structure):
+    _fields_ = [("bytes", C.c_uint64), ("granule", C.c_uint64), ("in_use", C.c_uint64), ("largest_free", C.c_uint64),
+                ("regions", C.c_int32), ("verified", C.c_int32), ("region_bytes", C.c_uint64 * 8),
+                ("same_region_gbs", C.c_float), ("cross_region_gbs", C.c_float), ("seconds", C.c_float),
+                ("probes", C.c_int32)]
+
+    def as_dict(self) -> dict:
+        return {"bytes": self.bytes, "granule": self.granule, "in_use": self.in_use, "largest_free": self.largest_free,
+                "regions": self.regions, "verified": self.verified,
+                "region_gib": [round(b / 2**30, 1) for b in list(self.region_bytes)[:max(self.regions, 1)]],
+                "same_region_gbs": round(self.same_region_gbs, 1), "cross_region_gbs": round(self.cross_region_gbs, 1),
+                "seconds": round(self.seconds, 3), "probes": self.probes}
+
+
 class PoolStats(C.Structure):
     _fields_ = [("hits", C.c_uint64), ("misses", C.c_uint64), ("inserts", C.c_uint64),
                 ("evictions", C.c_uint64), ("bytes", C.c_uint64), ("entries", C.c_uint64)]
@@ -162,6 +176,16 @@ def lib() -> C.CDLL:
         L.kdn_probe_stream.argtypes = [vp, vp, vp, C.c_uint32, i32, i32, i32, vp]
         L.kdn_f32_to_bf16.restype = C.c_int
         L.kdn_f32_to_bf16.argtypes = [vp, vp, u64, vp]
+        L.kdn_arena_create.restype = C.c_int
+        L.kdn_arena_create.argtypes = [u64, i32, C.POINTER(ArenaInfo)]
+        L.kdn_arena_alloc.restype = C.c_int
+        L.kdn_arena_alloc.argtypes = [u64, C.POINTER(vp)]
+        L.kdn_arena_free.restype = C.c_int
+        L.kdn_arena_free.argtypes = [vp]
+        L.kdn_arena_query.restype = C.c_int
+        L.kdn_arena_query.argtypes = [C.POINTER(ArenaInfo)]
+        L.kdn_arena_destroy.restype = C.c_int
+        L.kdn_arena_destroy.argtypes = []
         L.kdn_shutdown.restype = C.c_int
         L.kdn_shutdown.argtypes = []
         L.kdn_status_str.restype = C.c_char_p
@@ -184,7 +208,8 @@ EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_ch
            "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec", "kdn_rope_release",
            "kdn_validate_block_table", "kdn_probe_stream", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version", "kdn_pool_create", "kdn_pool_destroy", "kdn_pool_hash", "kdn_pool_lookup",
-           "kdn_pool_insert", "kdn_pool_remove", "kdn_pool_get_stats"]
+           "kdn_pool_insert", "kdn_pool_remove", "kdn_pool_get_stats", "kdn_arena_create", "kdn_arena_alloc",
+           "kdn_arena_free", "kdn_arena_query", "kdn_arena_destroy"]
 
 
 def status_str(status: int) -> str:
@@ -284,13 +309,13 @@ def kdn_chunk_bytes(L: int, H: int, D: int, num_tokens: int, fmt: int) -> int:
     return int(lib().kdn_chunk_bytes(L, H, D, num_tokens, fmt))
 
 
-def alloc_chunk(cache: PagedCache, num_tokens: int, fmt: int) -> Chunk:
-    """Allocate the device buffer of a chunk with torch and describe it."""
+def alloc_chunk(cache: PagedCache, num_tokens: int, fmt: int, arena: bool = False) -> Chunk:
+    """Allocate the device buffer of a chunk (with torch, or from the striped arena) and describe it."""
     L, _, _, H, D = cache.shape
     n = kdn_chunk_bytes(L, H, D, num_tokens, fmt)
     if n == 0:
         raise KdnError(EINVAL, "kdn_chunk_bytes")
-    data = torch.empty(n, dtype=torch.uint8, device=cache.k.device)
+    data = arena_tensor(n) if arena else torch.empty(n, dtype=torch.uint8, device=cache.k.device)
     d = ChunkDesc()
     _check(lib().kdn_chunk_init(C.byref(d), data.data_ptr(), n, fmt, L, H, D, num_tokens),
            "kdn_chunk_init")
@@ -600,6 +625,55 @@ def kdn_f32_to_bf16(x: torch.Tensor, out: torch.Tensor | None = None, stream=Non
     _check(lib().kdn_f32_to_bf16(x.data_ptr(), out.data_ptr(), x.numel(), _stream(stream)),
            "kdn_f32_to_bf16")
     return out
+
+
+# ------------------------------------------------------------------ striped device arena
+def kdn_arena_create(nbytes: int, granule_mib: int = 0) -> dict:
+    """Create the current device's arena (include/kdn_arena.h); returns what was measured."""
+    info = ArenaInfo()
+    _check(lib().kdn_arena_create(nbytes, granule_mib, C.byref(info)), "kdn_arena_create")
+    return info.as_dict()
+
+
+def kdn_arena_query() -> dict:
+    info = ArenaInfo()
+    _check(lib().kdn_arena_query(C.byref(info)), "kdn_arena_query")
+    return info.as_dict()
+
+
+def kdn_arena_alloc(nbytes: int) -> int:
+    p = C.c_void_p()
+    _check(lib().kdn_arena_alloc(nbytes, C.byref(p)), "kdn_arena_alloc")
+    return int(p.value)
+
+
+def kdn_arena_free(ptr: int) -> None:
+    _check(lib().kdn_arena_free(ptr), "kdn_arena_free")
+
+
+def kdn_arena_destroy() -> None:
+    """Every tensor from arena_tensor must be gone (or never used again) before this."""
+    _check(lib().kdn_arena_destroy(), "kdn_arena_destroy")
+
+
+class _ArenaBlock:
+    """Owns one kdn_arena_alloc block; torch holds it for as long as a tensor views the memory."""
+
+    def __init__(self, nbytes: int):
+        self.ptr = kdn_arena_alloc(nbytes)
+        self.__cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (self.ptr, False),
+                                         "version": 2}
+
+    def __del__(self):
+        ptr, self.ptr = getattr(self, "ptr", 0), 0
+        if ptr and _lib is not None:
+            _lib.kdn_arena_free(ptr)     # ENOTFOUND after kdn_arena_destroy: nothing left to give back
+
+
+def arena_tensor(nbytes: int) -> torch.Tensor:
+    """A uint8 tensor of nbytes on the current device whose memory is cut from the arena; the
+    block goes back to the arena when the last tensor that views it is collected."""
+    return torch.as_tensor(_ArenaBlock(nbytes), device="cuda")
 
 
 def kdn_shutdown() -> None:

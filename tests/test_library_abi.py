@@ -153,12 +153,13 @@ def test_headers_are_plain_c_and_the_library_links_from_c(lib, tmp_path):
     if shutil.which("gcc") is None:
         pytest.skip("needs gcc")
     src = tmp_path / "abi.c"
-    src.write_text('#include "kdn.h"\n#include "kdn_pool.h"\n#include <stdio.h>\n'
+    src.write_text('#include "kdn.h"\n#include "kdn_pool.h"\n#include "kdn_arena.h"\n#include <stdio.h>\n'
                    'int main(void) {\n'
                    '    kdn_chunk c; char buf[16] __attribute__((aligned(16)));\n'
                    '    unsigned long long n = kdn_chunk_bytes(32, 8, 128, 1, KDN_FMT_INT8_ROWSCALE);\n'
                    '    int st = kdn_chunk_init(&c, buf, sizeof buf, KDN_FMT_RAW_BF16, 1, 1, 16, 1);\n'
-                   '    printf("%llu %d %s\\n", n, st, kdn_status_str(KDN_ESIZE));\n'
+                   '    kdn_arena_info ai; int a = kdn_arena_query(&ai);   /* no arena: not found, or no device */\n'
+                   '    printf("%llu %d %d %u %s\\n", n, st, a, (unsigned)sizeof ai, kdn_status_str(KDN_ESIZE));\n'
                    '    return 0;\n}\n')
     exe = str(tmp_path / "abi")
     libdir = os.path.dirname(build.LIB_PATH)
@@ -168,4 +169,22 @@ def test_headers_are_plain_c_and_the_library_links_from_c(lib, tmp_path):
     assert p.returncode == 0, p.stderr
     out = subprocess.run([exe], capture_output=True, text=True, timeout=60)
     assert out.returncode == 0, out.stderr
-    assert out.stdout.split()[:2] == ["67584", str(kdn.ESIZE)]
+    got = out.stdout.split()
+    assert got[:2] == ["67584", str(kdn.ESIZE)]
+    assert int(got[2]) in (kdn.ENOTFOUND, kdn.EDEVICE)
+    assert int(got[3]) == C.sizeof(kdn.ArenaInfo)          # the binding's struct is the header's
+
+
+def test_arena_calls_check_their_arguments_before_any_device_work(lib):
+    info = kdn.ArenaInfo()
+    assert lib.kdn_arena_create(0, 0, C.byref(info)) == kdn.EINVAL           # no bytes
+    assert lib.kdn_arena_create(1 << 30, 3, C.byref(info)) == kdn.EINVAL     # granule not a power of two
+    assert lib.kdn_arena_create(1 << 30, 1024, C.byref(info)) == kdn.EINVAL  # granule above 512 MiB
+    p = C.c_void_p()
+    assert lib.kdn_arena_alloc(0, C.byref(p)) == kdn.EINVAL
+    assert lib.kdn_arena_alloc(4096, None) == kdn.EINVAL
+    assert lib.kdn_arena_free(None) == kdn.EINVAL
+    assert lib.kdn_arena_query(None) == kdn.EINVAL
+    # with no arena (or no device at all) nothing is handed out
+    assert lib.kdn_arena_alloc(4096, C.byref(p)) in (kdn.ENOTFOUND, kdn.EDEVICE) and not p.value
+    assert lib.kdn_arena_destroy() in (kdn.ENOTFOUND, kdn.EDEVICE)

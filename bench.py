@@ -52,9 +52,9 @@ FMT_IDS = {"raw": 0, "int8": 1, "int4": 2, "fp8": 3}
 # under profiles/ (the file named here), per workload; valid only for the library sources
 # they were taken with, whose fingerprint the library itself carries.
 COUNTER_TRAFFIC = {
-    "source_fingerprint": "f8eb94d3943926ed",
-    "70b_long": {"k_place_bytes_per_launch": 16276755546, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
-    "8b": {"k_place_bytes_per_launch": 814054503, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
+    "source_fingerprint": "2bd8412caa8435b9",
+    "70b_long": {"k_place_bytes_per_launch": 16276903127, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
+    "8b": {"k_place_bytes_per_launch": 814060527, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
 }
 
 
@@ -411,7 +411,7 @@ def workload_70b(args, dev):
     wall, ms = Timed(("store", "compose"), args.steps).run(step, args.warmup)
     bytes_call = T * (sh.paged_bytes_per_token + sh.stored_bytes_per_token(args.fmt))
     extra = {}
-    if ARENA is not None:       # the same two calls with the chunk in plain device memory, for the difference
+    if ARENA is not None and not args.only:     # the same two calls with the chunk in plain device memory, for the difference
         plain = kdn.alloc_chunk(cache, T, FMT_IDS[args.fmt])
         plain_slices = [plain.slice(i * 8192, 8192) for i in range(4)]
 
@@ -1041,8 +1041,8 @@ def main() -> int:
                              "host_stream_raw", "pool_trace", "pool_trace_tiered", "sweep", "stream_probe"),
                     default="70b_long")
     ap.add_argument("--only", action="store_true",
-                    help="the named workload alone: the default run's shorter 8b and batched_reuse passes and the "
-                         "streaming yardstick are left out (for profiling)")
+                    help="the named workload alone: the default run's shorter 8b and batched_reuse passes, the "
+                         "streaming yardstick and the plain-memory comparison are left out (for profiling)")
     ap.add_argument("--fmt", choices=("int8", "int4", "fp8", "raw"), default="int8",
                     help="stored form used by the 8b and 70b_long workloads")
     ap.add_argument("--layout", choices=("planes", "kv_pair", "block_major"), default="planes",
@@ -1059,9 +1059,9 @@ def main() -> int:
     ap.add_argument("--pool-blocks", type=int, default=0,
                     help="blocks per (layer, side) plane of the paged pool, instead of --pool-gib")
     ap.add_argument("--chunk-memory", choices=("arena", "plain"), default="arena",
-                    help="where the stored chunks lie: in the library's arena, whose 16 MiB granules alternate "
-                         "between the regions of the device memory (created first, before the pool), or in plain "
-                         "torch allocations")
+                    help="where the stored chunks lie: in the library's arena, whose neighbouring 16 MiB granules "
+                         "lie far apart in the device memory (created first, before the pool), or in plain torch "
+                         "allocations")
     ap.add_argument("--arena-gib", type=float, default=24.0, help="size of the arena")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=8, help="oracle steps of the 8b workload's CPU baseline")
@@ -1144,8 +1144,9 @@ def main() -> int:
     out.update(body)
     out["library"] = kdn.kdn_version()
     if ARENA is not None:
-        out["arena"] = dict(ARENA, what="stored chunks lie in kdn_arena memory: granules taken in turn from the "
-                                        "regions of the device memory that kdn_arena_create found by measurement")
+        out["arena"] = dict(ARENA, what="stored chunks lie in kdn_arena memory: granule i is free granule (i * stride) "
+                                        "mod free_granules of the device memory in the driver's order; striped_gbs / "
+                                        "packed_gbs: scattered tile writes over 1 GiB of it / of memory in that order")
     if out["roofline"]["traffic"] is not None:
         out["roofline"]["traffic_from"] = COUNTER_TRAFFIC[args.workload]["profile"]
     del res

@@ -1,6 +1,6 @@
 // The striped device arena of kdn_arena.h: host code over HIP's virtual memory calls; the
 // only device work is the library's own bandwidth yardstick (kdn_probe_stream), used to
-// find the memory's regions.
+// report what the striping gained.
 #include "kdn_arena.h"
 
 #include <hip/hip_runtime.h>
@@ -10,6 +10,7 @@
 #include <cstring>
 #include <map>
 #include <mutex>
+#include <numeric>
 #include <random>
 #include <utility>
 #include <vector>
@@ -19,13 +20,12 @@ namespace {
 using Handle = hipMemGenericAllocationHandle_t;
 
 constexpr size_t kMiB = (size_t)1 << 20, kGiB = (size_t)1 << 30;
-constexpr size_t kSideBytes = 512 * kMiB;  // a timed pair is two runs of this size, mapped side by side
-constexpr size_t kRunBytes = kGiB;         // the unit of the bisection: a region boundary is found to within one
 constexpr int32_t kTileKib = 32;           // the tile of the Llama shapes at block size 16
-constexpr uint32_t kProbeTiles = 16384;    // tiles written per launch: half of the pair's tiles, drawn at random
-constexpr size_t kMargin = 2 * kGiB;       // left free while the regions are measured
-constexpr double kSameFactor = 1.12;       // a pair slower than this times the same-region rate lies in one region
-                                           // (measured: 5.0 TB/s inside one region, 6.2 and more across two)
+constexpr size_t kTileBytes = (size_t)kTileKib << 10;
+constexpr size_t kWindowMax = kGiB;        // the rates are measured over at most this much
+constexpr size_t kWindowMin = 64 * kMiB;   // and not at all on an arena smaller than this
+constexpr size_t kMargin = 2 * kGiB;       // left free while the granules are held
+constexpr double kGolden = 0.3819660112501051; // 2 - golden ratio: the stride, as a share of the free granules
 constexpr size_t kAlign = 4096;
 
 struct Arena {
@@ -45,82 +45,53 @@ double now()
     return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
 }
 
-// Times scattered tile writes over two runs of granules mapped side by side.
+// Scattered tile writes over a mapped window, timed: half of the window's tiles, drawn at
+// random, each written once per launch from a source that is read in order.
 struct Prober {
-    size_t granule = 0;
-    size_t per_side = 0;                  // granules per run
-    const std::vector<Handle> *h = nullptr;
-    hipMemAccessDesc access{};
-    void *window = nullptr;               // 2 * kSideBytes of reserved addresses
-    void *src = nullptr;                  // kProbeTiles half tiles, read in order
-    int32_t *ids = nullptr;               // kProbeTiles distinct tiles of the window
+    size_t window = 0;                    // bytes
+    uint32_t tiles = 0;
+    void *src = nullptr;
+    int32_t *ids = nullptr;
     hipEvent_t t0 = nullptr, t1 = nullptr;
-    int probes = 0;
-    bool failed = false;
 
-    bool setup(size_t g, const std::vector<Handle> *handles, int device)
+    bool setup(size_t window_bytes)
     {
-        granule = g;
-        per_side = kSideBytes / g;
-        h = handles;
-        access.location.type = hipMemLocationTypeDevice;
-        access.location.id = device;
-        access.flags = hipMemAccessFlagsProtReadWrite;
-        std::vector<int32_t> perm(2 * kSideBytes / ((size_t)kTileKib << 10));
-        for (size_t i = 0; i < perm.size(); ++i)
-            perm[i] = (int32_t)i;
+        window = window_bytes;
+        const size_t all = window / kTileBytes;
+        tiles = (uint32_t)(all / 2);
+        std::vector<int32_t> perm(all);
+        std::iota(perm.begin(), perm.end(), 0);
         std::mt19937_64 rng(20240913);
-        for (size_t i = perm.size() - 1; i > 0; --i)
+        for (size_t i = all - 1; i > 0; --i)
             std::swap(perm[i], perm[rng() % (i + 1)]);
-        const size_t src_bytes = (size_t)kProbeTiles * ((size_t)kTileKib << 9);
+        const size_t src_bytes = (size_t)tiles * (kTileBytes / 2);
         return hipMalloc(&src, src_bytes) == hipSuccess && hipMemset(src, 0x3c, src_bytes) == hipSuccess
-               && hipMalloc(reinterpret_cast<void **>(&ids), kProbeTiles * sizeof(int32_t)) == hipSuccess
-               && hipMemcpy(ids, perm.data(), kProbeTiles * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess
-               && hipEventCreate(&t0) == hipSuccess && hipEventCreate(&t1) == hipSuccess
-               && hipMemAddressReserve(&window, 2 * kSideBytes, 0, nullptr, 0) == hipSuccess;
+               && hipMalloc(reinterpret_cast<void **>(&ids), tiles * sizeof(int32_t)) == hipSuccess
+               && hipMemcpy(ids, perm.data(), tiles * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess
+               && hipEventCreate(&t0) == hipSuccess && hipEventCreate(&t1) == hipSuccess;
     }
 
-    // GB/s of algorithmic bytes over granules [g0, g0 + per_side) and [g1, g1 + per_side); 0 after a failure
-    double rate(size_t g0, size_t g1)
+    // GB/s of algorithmic bytes (16 KiB read and 32 KiB written per tile); 0 after a failure.
+    // Returns with the device idle, so the caller may unmap the window.
+    double rate(void *mapped)
     {
-        if (failed)
-            return 0.0;
-        char *base = static_cast<char *>(window);
-        size_t mapped = 0;
-        bool ok = true;
-        for (size_t i = 0; ok && i < 2 * per_side; ++i) {
-            const Handle x = (*h)[i < per_side ? g0 + i : g1 + (i - per_side)];
-            ok = hipMemMap(base + i * granule, granule, 0, x, 0) == hipSuccess;
-            mapped += ok;
-        }
-        ok = ok && hipMemSetAccess(window, 2 * kSideBytes, &access, 1) == hipSuccess;
+        constexpr int kTimed = 4;
+        bool ok = kdn_probe_stream(src, mapped, ids, tiles, kTileKib, 0, 0, nullptr) == KDN_OK
+                  && hipEventRecord(t0, nullptr) == hipSuccess;
+        for (int r = 0; ok && r < kTimed; ++r)
+            ok = kdn_probe_stream(src, mapped, ids, tiles, kTileKib, 0, 0, nullptr) == KDN_OK;
+        ok = ok && hipEventRecord(t1, nullptr) == hipSuccess;
         float ms = 0.0f;
-        if (ok) {
-            constexpr int kTimed = 3;
-            ok = kdn_probe_stream(src, window, ids, kProbeTiles, kTileKib, 0, 0, nullptr) == KDN_OK
-                 && hipEventRecord(t0, nullptr) == hipSuccess;
-            for (int r = 0; ok && r < kTimed; ++r)
-                ok = kdn_probe_stream(src, window, ids, kProbeTiles, kTileKib, 0, 0, nullptr) == KDN_OK;
-            ok = ok && hipEventRecord(t1, nullptr) == hipSuccess;
-            // the window is not unmapped under running work, whatever failed above
-            ok = (hipDeviceSynchronize() == hipSuccess) && ok && hipEventElapsedTime(&ms, t0, t1) == hipSuccess;
-            ms /= kTimed;
-        }
-        for (size_t i = 0; i < mapped; ++i)
-            ok = (hipMemUnmap(base + i * granule, granule) == hipSuccess) && ok;
-        ++probes;
+        ok = (hipDeviceSynchronize() == hipSuccess) && ok && hipEventElapsedTime(&ms, t0, t1) == hipSuccess;
         if (!ok || !(ms > 0.0f)) {
             (void)hipGetLastError();
-            failed = true;
             return 0.0;
         }
-        return kProbeTiles * ((size_t)kTileKib << 10) * 1.5 / (ms * 1e6);
+        return (double)tiles * kTileBytes * 1.5 / (ms / kTimed * 1e6);
     }
 
     void teardown()
     {
-        if (window)
-            (void)hipMemAddressFree(window, 2 * kSideBytes);
         if (t0)
             (void)hipEventDestroy(t0);
         if (t1)
@@ -129,70 +100,11 @@ struct Prober {
             (void)hipFree(ids);
         if (src)
             (void)hipFree(src);
-        window = src = nullptr;
+        src = nullptr;
         ids = nullptr;
         t0 = t1 = nullptr;
     }
 };
-
-struct Region {
-    size_t first, last; // runs of kRunBytes, inclusive
-};
-
-// The regions along the allocation order.  Region membership is taken to be monotone along
-// it (a region is one stretch of runs), which the caller checks afterwards on other runs.
-std::vector<Region> find_regions(Prober &p, size_t n_runs, size_t run, kdn_arena_info &info)
-{
-    std::vector<Region> out;
-    const double base = p.rate(0, p.per_side); // the two halves of the first run
-    if (p.failed)
-        return out;
-    info.same_region_gbs = (float)base;
-    const double limit = kSameFactor * base;
-    auto same = [&](size_t ref, size_t r) { return p.rate(ref * run, r * run) < limit; };
-    size_t ref = 0;
-    while (ref + 1 < n_runs && out.size() < KDN_ARENA_MAX_REGIONS && !p.failed) {
-        size_t lo = ref, hi = n_runs - 1; // same(ref, lo) holds
-        if (same(ref, hi))
-            lo = hi;
-        while (lo + 1 < hi && !p.failed) {
-            const size_t mid = lo + (hi - lo) / 2;
-            if (same(ref, mid))
-                lo = mid;
-            else
-                hi = mid;
-        }
-        out.push_back({ref, lo});
-        ref = lo + 2; // the run after a region's last one may lie across the boundary
-    }
-    if (p.failed)
-        out.clear();
-    return out;
-}
-
-// Runs that the bisection did not start from: one third and two thirds into each region.
-bool check_regions(Prober &p, const std::vector<Region> &regions, size_t run, kdn_arena_info &info)
-{
-    const double limit = kSameFactor * info.same_region_gbs;
-    double lowest_cross = 0.0;
-    std::vector<std::pair<size_t, size_t>> at;
-    for (const Region &r : regions) {
-        const size_t len = r.last - r.first + 1;
-        at.push_back({r.first + len / 3, r.first + (2 * len) / 3});
-    }
-    for (size_t i = 0; i < regions.size(); ++i) {
-        if (at[i].first != at[i].second && !(p.rate(at[i].first * run, at[i].second * run) < limit))
-            return false;
-        for (size_t j = i + 1; j < regions.size(); ++j) {
-            const double x = p.rate(at[i].first * run, at[j].second * run);
-            if (!(x >= limit))
-                return false;
-            lowest_cross = lowest_cross == 0.0 ? x : std::min(lowest_cross, x);
-        }
-    }
-    info.cross_region_gbs = (float)lowest_cross;
-    return !p.failed;
-}
 
 void release_all(std::vector<Handle> &h, const std::vector<char> *keep = nullptr)
 {
@@ -240,6 +152,9 @@ kdn_status kdn_arena_create(uint64_t bytes, int32_t granule_mib, kdn_arena_info 
     prop.type = hipMemAllocationTypePinned;
     prop.location.type = hipMemLocationTypeDevice;
     prop.location.id = device;
+    hipMemAccessDesc access{};
+    access.location = prop.location;
+    access.flags = hipMemAccessFlagsProtReadWrite;
     size_t min_granule = 0, free_b = 0, total_b = 0;
     if (hipMemGetAllocationGranularity(&min_granule, &prop, hipMemAllocationGranularityRecommended) != hipSuccess
         || min_granule == 0 || hipMemGetInfo(&free_b, &total_b) != hipSuccess) {
@@ -258,13 +173,11 @@ kdn_status kdn_arena_create(uint64_t bytes, int32_t granule_mib, kdn_arena_info 
     a.granule = G;
     a.info.bytes = a.bytes;
     a.info.granule = G;
-    a.info.regions = 1;
 
-    // what the measurement needs is taken before the free memory is
-    std::vector<Handle> h;
+    // the measuring buffers are taken before the free memory is
+    const size_t window = std::min(kWindowMax, a.bytes) / G * G;
     Prober p;
-    const size_t run = kRunBytes / G;
-    bool measure = p.setup(G, &h, device);
+    bool measure = window >= kWindowMin && window % kTileBytes == 0 && p.setup(window);
     if (!measure) {
         (void)hipGetLastError();
         p.teardown();
@@ -274,7 +187,10 @@ kdn_status kdn_arena_create(uint64_t bytes, int32_t granule_mib, kdn_arena_info 
         p.teardown();
         return KDN_ESIZE;
     }
-    const size_t take = measure ? (free_b - kMargin) / G : n;
+
+    // every free granule, in the order the driver hands them out
+    std::vector<Handle> h;
+    const size_t take = (free_b - kMargin) / G;
     h.reserve(take);
     for (size_t i = 0; i < take; ++i) {
         Handle x;
@@ -284,67 +200,28 @@ kdn_status kdn_arena_create(uint64_t bytes, int32_t granule_mib, kdn_arena_info 
         }
         h.push_back(x);
     }
-    if (h.size() < n) {
+    const size_t N = h.size();
+    if (N < n) {
         release_all(h);
         p.teardown();
         return KDN_ESIZE;
     }
 
-    // regions, as lists of granules in allocation order
-    std::vector<std::vector<size_t>> by;
-    const size_t n_runs = h.size() / run;
-    if (measure && n_runs >= 4) {
-        std::vector<Region> regions = find_regions(p, n_runs, run, a.info);
-        // a stretch of a few runs between two boundaries is no region to stripe over
-        regions.erase(std::remove_if(regions.begin(), regions.end(),
-                                     [&](const Region &r) { return (r.last - r.first + 1) * 10 < n_runs; }),
-                      regions.end());
-        if (regions.size() >= 2 && check_regions(p, regions, run, a.info)) {
-            a.info.verified = 1;
-            a.info.regions = (int32_t)regions.size();
-            for (size_t i = 0; i < regions.size(); ++i) {
-                by.emplace_back();
-                for (size_t g = regions[i].first * run; g < (regions[i].last + 1) * run; ++g)
-                    by.back().push_back(g);
-                a.info.region_bytes[i] = by.back().size() * G;
-            }
-        } else if (regions.size() == 1 && !p.failed) {
-            a.info.verified = 1; // one region is all that is free
-        }
+    // granule i of the arena is free granule (i * stride) mod N: neighbours in the arena lie
+    // 0.38 of the free memory apart, and no granule is taken twice because the stride shares
+    // no factor with N
+    size_t stride = std::max<size_t>(1, (size_t)(kGolden * (double)N));
+    while (std::gcd(stride, N) != 1)
+        ++stride;
+    std::vector<char> taken(N, 0);
+    a.handles.reserve(n);
+    for (size_t i = 0; i < n; ++i) {
+        const size_t g = (size_t)(((unsigned __int128)i * stride) % N);
+        taken[g] = 1;
+        a.handles.push_back(h[g]);
     }
-    a.info.probes = p.probes;
-    p.teardown();
-    std::vector<char> taken(h.size(), 0);
-    if (by.empty()) {
-        a.info.regions = 1;
-        a.info.cross_region_gbs = 0.0f;
-        std::memset(a.info.region_bytes, 0, sizeof a.info.region_bytes);
-        a.info.region_bytes[0] = h.size() * G;
-    }
-
-    // granule i of the arena comes from region i mod R; a region that runs out is passed over,
-    // and what no region holds is taken from the granules left over, in order
-    std::vector<size_t> order;
-    order.reserve(n);
-    {
-        std::vector<size_t> next(by.size(), 0);
-        size_t exhausted = 0, turn = 0;
-        while (order.size() < n && exhausted < by.size()) {
-            const size_t r = turn++ % by.size();
-            if (next[r] < by[r].size()) {
-                order.push_back(by[r][next[r]++]);
-                taken[order.back()] = 1;
-                if (next[r] == by[r].size())
-                    ++exhausted;
-            }
-        }
-        for (size_t g = 0; g < h.size() && order.size() < n; ++g)
-            if (!taken[g]) {
-                order.push_back(g);
-                taken[g] = 1;
-            }
-    }
-    release_all(h, &taken);
+    a.info.free_granules = N;
+    a.info.stride = stride;
 
     kdn_status rc = KDN_OK;
     size_t mapped = 0;
@@ -353,31 +230,52 @@ kdn_status kdn_arena_create(uint64_t bytes, int32_t granule_mib, kdn_arena_info 
         rc = KDN_EDEVICE;
     }
     for (size_t i = 0; rc == KDN_OK && i < n; ++i) {
-        if (hipMemMap(static_cast<char *>(a.va) + i * G, G, 0, h[order[i]], 0) != hipSuccess)
+        if (hipMemMap(static_cast<char *>(a.va) + i * G, G, 0, a.handles[i], 0) != hipSuccess)
             rc = KDN_EDEVICE;
         else
             ++mapped;
     }
-    if (rc == KDN_OK) {
-        hipMemAccessDesc access{};
-        access.location = prop.location;
-        access.flags = hipMemAccessFlagsProtReadWrite;
-        if (hipMemSetAccess(a.va, a.bytes, &access, 1) != hipSuccess)
-            rc = KDN_EDEVICE;
-    }
+    if (rc == KDN_OK && hipMemSetAccess(a.va, a.bytes, &access, 1) != hipSuccess)
+        rc = KDN_EDEVICE;
     if (rc != KDN_OK) {
         (void)hipGetLastError();
         for (size_t i = 0; i < mapped; ++i)
             (void)hipMemUnmap(static_cast<char *>(a.va) + i * G, G);
         if (a.va)
             (void)hipMemAddressFree(a.va, a.bytes);
-        for (size_t g : order)
-            (void)hipMemRelease(h[g]);
+        release_all(h);
+        p.teardown();
         return rc;
     }
-    a.handles.reserve(n);
-    for (size_t g : order)
-        a.handles.push_back(h[g]);
+
+    // what the striping gained, for the record: the same scattered writes over the head of the
+    // arena and over as many granules that follow one another in the driver's order
+    if (measure) {
+        a.info.striped_gbs = (float)p.rate(a.va);
+        std::vector<size_t> run; // the first untaken granules, in the driver's order
+        const size_t want = window / G;
+        for (size_t g = 0; g < N && run.size() < want; ++g)
+            if (!taken[g])
+                run.push_back(g);
+        void *w = nullptr;
+        if (run.size() == want && hipMemAddressReserve(&w, window, 0, nullptr, 0) == hipSuccess) {
+            size_t m = 0;
+            bool ok = true;
+            for (; ok && m < want; ++m)
+                ok = hipMemMap(static_cast<char *>(w) + m * G, G, 0, h[run[m]], 0) == hipSuccess;
+            if (!ok)
+                --m;
+            if (ok && hipMemSetAccess(w, window, &access, 1) == hipSuccess)
+                a.info.packed_gbs = (float)p.rate(w);
+            for (size_t i = 0; i < m; ++i)
+                (void)hipMemUnmap(static_cast<char *>(w) + i * G, G);
+            (void)hipMemAddressFree(w, window);
+        }
+        (void)hipGetLastError();
+    }
+    p.teardown();
+    release_all(h, &taken);
+
     a.free_at[0] = a.bytes;
     a.info.seconds = (float)(now() - t_start);
     if (info_out)

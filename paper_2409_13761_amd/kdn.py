@@ -59,16 +59,14 @@ class LaunchOpts(C.Structure):
 
 class ArenaInfo(C.Structure):
     _fields_ = [("bytes", C.c_uint64), ("granule", C.c_uint64), ("in_use", C.c_uint64), ("largest_free", C.c_uint64),
-                ("regions", C.c_int32), ("verified", C.c_int32), ("region_bytes", C.c_uint64 * 8),
-                ("same_region_gbs", C.c_float), ("cross_region_gbs", C.c_float), ("seconds", C.c_float),
-                ("probes", C.c_int32)]
+                ("free_granules", C.c_uint64), ("stride", C.c_uint64), ("striped_gbs", C.c_float),
+                ("packed_gbs", C.c_float), ("seconds", C.c_float), ("reserved", C.c_int32)]
 
     def as_dict(self) -> dict:
         return {"bytes": self.bytes, "granule": self.granule, "in_use": self.in_use, "largest_free": self.largest_free,
-                "regions": self.regions, "verified": self.verified,
-                "region_gib": [round(b / 2**30, 1) for b in list(self.region_bytes)[:max(self.regions, 1)]],
-                "same_region_gbs": round(self.same_region_gbs, 1), "cross_region_gbs": round(self.cross_region_gbs, 1),
-                "seconds": round(self.seconds, 3), "probes": self.probes}
+                "free_granules": self.free_granules, "stride": self.stride,
+                "striped_gbs": round(self.striped_gbs, 1), "packed_gbs": round(self.packed_gbs, 1),
+                "seconds": round(self.seconds, 3)}
 
 
 class PoolStats(C.Structure):

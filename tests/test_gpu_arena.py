@@ -1,6 +1,7 @@
 """The striped device arena on the GPU: what kdn_arena_create reports, the block list, and
 store / load / compose on chunks and a paged pool cut from it, against the oracle."""
 import gc
+import math
 
 import numpy as np
 import pytest
@@ -24,10 +25,10 @@ def arena():
     torch.zeros(1, device="cuda")
     print("[arena] creating %d bytes" % ARENA_BYTES, flush=True)
     info = kdn.kdn_arena_create(ARENA_BYTES)
-    notes.note("[arena] %d regions (%s GiB free in each), verified %d, same-region %.0f GB/s, lowest cross-region "
-               "%.0f GB/s, %d probes, created in %.2f s" % (info["regions"], info["region_gib"], info["verified"],
-                                                          info["same_region_gbs"], info["cross_region_gbs"],
-                                                          info["probes"], info["seconds"]))
+    notes.note("[arena] %d granules of %d MiB drawn with stride %d from %d free ones; scattered tile writes over the "
+               "first GiB %.0f GB/s, over as much memory in the driver's order %.0f GB/s; created in %.2f s"
+               % (info["bytes"] // info["granule"], info["granule"] >> 20, info["stride"], info["free_granules"],
+                  info["striped_gbs"], info["packed_gbs"], info["seconds"]))
     yield info
     gc.collect()
     torch.cuda.synchronize()
@@ -41,11 +42,12 @@ def test_what_create_reports_is_consistent(arena):
     g = 16 << 20
     assert arena["granule"] == g and arena["bytes"] == (ARENA_BYTES + g - 1) // g * g
     assert arena["in_use"] == 0 and arena["largest_free"] == arena["bytes"]
-    assert 1 <= arena["regions"] <= 8 and arena["seconds"] < 30
-    if arena["regions"] > 1:                                       # striped only over regions that were checked
-        assert arena["verified"] == 1 and arena["probes"] >= 4
-        assert arena["cross_region_gbs"] >= 1.12 * arena["same_region_gbs"] > 0
-        assert all(b > 0 for b in arena["region_gib"])
+    n, N, stride = arena["bytes"] // g, arena["free_granules"], arena["stride"]
+    assert N >= n and 0 < stride < N and math.gcd(stride, N) == 1      # no free granule is taken twice
+    assert abs(stride / N - 0.382) < 0.01 or N < 1000                  # neighbours lie 38% of the free memory apart
+    assert arena["seconds"] < 60
+    # both rates were measured and are rates of this device; which is higher is the bench's business
+    assert 1000 < arena["striped_gbs"] < 8000 and 1000 < arena["packed_gbs"] < 8000
     with pytest.raises(kdn.KdnError) as e:                         # one arena per device
         kdn.kdn_arena_create(GIB)
     assert e.value.status == kdn.EINVAL

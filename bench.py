@@ -52,9 +52,9 @@ FMT_IDS = {"raw": 0, "int8": 1, "int4": 2, "fp8": 3}
 # under profiles/ (the file named here), per workload; valid only for the library sources
 # they were taken with, whose fingerprint the library itself carries.
 COUNTER_TRAFFIC = {
-    "source_fingerprint": "2bd8412caa8435b9",
-    "70b_long": {"k_place_bytes_per_launch": 16276903127, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
-    "8b": {"k_place_bytes_per_launch": 814060527, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
+    "source_fingerprint": "898df68d98d3a243",
+    "70b_long": {"k_place_bytes_per_launch": 16277130567, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
+    "8b": {"k_place_bytes_per_launch": 814076058, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
 }
 
 
@@ -132,7 +132,8 @@ class Timed:
 
 
 def _probe_rate(kdn, torch, small, big, tiles, ids, tile_kib, direction, cap, reps):
-    """GB/s of kdn_probe_stream over rotating buffer sets (HIP events on the launch stream)."""
+    """GB/s of kdn_probe_stream over rotating buffer sets (HIP events on the launch stream).  Bytes per
+    tile: tile_kib of the big buffer, and half as much of the small one in directions 0 and 1."""
     sets = len(small)
     for i in range(sets):
         kdn.kdn_probe_stream(small[i], big[i], tiles, ids, tile_kib, direction, cap)
@@ -143,7 +144,8 @@ def _probe_rate(kdn, torch, small, big, tiles, ids, tile_kib, direction, cap, re
         kdn.kdn_probe_stream(small[i % sets], big[i % sets], tiles, ids, tile_kib, direction, cap)
     e1.record()
     torch.cuda.synchronize()
-    return tiles * tile_kib * 1536 / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
+    per_tile = tile_kib * (1536 if direction in (0, 1) else 1024)
+    return tiles * per_tile / (e0.elapsed_time(e1) / reps * 1e-3) / 1e9
 
 
 def stream_ceiling(dev, pool_gib):
@@ -173,6 +175,13 @@ def stream_ceiling(dev, pool_gib):
            "place_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, wide, 32, 0, 0, reps),
            "place_pattern_scattered_within_16GiB_GBps": _probe_rate(kdn, torch, small, big, tiles, narrow, 32, 0, 0, reps),
            "store_pattern_scattered_GBps": _probe_rate(kdn, torch, small, big, tiles, wide, 32, 1, 0, reps)}
+    # the two directions of the memory on their own, over the same big buffer (1.07 GB per launch)
+    out["one_direction_GBps"] = {
+        "read_in_order": _probe_rate(kdn, torch, small, big, tiles, None, 32, 3, 0, reps),
+        "read_scattered": _probe_rate(kdn, torch, small, big, tiles, wide, 32, 3, 0, reps),
+        "write_in_order": _probe_rate(kdn, torch, small, big, tiles, None, 32, 2, 0, reps),
+        "write_scattered": _probe_rate(kdn, torch, small, big, tiles, wide, 32, 2, 0, reps),
+        "write_scattered_within_16GiB": _probe_rate(kdn, torch, small, big, tiles, narrow, 32, 2, 0, reps)}
     if ARENA is not None:
         out["store_pattern_scattered_small_buffer_in_plain_memory_GBps"] = _probe_rate(kdn, torch, plain, big, tiles, wide,
                                                                                        32, 1, 0, reps)
@@ -237,7 +246,11 @@ def workload_stream_probe(args, dev):
         span_ids = torch.from_numpy(pool_ids[pick].astype(np.int32)).to(dev)
         spans.append({"tiles_drawn_from": what,
                       "place_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 0, 0, reps),
-                      "store_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 1, 0, reps)})
+                      "store_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 1, 0, reps),
+                      "write_only_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 2, 0, reps),
+                      "read_only_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 3, 0, reps)})
+    one_way = {"read_in_order_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, None, 32, 3, 0, reps),
+               "write_in_order_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, None, 32, 2, 0, reps)}
     del huge
     r32 = rows[2]
     ms = {"place_scattered": 1.5 * (1 << 30) / r32["place_scattered_GBps"] / 1e6}
@@ -250,7 +263,8 @@ def workload_stream_probe(args, dev):
                     "scattered, place-pattern row (no tokens are moved: value is 0)",
         "extra": {"by_tile_size": rows, "by_launch_width_at_32KiB_tiles": caps,
                   "by_scatter_window_at_32KiB_tiles": windows,
-                  "by_span_of_device_memory_at_32KiB_tiles": spans},
+                  "by_span_of_device_memory_at_32KiB_tiles": spans,
+                  "one_direction_in_order_at_32KiB_tiles": one_way},
         "traffic": None,
     }
 

@@ -429,9 +429,11 @@ kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t tabl
  * and compose: a workgroup reads tile i of small_dev and writes tile i of big_dev, or, with
  * tile_ids_dev [device, `tiles` distinct int32], tile tile_ids_dev[i] (destination tiles
  * scattered like the blocks of a random block table).  direction 1, the pattern of store: reads
- * that tile of big_dev, writes tile i of small_dev.  max_workgroups > 0 caps the launch (the
- * workgroups then stride over the tiles).  small_dev: [device] tiles * tile_kib/2 KiB; big_dev:
- * [device], holds every tile that is named.  Ids are not checked. */
+ * that tile of big_dev, writes tile i of small_dev.  direction 2 writes that tile of big_dev and
+ * reads nothing, direction 3 reads it and writes nothing (small_dev is then only a place the
+ * kernel could write to): the two directions of the memory on their own.  max_workgroups > 0 caps
+ * the launch (the workgroups then stride over the tiles).  small_dev: [device] tiles * tile_kib/2
+ * KiB; big_dev: [device], holds every tile that is named.  Ids are not checked. */
 kdn_status kdn_probe_stream(void *small_dev, void *big_dev, const int32_t *tile_ids_dev, uint32_t tiles,
                             int32_t tile_kib, int32_t direction, int32_t max_workgroups, void *stream);
 

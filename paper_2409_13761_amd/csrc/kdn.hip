@@ -820,7 +820,7 @@ kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t tabl
 kdn_status kdn_probe_stream(void *small_dev, void *big_dev, const int32_t *tile_ids_dev, uint32_t tiles,
                             int32_t tile_kib, int32_t direction, int32_t max_workgroups, void *stream)
 {
-    if (!small_dev || !big_dev || tiles == 0 || max_workgroups < 0 || (direction != 0 && direction != 1))
+    if (!small_dev || !big_dev || tiles == 0 || max_workgroups < 0 || direction < 0 || direction > 3)
         return KDN_EINVAL;
     if (tile_kib < 8 || tile_kib > 4096 || tile_kib % 8 != 0)
         return KDN_EINVAL;
@@ -831,14 +831,21 @@ kdn_status kdn_probe_stream(void *small_dev, void *big_dev, const int32_t *tile_
     hipStream_t hs = static_cast<hipStream_t>(stream);
     u32x4 *sm = static_cast<u32x4 *>(small_dev), *bg = static_cast<u32x4 *>(big_dev);
     const dim3 g(grid), b(kThreads);
-    if (direction == 0 && chunks == 4)
-        hipLaunchKernelGGL((k_probe_stream<0, 4>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
-    else if (direction == 0)
-        hipLaunchKernelGGL((k_probe_stream<0, 0>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
-    else if (chunks == 4)
-        hipLaunchKernelGGL((k_probe_stream<1, 4>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
-    else
-        hipLaunchKernelGGL((k_probe_stream<1, 0>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks);
+    const bool fixed = chunks == 4; // the 32 KiB tile has a kernel of its own with nothing predicated
+#define KDN_PROBE(DIR)                                                                                      \
+    case DIR:                                                                                               \
+        if (fixed)                                                                                          \
+            hipLaunchKernelGGL((k_probe_stream<DIR, 4>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks); \
+        else                                                                                                \
+            hipLaunchKernelGGL((k_probe_stream<DIR, 0>), g, b, 0, hs, sm, bg, tile_ids_dev, tiles, chunks); \
+        break;
+    switch (direction) {
+        KDN_PROBE(0)
+        KDN_PROBE(1)
+        KDN_PROBE(2)
+        KDN_PROBE(3)
+    }
+#undef KDN_PROBE
     return hip_status(hipGetLastError());
 }
 

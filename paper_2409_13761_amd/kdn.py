@@ -605,7 +605,8 @@ def kdn_probe_stream(small: torch.Tensor, big: torch.Tensor, tiles: int, tile_id
     """The streaming yardstick: per tile, tile_kib/2 KiB of `small` and tile_kib KiB of `big`
     (tile i of `small` with tile tile_ids[i] of `big` when ids are given; the ids are the caller's
     to keep inside `big`: nothing here reads them back, a call only enqueues).  direction 0 reads
-    `small` and writes `big` (load, compose), direction 1 the reverse (store)."""
+    `small` and writes `big` (load, compose), direction 1 the reverse (store), direction 2 only
+    writes `big`, direction 3 only reads it."""
     assert small.is_cuda and big.is_cuda and small.is_contiguous() and big.is_contiguous()
     assert small.numel() * small.element_size() >= tiles * tile_kib * 512
     if tile_ids is None:

@@ -975,8 +975,9 @@ def lib_store_to_host_with_device_chunk(dc, a, fmt, staging, layers_per_stage):
 def test_probe_stream_moves_the_bytes_it_is_timed_for(tile_kib, cap):
     """The yardstick kernel is only worth timing if it moves what it says: every tile of the
     small buffer lands in the tile of the big one that the id names (each 4 KiB run twice, the
-    second copy with one bit pattern flipped per 16 bytes), nothing else is written, and the
-    reverse direction folds the two copies back."""
+    second copy with one bit pattern flipped per 16 bytes), nothing else is written, the
+    reverse direction folds the two copies back, the write-only direction fills exactly the
+    named tiles and the read-only one changes nothing."""
     tiles = 37
     rng = np.random.default_rng(500 + tile_kib)
     ids_h = rng.permutation(64)[:tiles].astype(np.int32)
@@ -1003,6 +1004,25 @@ def test_probe_stream_moves_the_bytes_it_is_timed_for(tile_kib, cap):
     kdn.kdn_probe_stream(small, big, tiles, None, tile_kib, 0, cap)
     torch.cuda.synchronize()
     assert np.array_equal(big.cpu().numpy().reshape(64, tile_kib // 8, 2, 4096)[:tiles, :, 0], src)
-    with pytest.raises(kdn.KdnError) as e:
-        kdn.kdn_probe_stream(small, big, tiles, ids, 4, 0, 0)      # below the smallest tile
-    assert e.value.status == kdn.EINVAL
+    # write only: every named tile holds (tile, 4 KiB run, lane, mark) per 16 bytes, the others are untouched
+    big.fill_(0xA5)
+    keep = small.clone()
+    kdn.kdn_probe_stream(small, big, tiles, ids, tile_kib, 2, cap)
+    torch.cuda.synchronize()
+    got = big.cpu().numpy().reshape(64, tile_kib // 4, 256, 16)
+    want = np.empty((tiles, tile_kib // 4, 256, 4), dtype=np.uint32)
+    want[..., 0] = ids_h[:, None, None]
+    want[..., 1] = np.arange(tile_kib // 4)[None, :, None]
+    want[..., 2] = np.arange(256)[None, None, :]
+    want[..., 3] = 0x4B444E21
+    assert np.array_equal(got[ids_h].view(np.uint32).reshape(want.shape), want)
+    assert np.all(got[untouched] == 0xA5) and torch.equal(small, keep)
+    # read only: nothing changes anywhere
+    before = big.clone()
+    kdn.kdn_probe_stream(small, big, tiles, ids, tile_kib, 3, cap)
+    torch.cuda.synchronize()
+    assert torch.equal(big, before) and torch.equal(small, keep)
+    for bad_tile, bad_dir in ((4, 0), (tile_kib, 4), (tile_kib, -1)):   # below the smallest tile; no such direction
+        with pytest.raises(kdn.KdnError) as e:
+            kdn.kdn_probe_stream(small, big, tiles, ids, bad_tile, bad_dir, 0)
+        assert e.value.status == kdn.EINVAL

@@ -55,6 +55,7 @@ COUNTER_TRAFFIC = {
     "source_fingerprint": "898df68d98d3a243",
     "70b_long": {"k_place_bytes_per_launch": 16277130567, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
     "8b": {"k_place_bytes_per_launch": 814076058, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
+    "batched_reuse": {"k_place_bytes_per_launch": 0, "profile": "profiles/k_place_batched_reuse_64req.md"},
 }
 
 
@@ -516,7 +517,8 @@ def workload_batched(args, dev):
                   "bytes_counted": "each distinct chunk read once + every destination row written",
                   "bytes_if_every_draw_were_read_from_hbm": naive,
                   "GBps_if_every_draw_were_read_from_hbm": naive / (ms["compose_batch"] * 1e-3) / 1e9},
-        "traffic": None,
+        "traffic": counter_traffic("batched_reuse") if not args.pool_blocks and args.pool_gib == POOL_GIB_DEFAULT
+        else None,
     }
 
 
@@ -1186,6 +1188,8 @@ def main() -> int:
             a2.steps, a2.warmup = defaults_of[name]
             r2 = runners[name](a2, dev)
             others[name] = summarise(r2, a2.steps, a2.warmup, fmt_note(name))
+            if others[name]["roofline"]["traffic"] is not None:
+                others[name]["roofline"]["traffic_from"] = COUNTER_TRAFFIC[name]["profile"]
             del r2
             gc.collect()
             torch.cuda.empty_cache()

@@ -306,7 +306,13 @@ kdn_status kdn_compose_batch_rope(const kdn_request *requests, int32_t n_request
  * beyond the request and chunk records).  One record per chunk view, in the order the
  * kernels take them: grouped by stored form (one launch per form present, `launch`
  * counts them), and, when there is more than one request, views of the same stored rows
- * next to each other.  dest_token is the request token that receives the view's first
+ * next to each other.  Views that are exactly the same stored rows (same buffer, same token
+ * range) and whose destinations are congruent modulo the tile's token count (16, or the
+ * block size when that is no multiple of 16) are read once: the first such view has
+ * workgroups of its own, each later one names in `follows` the record it is chained behind
+ * (the workgroup that read a tile for that record places it for this one next, out of the
+ * caches), and chained records come after all records with workgroups in their launch.
+ * dest_token is the request token that receives the view's first
  * row: dest_token_start plus the token counts of the views before it in its request.
  * shares_rows is 1 when some stored rows are read by more than one view of that launch
  * (the kernels then keep them in the cache hierarchy).  Argument checks and status
@@ -320,6 +326,7 @@ typedef struct kdn_placement {
     int32_t num_tokens;
     int32_t offset;         /* RoPE position delta of the view */
     int32_t shares_rows;
+    int32_t follows;        /* index in `out` of the record this view is chained behind, -1: none */
 } kdn_placement;
 kdn_status kdn_compose_plan(const kdn_request *requests, int32_t n_requests, const kdn_cache_desc *cache,
                             kdn_placement *out, int32_t cap, int32_t *n_out);

@@ -409,7 +409,7 @@ kdn_status kdn_compose_batch_static(const kdn_request *requests, int32_t n_reque
         std::vector<Seg> segs(all.begin() + (long)first[f], all.begin() + (long)(first[f] + plan.segs[f].size()));
         p.reuse = plan.reuse[f];
         st = place_segments(ds, p, f, segs, hs, 0,
-                            reinterpret_cast<const Seg *>(scratch + kStaticRopeBytes) + first[f]);
+                            reinterpret_cast<const Seg *>(scratch + kStaticRopeBytes) + first[f], plan.heads[f]);
         if (st != KDN_OK)
             return st;
     }
@@ -449,8 +449,10 @@ kdn_status kdn_compose_plan(const kdn_request *requests, int32_t n_requests, con
     size_t k = 0;
     int32_t launch = 0;
     for (int f = 0; f < kFormats; ++f) {
+        const size_t base = k; // `follows` counts within a launch; the output numbers all records
         for (const PlannedSeg &ps : plan.segs[f])
-            out[k++] = {ps.request, ps.chunk, f, launch, ps.seg.S, ps.seg.T, ps.offset, plan.reuse[f]};
+            out[k++] = {ps.request, ps.chunk, f, launch, ps.seg.S, ps.seg.T, ps.offset, plan.reuse[f],
+                        ps.follows < 0 ? -1 : (int32_t)(base + (size_t)ps.follows)};
         launch += plan.segs[f].empty() ? 0 : 1;
     }
     return KDN_OK;
@@ -681,7 +683,7 @@ static kdn_status compose_from_host_impl(const kdn_chunk *chunks, const int32_t 
             s.T = ch.num_tokens;
             s.S = S;
             s.rope_row = rows[i];
-            s.pad = 0;
+            s.next = 0;
             segs[ch.fmt].push_back(s);
             S += ch.num_tokens;
         }

@@ -44,7 +44,9 @@ struct Seg {
     const int32_t *bt;
     int32_t Tp, tok0, T, S;
     int32_t rope_row; // row of the cos/sin table, -1: no rotation
-    int32_t pad;
+    int32_t next;     // record of another view of exactly these stored rows, placed by the same workgroups
+                      // right after this one (its tiles cut the rows the same way); 0: none (record 0
+                      // always has workgroups of its own)
 };
 static_assert(sizeof(Seg) == 40, "Seg layout");
 
@@ -398,8 +400,8 @@ __device__ __forceinline__ T load_stored(const uint8_t *ptr)
 // its upper half (half-split: these pair up; interleaved: each vector holds 4 neighbouring
 // pairs of its own); the part behind the rotary one is split into halves the same way and
 // never rotates.
-template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE, typename Segs>
-__device__ __forceinline__ void place_tile(const PlaceP &p, const Segs &segs, const uint32_t bx)
+template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE>
+__device__ __forceinline__ void place_tile(const PlaceP &p, const Seg &sg, const uint32_t bx)
 {
     constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 2 : 4;
     constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT4_GROUP32 ? 1 : 2; // 32-bit words per 8 stored elements
@@ -413,7 +415,6 @@ __device__ __forceinline__ void place_tile(const PlaceP &p, const Segs &segs, co
     const int L2 = 2 * p.c.L;
     const int NT = blockDim.x; // a small tile is launched with fewer wavefronts
 
-    const Seg &sg = segs.at(blockIdx.y);
     const int S = sg.S, T = sg.T;
     const int piece = bx / L2;
     const int ls = bx - piece * L2;
@@ -604,16 +605,27 @@ __device__ __forceinline__ void place_tile(const PlaceP &p, const Segs &segs, co
     }
 }
 
-// One workgroup per tile, or fewer workgroups striding over the tiles (see k_store).  The
-// barrier between tiles keeps a fast wavefront from restaging the cos/sin row while a slow
-// one still reads the previous tile's.
+// One workgroup per tile, or fewer workgroups striding over the tiles (see k_store).  A row
+// of the grid (blockIdx.y) is a view with workgroups of its own; the views chained behind it
+// (Seg::next) read exactly the same stored rows, so the workgroup that has just read a tile
+// places it again for each of them, through the caches, before it moves on: a chunk that
+// many requests of a batch draw crosses the memory interface once.  The barrier between
+// tiles keeps a fast wavefront from restaging the cos/sin row while a slow one still reads
+// the previous tile's.
 template <int DT, int FMT, bool DENSE, bool VAR, bool REUSE, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place(PlaceP p, Segs segs)
 {
-    place_tile<DT, FMT, DENSE, VAR, REUSE, Segs>(p, segs, blockIdx.x); // the common launch ends here
-    for (uint32_t bx = blockIdx.x + gridDim.x; bx < p.tiles_x; bx += gridDim.x) {
-        __syncthreads();
-        place_tile<DT, FMT, DENSE, VAR, REUSE, Segs>(p, segs, bx);
+    bool first = true;
+    for (uint32_t bx = blockIdx.x; bx < p.tiles_x; bx += gridDim.x) { // the common launch has one tile per workgroup
+        int at = blockIdx.y;
+        do {
+            if (!first)
+                __syncthreads();
+            first = false;
+            const Seg &sg = segs.at(at);
+            place_tile<DT, FMT, DENSE, VAR, REUSE>(p, sg, bx);
+            at = sg.next;
+        } while (at != 0);
     }
 }
 
@@ -646,8 +658,8 @@ __device__ __forceinline__ void dequantise8(const uint32_t *w, float scale, floa
 // Interleaved pairs lie inside a lane's own 8 elements.  All lanes stay active through
 // the exchange; loads and stores are predicated instead.
 // Grid as k_place.
-template <int DT, int FMT, bool DENSE, bool REUSE, typename Segs>
-__device__ __forceinline__ void place_tile_c(const PlaceP &p, const Segs &segs, const uint32_t bx)
+template <int DT, int FMT, bool DENSE, bool REUSE>
+__device__ __forceinline__ void place_tile_c(const PlaceP &p, const Seg &sg, const uint32_t bx)
 {
     constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 4 : 8;
     constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT4_GROUP32 ? 1 : 2; // words per 8 stored elements
@@ -658,7 +670,6 @@ __device__ __forceinline__ void place_tile_c(const PlaceP &p, const Segs &segs, 
     const int L2 = 2 * p.c.L;
     const int NT = blockDim.x; // a small tile is launched with fewer wavefronts
 
-    const Seg &sg = segs.at(blockIdx.y);
     const int S = sg.S, T = sg.T;
     const int piece = bx / L2;
     const int ls = bx - piece * L2;
@@ -812,13 +823,21 @@ __device__ __forceinline__ void place_tile_c(const PlaceP &p, const Segs &segs, 
     }
 }
 
+// Grid rows, chained views and the barrier as in k_place.
 template <int DT, int FMT, bool DENSE, bool REUSE, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
 {
-    place_tile_c<DT, FMT, DENSE, REUSE, Segs>(p, segs, blockIdx.x);
-    for (uint32_t bx = blockIdx.x + gridDim.x; bx < p.tiles_x; bx += gridDim.x) {
-        __syncthreads();
-        place_tile_c<DT, FMT, DENSE, REUSE, Segs>(p, segs, bx);
+    bool first = true;
+    for (uint32_t bx = blockIdx.x; bx < p.tiles_x; bx += gridDim.x) { // the common launch has one tile per workgroup
+        int at = blockIdx.y;
+        do {
+            if (!first)
+                __syncthreads();
+            first = false;
+            const Seg &sg = segs.at(at);
+            place_tile_c<DT, FMT, DENSE, REUSE>(p, sg, bx);
+            at = sg.next;
+        } while (at != 0);
     }
 }
 

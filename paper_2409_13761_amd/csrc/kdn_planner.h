@@ -9,6 +9,8 @@
 #include <cstring>
 #include <mutex>
 #include <unordered_map>
+#include <map>
+#include <tuple>
 #include <vector>
 
 #include "kdn_kernels.h"
@@ -502,13 +504,21 @@ void launch_place_d(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs
 // max_workgroups > 0 caps the launch; the workgroups then stride over the tiles.
 // resident: the same records already in device memory (the caller put them there on `st`);
 // the kernel then reads them from there and nothing is copied or allocated here.
+// heads: the first `heads` records get workgroups of their own (a row of the grid each); the
+// others are reached through the `next` links of the records before them (0 = all of them).
 inline kdn_status place_segments(DeviceState *ds, const PlaceP &p_in, int32_t fmt, const std::vector<Seg> &segs,
-                                 hipStream_t st, int32_t max_workgroups = 0, const Seg *resident = nullptr)
+                                 hipStream_t st, int32_t max_workgroups = 0, const Seg *resident = nullptr,
+                                 size_t heads = 0)
 {
     if (segs.empty())
         return KDN_OK;
-    if (segs.size() > 65535 || segs.size() * sizeof(Seg) > kSegSlotBytes)
+    if (heads == 0)
+        heads = segs.size();
+    if (heads > 65535 || heads > segs.size() || segs.size() * sizeof(Seg) > kSegSlotBytes)
         return KDN_ESIZE;
+    for (size_t i = 0; i < segs.size(); ++i) // a chain only ever moves forward, into the records without a row of their own
+        if (segs[i].next != 0 && ((size_t)segs[i].next <= i || (size_t)segs[i].next < heads || (size_t)segs[i].next >= segs.size()))
+            return KDN_EINVAL;
     int64_t max_groups = 0;
     for (const Seg &s : segs)
         max_groups = std::max(max_groups, groups_spanned(s.S, s.T, p_in.c.G));
@@ -518,8 +528,8 @@ inline kdn_status place_segments(DeviceState *ds, const PlaceP &p_in, int32_t fm
     p.tiles_x = (uint32_t)(max_groups * 2 * p.c.L);
     uint32_t gx = p.tiles_x;
     if (max_workgroups > 0)
-        gx = std::min<uint32_t>(gx, std::max<uint32_t>(1u, (uint32_t)max_workgroups / (uint32_t)segs.size()));
-    dim3 grid(gx, (unsigned)segs.size(), 1);
+        gx = std::min<uint32_t>(gx, std::max<uint32_t>(1u, (uint32_t)max_workgroups / (uint32_t)heads));
+    dim3 grid(gx, (unsigned)heads, 1);
 
     const Seg *segs_dev = resident;
     int slot = -1;
@@ -570,11 +580,57 @@ inline kdn_status place_segments(DeviceState *ds, const PlaceP &p_in, int32_t fm
 struct PlannedSeg {
     Seg seg;
     int32_t request, chunk, offset;
+    int32_t follows; // record of the same launch whose workgroups place this view as well, -1: its own
 };
 struct ComposePlan {
     std::vector<PlannedSeg> segs[kFormats];
     int32_t reuse[kFormats] = {};
+    size_t heads[kFormats] = {}; // records with workgroups of their own: the first heads[f] of segs[f]
 };
+
+// Views of exactly the same stored rows whose tiles cut them the same way (same rows of the
+// same buffer, destinations congruent modulo the token group) are chained: the first keeps
+// its workgroups, the others follow it through Seg::next and are moved behind all records
+// that have workgroups.  Order is otherwise kept.  Returns the number of records with
+// workgroups.
+inline size_t chain_views(std::vector<PlannedSeg> &v, int32_t G)
+{
+    using Key = std::tuple<const uint8_t *, int32_t, int32_t, int32_t, int32_t>;
+    std::map<Key, size_t> last; // key -> position in `v` of the latest view with that key
+    std::vector<size_t> before(v.size(), SIZE_MAX);
+    std::vector<size_t> order, tail;
+    for (size_t i = 0; i < v.size(); ++i) {
+        const Seg &s = v[i].seg;
+        const Key key{s.data, s.Tp, s.tok0, s.T, s.S % G};
+        auto it = last.find(key);
+        if (it == last.end()) {
+            order.push_back(i);
+            last.emplace(key, i);
+        } else {
+            before[i] = it->second;
+            it->second = i;
+            tail.push_back(i);
+        }
+    }
+    const size_t heads = order.size();
+    order.insert(order.end(), tail.begin(), tail.end());
+    std::vector<size_t> where(v.size());
+    for (size_t k = 0; k < order.size(); ++k)
+        where[order[k]] = k;
+    std::vector<PlannedSeg> out(v.size());
+    for (size_t k = 0; k < order.size(); ++k) {
+        out[k] = v[order[k]];
+        out[k].seg.next = 0;
+        out[k].follows = -1;
+    }
+    for (size_t i = 0; i < v.size(); ++i)
+        if (before[i] != SIZE_MAX) {
+            out[where[before[i]]].seg.next = (int32_t)where[i];
+            out[where[i]].follows = (int32_t)where[before[i]];
+        }
+    v.swap(out);
+    return heads;
+}
 
 inline kdn_status plan_compose(const kdn_request *reqs, int32_t n_reqs, const kdn_cache_desc *cache,
                                ComposePlan &plan)
@@ -612,7 +668,8 @@ inline kdn_status plan_compose(const kdn_request *reqs, int32_t n_reqs, const kd
             ps.seg.T = ch.num_tokens;
             ps.seg.S = S;
             ps.seg.rope_row = 0;
-            ps.seg.pad = 0;
+            ps.seg.next = 0;
+            ps.follows = -1;
             ps.request = r;
             ps.chunk = i;
             ps.offset = q.offsets[i];
@@ -620,13 +677,19 @@ inline kdn_status plan_compose(const kdn_request *reqs, int32_t n_reqs, const kd
             S += ch.num_tokens;
         }
     }
+    const int32_t G = make_cache_p(cache).G;
     for (int f = 0; f < kFormats; ++f) {
         // Segments that read the same stored rows run back to back, so that a popular
-        // chunk is fetched from HBM once and from the last-level cache afterwards.
+        // chunk is fetched from HBM once and from the last-level cache afterwards; views
+        // that are the very same rows are chained onto one set of workgroups.
         plan.reuse[f] = 0;
-        if (n_reqs <= 1)
-            continue;
         std::vector<PlannedSeg> &v = plan.segs[f];
+        plan.heads[f] = v.size();
+        if (n_reqs <= 1) { // one request: its order is kept; a view it holds twice is still read once
+            plan.heads[f] = chain_views(v, G);
+            plan.reuse[f] = plan.heads[f] < v.size();
+            continue;
+        }
         std::stable_sort(v.begin(), v.end(), [](const PlannedSeg &a, const PlannedSeg &b) {
             return a.seg.data != b.seg.data ? a.seg.data < b.seg.data : a.seg.tok0 < b.seg.tok0;
         });
@@ -640,6 +703,9 @@ inline kdn_status plan_compose(const kdn_request *reqs, int32_t n_reqs, const kd
                 plan.reuse[f] = 1;
             reach = std::max<int64_t>(reach, (int64_t)v[i].seg.tok0 + v[i].seg.T);
         }
+        plan.heads[f] = chain_views(v, G);
+        if (plan.heads[f] < v.size())
+            plan.reuse[f] = 1;
     }
     return KDN_OK;
 }
@@ -682,7 +748,7 @@ inline kdn_status compose_impl(const kdn_request *reqs, int32_t n_reqs, const kd
             segs.back().rope_row = rows[k++];
         }
         p.reuse = plan.reuse[f];
-        st = place_segments(ds, p, f, segs, static_cast<hipStream_t>(stream), max_workgroups);
+        st = place_segments(ds, p, f, segs, static_cast<hipStream_t>(stream), max_workgroups, nullptr, plan.heads[f]);
         if (st != KDN_OK)
             return st;
     }

@@ -463,7 +463,7 @@ def kdn_compose_batch_static(plan_or_requests, cache: PagedCache, rope_base: flo
 class PlacementDesc(C.Structure):
     _fields_ = [("request", C.c_int32), ("chunk", C.c_int32), ("fmt", C.c_int32), ("launch", C.c_int32),
                 ("dest_token", C.c_int32), ("num_tokens", C.c_int32), ("offset", C.c_int32),
-                ("shares_rows", C.c_int32)]
+                ("shares_rows", C.c_int32), ("follows", C.c_int32)]
 
 
 def kdn_compose_plan(plan_or_requests, cache: PagedCache):

@@ -19,7 +19,7 @@ def test_fingerprint_is_reproducible():
     from paper_2409_13761_amd import build
     a, b = bench.kernel_source_fingerprint(), bench.kernel_source_fingerprint()
     assert a == b == build.source_fingerprint() and len(a) == 16
-    for w in ("70b_long", "8b"):
+    for w in ("70b_long", "8b", "batched_reuse"):
         assert bench.counter_traffic(w) in (None, bench.COUNTER_TRAFFIC[w]["k_place_bytes_per_launch"])
         assert os.path.exists(os.path.join(ROOT, bench.COUNTER_TRAFFIC[w]["profile"]))
 

@@ -61,7 +61,14 @@ def test_batched_views_of_the_same_rows_adjoin_and_are_flagged():
     plan = kdn.kdn_compose_plan(reqs, cache)
     assert len(plan) == 36 and {p["shares_rows"] for p in plan} == {1}
     key = [pool[int(draws[p["request"], p["chunk"]])].data.data_ptr() for p in plan]
-    assert key == sorted(key)                                     # equal buffers back to back
+    own = [i for i, p in enumerate(plan) if p["follows"] < 0]     # records with workgroups of their own
+    assert own == list(range(len(own)))                           # come first,
+    assert [key[i] for i in own] == sorted(key[i] for i in own)   # equal buffers back to back;
+    assert len(own) == len(set(key)) == 5                         # whole chunks at multiples of 64: one per buffer
+    for i, p in enumerate(plan):                                  # every other view is chained behind one of the
+        if p["follows"] >= 0:                                     # same buffer, earlier in the launch
+            assert p["follows"] < i and key[p["follows"]] == key[i]
+    assert len({p["follows"] for p in plan if p["follows"] >= 0}) == 36 - 5   # and nobody has two followers
     for p in plan:                                                # placement untouched by the reordering
         assert p["dest_token"] == 64 * p["chunk"]
     assert sorted((p["request"], p["chunk"]) for p in plan) == [(r, c) for r in range(12) for c in range(3)]
@@ -71,6 +78,39 @@ def test_batched_views_of_the_same_rows_adjoin_and_are_flagged():
     assert {p["shares_rows"] for p in kdn.kdn_compose_plan(reqs, cache)} == {0}
     reqs = [([a.slice(0, 64)], [0], _table(4), 0), ([a.slice(63, 64)], [0], _table(4), 0)]
     assert {p["shares_rows"] for p in kdn.kdn_compose_plan(reqs, cache)} == {1}
+
+
+def test_views_are_chained_only_when_their_tiles_cut_the_same_rows_the_same_way():
+    """A view is read once for several destinations only if those are the very same stored rows
+    and the destinations are congruent modulo the tile's 16 tokens."""
+    cache = _cache()
+    a, b = _chunk(cache, 96, INT8), _chunk(cache, 5, INT8)
+
+    def follows(reqs):
+        return {(p["request"], p["chunk"]): p["follows"] for p in kdn.kdn_compose_plan(reqs, cache)}, \
+               kdn.kdn_compose_plan(reqs, cache)
+
+    # one request holding the same chunk twice, 96 tokens apart: chained (and then flagged as sharing rows)
+    f, plan = follows([([a, a], [0, 96], _table(12), 0)])
+    assert [p["chunk"] for p in plan] == [0, 1] and [p["follows"] for p in plan] == [-1, 0]
+    assert {p["shares_rows"] for p in plan} == {1}
+    # the second copy lands 5 tokens off the grid of the first: same rows, other tiles, not chained
+    f, plan = follows([([a, b, a], [0, 96, 101], _table(14), 0)])
+    assert [p["follows"] for p in plan] == [-1, -1, -1]
+    # across requests: same slice at 0 and at 32 is chained, at 8 it is not; another slice of the buffer never is
+    reqs = [([a.slice(16, 64)], [0], _table(8), 0), ([a.slice(16, 64)], [7], _table(8), 32),
+            ([a.slice(16, 64)], [0], _table(8), 8), ([a.slice(16, 63)], [0], _table(8), 0),
+            ([a.slice(17, 64)], [0], _table(8), 0), ([a.slice(16, 64)], [3], _table(8), 48)]
+    f, plan = follows(reqs)
+    head = next(i for i, p in enumerate(plan) if p["request"] == 0)
+    second = next(i for i, p in enumerate(plan) if p["request"] == 1)
+    assert f[(0, 0)] == -1 and f[(1, 0)] == head and f[(5, 0)] == second      # a chain of three
+    assert f[(2, 0)] == f[(3, 0)] == f[(4, 0)] == -1
+    assert [p["follows"] for p in plan][:4] == [-1] * 4 and sorted(p["follows"] for p in plan)[-2:] == [head, second]
+    # other stored forms are other launches: never chained across
+    c = _chunk(cache, 96, RAW)
+    f, plan = follows([([a], [0], _table(8), 0), ([c], [0], _table(8), 0)])
+    assert [p["follows"] for p in plan] == [-1, -1]
 
 
 def test_argument_checks():

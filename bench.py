@@ -774,7 +774,8 @@ SWEEP_SHAPES = (
     (24, 8, 192, 16, "head_dim 192"),
     (16, 8, 256, 16, "head_dim 256"),
     (8, 8, 512, 16, "head_dim 512"),
-    (64, 1, 128, 16, "one KV head"),
+    (80, 1, 128, 16, "one KV head: Llama-3-70B, one GPU's share of 8 under tensor parallelism"),
+    (80, 2, 128, 16, "two KV heads: the same model's share of 4"),
     (64, 2, 64, 16, "two KV heads of 64"),
     (32, 8, 128, 1, "block size 1 (paging by the token)"),
     (32, 8, 128, 2, "block size 2"),

@@ -85,6 +85,19 @@ def chunk_alloc(kdn, cache, T, fmt):
     return kdn.alloc_chunk(cache, T, fmt, arena=ARENA is not None)
 
 
+def pool_tensors(args, kdn, shape, dev):
+    """The paged pool's K and V tensors: torch allocations (an engine's own memory), or, with
+    --pool-memory arena, cut from the library's arena like the chunks."""
+    import torch
+    if getattr(args, "pool_memory", "torch") == "arena" and ARENA is not None:
+        n = 2
+        for d in shape:
+            n *= d
+        return tuple(kdn.arena_tensor(n).view(torch.bfloat16).view(shape) for _ in range(2))
+    k = torch.empty(shape, device=dev, dtype=torch.bfloat16)
+    return k, torch.empty_like(k)
+
+
 def pool_blocks_for(args, need, plane_bytes_per_block):
     """Blocks per (layer, side) plane of the paged pool.  --pool-blocks names it directly;
     otherwise --pool-gib sizes each of the K and V tensors (all layers) to that many GiB, as an
@@ -283,8 +296,7 @@ def workload_8b(args, dev):
     g = torch.Generator(device=dev)
     g.manual_seed(w.seed)
     if args.layout == "planes":         # K and V tensors [L][num_blocks][bs][H][D]
-        k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
-        v = torch.empty_like(k)
+        k, v = pool_tensors(args, kdn, (sh.L, nb, sh.bs, sh.H, sh.D), dev)
     elif args.layout == "kv_pair":      # one tensor [L][num_blocks][2][bs][H][D]: a block's K and V adjoin
         big = torch.empty((sh.L, nb, 2, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
         k, v = big[:, :, 0], big[:, :, 1]
@@ -329,11 +341,14 @@ def workload_8b(args, dev):
         "place_calls": ("load", "compose"),
         "workload": "Llama-3-8B-shaped KV (L32 H8 D128 bs16): per step store 4096 tokens to %s, "
                     "load them at offset 0, compose them as 8x512-token slices in seeded order with "
-                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled; cache layout %s, pool of %d blocks; %s block tables"
+                    "RoPE offsets 0..3584 (base %g); %d buffer sets cycled; cache layout %s, pool of %d blocks (%s); %s block "
+                    "tables; chunk buffers in %s"
                     % (args.fmt, w.rope_base, n_sets, args.layout, nb,
-                       "random disjoint" if args.tables == "random" else "consecutive-block"),
+                       "in the striped arena" if args.pool_memory == "arena" and ARENA is not None else "a torch allocation",
+                       "random disjoint" if args.tables == "random" else "consecutive-block",
+                       "the striped arena" if ARENA is not None else "plain device memory"),
         "traffic": counter_traffic("8b") if args.fmt == "int8" and args.tables == "random" and args.layout == "planes"
-        and not args.pool_blocks and args.pool_gib == POOL_GIB_DEFAULT else None,
+        and not args.pool_blocks and args.pool_gib == POOL_GIB_DEFAULT and args.pool_memory == "torch" else None,
     }
     if not args.no_cpu_baseline and args.fmt == "int8":
         res["cpu_baseline"] = cpu_baseline(kdn, cache, sets[0], order, offsets, w.rope_base, T, n_slices,
@@ -404,8 +419,7 @@ def workload_70b(args, dev):
     nb = pool_blocks_for(args, n_sets * 2 * blocks, sh.L * sh.bs * sh.H * sh.D * 2)
     g = torch.Generator(device=dev)
     g.manual_seed(w.seed)
-    k = torch.empty((sh.L, nb, sh.bs, sh.H, sh.D), device=dev, dtype=torch.bfloat16)
-    v = torch.empty_like(k)
+    k, v = pool_tensors(args, kdn, (sh.L, nb, sh.bs, sh.H, sh.D), dev)
     fill_normal(k, g)
     fill_normal(v, g)
     cache = kdn.PagedCache(k, v)
@@ -450,7 +464,7 @@ def workload_70b(args, dev):
                        "the striped arena" if ARENA is not None else "plain device memory"),
         "extra": extra,
         "traffic": counter_traffic("70b_long") if args.fmt == "int8" and not args.pool_blocks
-        and args.pool_gib == POOL_GIB_DEFAULT else None,
+        and args.pool_gib == POOL_GIB_DEFAULT and args.pool_memory == "torch" else None,
     }
     if not args.no_cpu_baseline and args.fmt == "int8":
         res["cpu_baseline"] = cpu_baseline_70b(kdn, cache, sets[0], offsets, w.rope_base, T, args.cpu_layers)
@@ -1080,6 +1094,10 @@ def main() -> int:
                          "lie far apart in the device memory (created first, before the pool), or in plain torch "
                          "allocations")
     ap.add_argument("--arena-gib", type=float, default=24.0, help="size of the arena")
+    ap.add_argument("--pool-memory", choices=("torch", "arena"), default="torch",
+                    help="where the paged pool of the 8b and 70b_long workloads lies: a torch allocation (the engine's "
+                         "own memory, the default) or the arena (give --arena-gib room for it): a pool much smaller "
+                         "than the device memory then still has its blocks spread over all of it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-steps", type=int, default=8, help="oracle steps of the 8b workload's CPU baseline")
     ap.add_argument("--cpu-layers", type=int, default=20,

@@ -307,8 +307,8 @@ kdn_status kdn_compose_batch_rope(const kdn_request *requests, int32_t n_request
  * kernels take them: grouped by stored form (one launch per form present, `launch`
  * counts them), and, when there is more than one request, views of the same stored rows
  * next to each other.  Views that are exactly the same stored rows (same buffer, same token
- * range) and whose destinations are congruent modulo the tile's token count (16, or the
- * block size when that is no multiple of 16) are read once: the first such view has
+ * range) and whose destinations are congruent modulo the tile's token count (16 for block
+ * sizes 1 to 3 and multiples of 16, the block size otherwise) are read once: the first such view has
  * workgroups of its own, each later one names in `follows` the record it is chained behind
  * (the workgroup that read a tile for that record places it for this one next, out of the
  * caches), and chained records come after all records with workgroups in their launch.

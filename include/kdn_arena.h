@@ -28,7 +28,8 @@
  *
  * One arena per device.  The calls act on the current device and are serialised by a mutex.
  * Memory from the arena is ordinary device memory for kernels and copies; it must not be
- * passed to hipFree.  Nothing here is captured by a HIP graph.
+ * passed to hipFree.  kdn_shutdown leaves the arena alone; only kdn_arena_destroy (or the end
+ * of the process) releases it.  Nothing here is captured by a HIP graph.
  */
 #ifndef KDN_ARENA_H
 #define KDN_ARENA_H

@@ -307,8 +307,8 @@ kdn_status kdn_compose_batch_rope(const kdn_request *requests, int32_t n_request
  * kernels take them: grouped by stored form (one launch per form present, `launch`
  * counts them), and, when there is more than one request, views of the same stored rows
  * next to each other.  Views that are exactly the same stored rows (same buffer, same token
- * range) and whose destinations are congruent modulo the tile's token count (16 for block
- * sizes 1 to 3 and multiples of 16, the block size otherwise) are read once: the first such view has
+ * range) and whose destinations are congruent modulo the tile's token count
+ * (kdn_tile_tokens) are read once: the first such view has
  * workgroups of its own, each later one names in `follows` the record it is chained behind
  * (the workgroup that read a tile for that record places it for this one next, out of the
  * caches), and chained records come after all records with workgroups in their launch.
@@ -330,6 +330,11 @@ typedef struct kdn_placement {
 } kdn_placement;
 kdn_status kdn_compose_plan(const kdn_request *requests, int32_t n_requests, const kdn_cache_desc *cache,
                             kdn_placement *out, int32_t cap, int32_t *n_out);
+
+/* Tokens whose rows (one layer, one side) one workgroup moves at a time for this cache: 16
+ * for block sizes 1 to 3 and multiples of 16, else the block size.  Host only.  0 if the
+ * descriptor is not valid. */
+int32_t kdn_tile_tokens(const kdn_cache_desc *cache);
 
 /* Patch: the write-back half of selective recompute after a blend (Sec. 3.2, "KV-cache
  * blending": recomputing a small part of the composed KV).  rows_dev [device, 16-byte

@@ -458,6 +458,11 @@ kdn_status kdn_compose_plan(const kdn_request *requests, int32_t n_requests, con
     return KDN_OK;
 }
 
+int32_t kdn_tile_tokens(const kdn_cache_desc *cache)
+{
+    return check_cache(cache) == KDN_OK ? make_cache_p(cache).G : 0;
+}
+
 kdn_status kdn_compose_rope(const kdn_chunk *chunks, const int32_t *offsets, int32_t n_chunks,
                             const kdn_cache_desc *cache, const int32_t *block_table_dev,
                             int32_t table_len, int32_t dest_token_start, const kdn_rope_spec *rope,

@@ -162,6 +162,8 @@ def lib() -> C.CDLL:
         L.kdn_compose_plan.argtypes = [vp, i32, vp, vp, i32, C.POINTER(i32)]
         L.kdn_host_stage_plan.restype = C.c_int
         L.kdn_host_stage_plan.argtypes = [C.POINTER(ChunkDesc), i32, i32, i32, vp, i32, C.POINTER(i32), vp]
+        L.kdn_tile_tokens.restype = i32
+        L.kdn_tile_tokens.argtypes = [C.POINTER(CacheDesc)]
         L.kdn_rope_prepare.restype = C.c_int
         L.kdn_rope_prepare.argtypes = [C.c_double, i32, C.POINTER(i32), i32]
         L.kdn_rope_prepare_spec.restype = C.c_int
@@ -203,7 +205,7 @@ EXPORTS = ["kdn_chunk_bytes", "kdn_chunk_init", "kdn_chunk_slice", "kdn_store_ch
            "kdn_store_to_host", "kdn_store_staging_bytes", "kdn_store_chunk_opts", "kdn_compose_opts",
            "kdn_load_chunk", "kdn_compose", "kdn_compose_batch", "kdn_compose_batch_static", "kdn_compose_rope",
            "kdn_compose_batch_rope", "kdn_patch_rows", "kdn_compose_from_host", "kdn_compose_from_host_staged",
-           "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_rope_prepare", "kdn_rope_prepare_spec", "kdn_rope_release",
+           "kdn_staging_bytes", "kdn_host_stage_plan", "kdn_compose_plan", "kdn_tile_tokens", "kdn_rope_prepare", "kdn_rope_prepare_spec", "kdn_rope_release",
            "kdn_validate_block_table", "kdn_probe_stream", "kdn_f32_to_bf16", "kdn_shutdown", "kdn_status_str",
            "kdn_version", "kdn_pool_create", "kdn_pool_destroy", "kdn_pool_hash", "kdn_pool_lookup",
            "kdn_pool_insert", "kdn_pool_remove", "kdn_pool_get_stats", "kdn_arena_create", "kdn_arena_alloc",
@@ -475,6 +477,12 @@ def kdn_compose_plan(plan_or_requests, cache: PagedCache):
     out = (PlacementDesc * n.value)()
     _check(lib().kdn_compose_plan(plan.arr, plan.n, C.byref(cd), out, n.value, C.byref(n)), "kdn_compose_plan")
     return [{f: getattr(r, f) for f, _ in PlacementDesc._fields_} for r in out]
+
+
+def kdn_tile_tokens(cache: PagedCache) -> int:
+    """Tokens per tile for this cache (the modulus of the chaining rule of kdn_compose_plan)."""
+    cd = cache.desc()
+    return int(lib().kdn_tile_tokens(C.byref(cd)))
 
 
 def rope_spec(base: float = 10000.0, inv_freq=None, rot_dim: int = 0,

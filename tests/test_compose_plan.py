@@ -64,11 +64,14 @@ def test_batched_views_of_the_same_rows_adjoin_and_are_flagged():
     own = [i for i, p in enumerate(plan) if p["follows"] < 0]     # records with workgroups of their own
     assert own == list(range(len(own)))                           # come first,
     assert [key[i] for i in own] == sorted(key[i] for i in own)   # equal buffers back to back;
-    assert len(own) == len(set(key)) == 5                         # whole chunks at multiples of 64: one per buffer
+    G = kdn.kdn_tile_tokens(cache)
+    classes = {(key[i], p["dest_token"] % G) for i, p in enumerate(plan)}
+    assert len(own) == len(classes)                               # one per (buffer, place on the tile grid)
     for i, p in enumerate(plan):                                  # every other view is chained behind one of the
-        if p["follows"] >= 0:                                     # same buffer, earlier in the launch
-            assert p["follows"] < i and key[p["follows"]] == key[i]
-    assert len({p["follows"] for p in plan if p["follows"] >= 0}) == 36 - 5   # and nobody has two followers
+        if p["follows"] >= 0:                                     # same buffer and place, earlier in the launch
+            q = plan[p["follows"]]
+            assert p["follows"] < i and key[p["follows"]] == key[i] and q["dest_token"] % G == p["dest_token"] % G
+    assert len({p["follows"] for p in plan if p["follows"] >= 0}) == 36 - len(own)   # and nobody has two followers
     for p in plan:                                                # placement untouched by the reordering
         assert p["dest_token"] == 64 * p["chunk"]
     assert sorted((p["request"], p["chunk"]) for p in plan) == [(r, c) for r in range(12) for c in range(3)]
@@ -80,27 +83,44 @@ def test_batched_views_of_the_same_rows_adjoin_and_are_flagged():
     assert {p["shares_rows"] for p in kdn.kdn_compose_plan(reqs, cache)} == {1}
 
 
+def test_tile_tokens_by_block_size_and_row_length():
+    def g(bs, H, D, nb=8):
+        k = torch.zeros((1, nb, bs, H, D), dtype=torch.bfloat16)
+        return kdn.kdn_tile_tokens(kdn.PagedCache(k, torch.zeros_like(k)))
+    assert g(16, 8, 128) == 16 and g(32, 8, 128) == 16 and g(128, 8, 128) == 16   # 16-token pieces of a block
+    assert g(8, 8, 128) == 8 and g(24, 8, 128) == 24 and g(4, 2, 64) == 4         # a whole block of another size
+    assert g(1, 8, 128) == g(2, 8, 128) == g(3, 8, 128) == 16                     # rows look their own block up
+    assert g(16, 1, 128) == 16 and g(16, 2, 64) == 16                             # whatever the rows' length
+
+
 def test_views_are_chained_only_when_their_tiles_cut_the_same_rows_the_same_way():
     """A view is read once for several destinations only if those are the very same stored rows
-    and the destinations are congruent modulo the tile's 16 tokens."""
+    and the destinations are congruent modulo the tile's token count."""
     cache = _cache()
-    a, b = _chunk(cache, 96, INT8), _chunk(cache, 5, INT8)
+    G = kdn.kdn_tile_tokens(cache)
+    assert G == 16
+    T = 96
+    a, b = _chunk(cache, T, INT8), _chunk(cache, 5, INT8)
+    big = _table(NB)
 
     def follows(reqs):
-        return {(p["request"], p["chunk"]): p["follows"] for p in kdn.kdn_compose_plan(reqs, cache)}, \
-               kdn.kdn_compose_plan(reqs, cache)
+        plan = kdn.kdn_compose_plan(reqs, cache)
+        return {(p["request"], p["chunk"]): p["follows"] for p in plan}, plan
 
-    # one request holding the same chunk twice, 96 tokens apart: chained (and then flagged as sharing rows)
-    f, plan = follows([([a, a], [0, 96], _table(12), 0)])
-    assert [p["chunk"] for p in plan] == [0, 1] and [p["follows"] for p in plan] == [-1, 0]
+    # one request holding the same chunk twice, whole tiles apart: chained (and then flagged as sharing rows)
+    pad = -T % G
+    views = [a] + ([a.slice(0, pad)] if pad else []) + [a]
+    f, plan = follows([(views, list(range(len(views))), big, 0)])
+    assert [p["chunk"] for p in plan] == list(range(len(views)))
+    assert [p["follows"] for p in plan] == [-1] * (len(views) - 1) + [0]
     assert {p["shares_rows"] for p in plan} == {1}
     # the second copy lands 5 tokens off the grid of the first: same rows, other tiles, not chained
-    f, plan = follows([([a, b, a], [0, 96, 101], _table(14), 0)])
+    f, plan = follows([([a, b, a], [0, T, T + 5], big, 0)])
     assert [p["follows"] for p in plan] == [-1, -1, -1]
-    # across requests: same slice at 0 and at 32 is chained, at 8 it is not; another slice of the buffer never is
-    reqs = [([a.slice(16, 64)], [0], _table(8), 0), ([a.slice(16, 64)], [7], _table(8), 32),
-            ([a.slice(16, 64)], [0], _table(8), 8), ([a.slice(16, 63)], [0], _table(8), 0),
-            ([a.slice(17, 64)], [0], _table(8), 0), ([a.slice(16, 64)], [3], _table(8), 48)]
+    # across requests: same slice at 0 and at 2G is chained, at 8 it is not; another slice of the buffer never is
+    reqs = [([a.slice(16, 64)], [0], big, 0), ([a.slice(16, 64)], [7], big, 2 * G),
+            ([a.slice(16, 64)], [0], big, 8), ([a.slice(16, 63)], [0], big, 0),
+            ([a.slice(17, 64)], [0], big, 0), ([a.slice(16, 64)], [3], big, 3 * G)]
     f, plan = follows(reqs)
     head = next(i for i, p in enumerate(plan) if p["request"] == 0)
     second = next(i for i, p in enumerate(plan) if p["request"] == 1)
@@ -108,8 +128,8 @@ def test_views_are_chained_only_when_their_tiles_cut_the_same_rows_the_same_way(
     assert f[(2, 0)] == f[(3, 0)] == f[(4, 0)] == -1
     assert [p["follows"] for p in plan][:4] == [-1] * 4 and sorted(p["follows"] for p in plan)[-2:] == [head, second]
     # other stored forms are other launches: never chained across
-    c = _chunk(cache, 96, RAW)
-    f, plan = follows([([a], [0], _table(8), 0), ([c], [0], _table(8), 0)])
+    c = _chunk(cache, T, RAW)
+    f, plan = follows([([a], [0], big, 0), ([c], [0], big, 0)])
     assert [p["follows"] for p in plan] == [-1, -1]
 
 

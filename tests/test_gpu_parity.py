@@ -350,13 +350,16 @@ def test_batched_compose_matches_independent_oracle_composes(D, fmt):
 def test_views_read_once_for_many_destinations_equal_the_oracle(shape, fmt):
     """The same stored rows going to several destinations in one call: chained onto one set of
     workgroups where the tiles cut them the same way (same view, destinations congruent modulo
-    the tile), separate workgroups otherwise; every destination must hold what a compose of
-    its own would have put there, with its own rotation."""
+    the tile's token count), separate workgroups otherwise; every destination must hold what a
+    compose of its own would have put there, with its own rotation."""
     bs, H, D = shape
     L, T = 2, 96
-    need = [-(-(2 * T + 48) // bs)] * 7
-    nb = sum(need) + -(-T // bs) + 2 * -(-5 // bs) + 3
-    _say("chained views bs=%d H=%d D=%d fmt=%d" % (bs, H, D, fmt))
+    probe = torch.zeros((L, 4, bs, H, D), dtype=torch.bfloat16)
+    G = kdn.kdn_tile_tokens(kdn.PagedCache(probe, torch.zeros_like(probe)))
+    span = 3 * G + 2 * T                                            # tokens a request's table covers
+    need = [-(-span // bs)] * 7
+    nb = sum(need) + -(-T // bs) + -(-5 // bs) + 3
+    _say("chained views bs=%d H=%d D=%d fmt=%d (tile of %d tokens)" % (bs, H, D, fmt, G))
     src = host_cache(61, L, nb, bs, H, D)
     tabs = synth.disjoint_block_tables(61, nb, [-(-T // bs), -(-5 // bs)] + need)
     a = O.store(src, tabs[0], 0, T, fmt)
@@ -364,14 +367,13 @@ def test_views_read_once_for_many_destinations_equal_the_oracle(shape, fmt):
     da, db = chunk_to_dev(a), chunk_to_dev(b)
     hd = host_cache(62, L, nb, bs, H, D)
     dd = dev_cache(hd)
-    # (views, offsets, destination start): which of them chain depends on the tile's token count
-    cases = [([(a, da), (a, da)], [0, T], 0),                                   # one request, the chunk twice
-             ([(a.slice(16, 64), da.slice(16, 64))], [7], 32),                    # a slice ...
-             ([(a.slice(16, 64), da.slice(16, 64))], [-9], 32 + 2 * bs),          # ... again, whole blocks further on
-             ([(a.slice(16, 64), da.slice(16, 64))], [1000], 8),                  # off that grid
-             ([(b, db), (a, da)], [3, 5], 0),                                     # the chunk, 5 tokens in
-             ([(a, da)], [0], 48),                                                # no rotation
-             ([(a.slice(17, 64), da.slice(17, 64)), (a.slice(16, 63), da.slice(16, 63))], [2, 4], 0)]
+    sl = lambda t0, n: (a.slice(t0, n), da.slice(t0, n))
+    # (views, offsets, destination start)
+    cases = [([(a, da)], [0], 0), ([(a, da)], [T], G),                            # the chunk, a whole tile further on
+             ([sl(16, 64)], [7], 32), ([sl(16, 64)], [-9], 32 + 2 * G),           # a slice, two tiles further on
+             ([sl(16, 64)], [1000], 8),                                           # off that grid
+             ([(b, db), (a, da), (a, da)], [3, 5, 0], 0),                         # the chunk, 5 tokens in, and right behind
+             ([sl(17, 64), sl(16, 63)], [2, 4], 0)]                               # other slices of the buffer
     reqs = []
     for i, (views, offs, dest) in enumerate(cases):
         O.compose([h for h, _ in views], offs, hd, tabs[2 + i], 10000.0, dest=dest)
@@ -380,13 +382,18 @@ def test_views_read_once_for_many_destinations_equal_the_oracle(shape, fmt):
     assert sum(p["follows"] >= 0 for p in plan) >= 2, plan           # the case is about chains: there are some
     kdn.kdn_compose_batch(reqs, dd, 10000.0)
     assert_cache_equal(dd, hd)
-    # the same through capped launches (workgroups stride over tiles, each walking its chain)
+    # one request that holds the chunk twice a tile apart, through a capped launch (workgroups stride
+    # over tiles, each walking its chain)
     hd2 = host_cache(63, L, nb, bs, H, D)
     dd2 = dev_cache(hd2)
-    for views, offs, dest in cases[:1]:
-        O.compose([h for h, _ in views], offs, hd2, tabs[2], 10000.0, dest=dest)
-        kdn.kdn_compose([d for _, d in views], offs, dd2, dev_table(tabs[2]), 10000.0, dest, max_workgroups=3)
+    pad = -T % G                                                    # tokens up to the next tile boundary
+    views = [(a, da)] + ([sl(0, pad)] if pad else []) + [(a, da)]
+    offs = list(range(len(views)))
+    O.compose([h for h, _ in views], offs, hd2, tabs[2], 10000.0, dest=0)
+    kdn.kdn_compose([d for _, d in views], offs, dd2, dev_table(tabs[2]), 10000.0, 0, max_workgroups=3)
     assert_cache_equal(dd2, hd2)
+    assert [p["follows"] for p in kdn.kdn_compose_plan([([d for _, d in views], offs, dev_table(tabs[2]), 0)], dd2)] \
+        == [-1] * (len(views) - 1) + [0]
 
 
 # ------------------------------------------------------------------ utilities

@@ -658,10 +658,13 @@ __device__ __forceinline__ void dequantise8(const uint32_t *w, float scale, floa
 // Interleaved pairs lie inside a lane's own 8 elements.  All lanes stay active through
 // the exchange; loads and stores are predicated instead.
 // Grid as k_place.
-template <int DT, int FMT, bool DENSE, bool REUSE>
+// UQ: rows a lane of a quantised form keeps in flight: 8, or 4 for tiles of so few rows that
+// a wavefront could not fill 8 (short rows: few or narrow heads) and is better off with the
+// smaller register footprint, i.e. more wavefronts per SIMD.
+template <int DT, int FMT, bool DENSE, bool REUSE, int UQ>
 __device__ __forceinline__ void place_tile_c(const PlaceP &p, const Seg &sg, const uint32_t bx)
 {
-    constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 4 : 8;
+    constexpr int U = FMT == KDN_FMT_RAW_BF16 ? 4 : UQ;
     constexpr int W = FMT == KDN_FMT_RAW_BF16 ? 4 : FMT == KDN_FMT_INT4_GROUP32 ? 1 : 2; // words per 8 stored elements
     const int D = DT ? DT : p.c.D;
     const int R8 = D >> 3;   // lanes per row
@@ -824,7 +827,7 @@ __device__ __forceinline__ void place_tile_c(const PlaceP &p, const Seg &sg, con
 }
 
 // Grid rows, chained views and the barrier as in k_place.
-template <int DT, int FMT, bool DENSE, bool REUSE, typename Segs>
+template <int DT, int FMT, bool DENSE, bool REUSE, int UQ, typename Segs>
 __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
 {
     bool first = true;
@@ -835,7 +838,7 @@ __global__ __launch_bounds__(kThreads) void k_place_c(PlaceP p, Segs segs)
                 __syncthreads();
             first = false;
             const Seg &sg = segs.at(at);
-            place_tile_c<DT, FMT, DENSE, REUSE>(p, sg, bx);
+            place_tile_c<DT, FMT, DENSE, REUSE, UQ>(p, sg, bx);
             at = sg.next;
         } while (at != 0);
     }

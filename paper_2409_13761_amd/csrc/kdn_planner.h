@@ -19,6 +19,7 @@ namespace kdn_impl {
 
 constexpr int kFormats = 4; // kdn_format values
 constexpr int kPerTokenMaxBlock = 3; // block sizes served by per-token block lookup
+constexpr int kFewPasses = 4;        // tiles of at most this many wavefront passes take the narrow place flavour
 
 // Resolved RoPE variant of one call: frequencies either derived from `base` or given.
 struct RopeSpec {
@@ -452,28 +453,43 @@ void launch_place_c(const PlaceP &p, const Seg *segs, int32_t n, const Seg *segs
                     hipStream_t st)
 {
     const int flavour = !p.c.dense ? 0 : p.reuse ? 2 : 1;
-    // a wavefront takes 64/(D/8) rows per pass and keeps 8 (raw: 4) passes in flight
+    // a wavefront takes 64/(D/8) rows per pass and keeps 8 (raw: 4) passes in flight; a tile of
+    // at most 4 passes (one head of 128, two of 64: a block's rows are 4 KiB, one wavefront's
+    // work) goes to the flavour that keeps 4: 68 registers instead of 87, 7 wavefronts per SIMD
+    // instead of 5, and such tiles are bound by how many of them are in flight (one head of 128:
+    // compose 4.7 -> 4.9-5.1 TB/s, load 4.6 -> 5.4; at 8 passes, two heads of 128, it loses)
     const int64_t passes = ((int64_t)p.c.G * p.c.H + 64 / (p.c.D >> 3) - 1) / (64 / (p.c.D >> 3));
-    const dim3 block(block_threads(passes * 64, FMT == KDN_FMT_RAW_BF16 ? 4 : 8));
-    if (segs_dev) {
-        SegsDevice sd{segs_dev};
-        if (flavour == 0)
-            hipLaunchKernelGGL((k_place_c<DT, FMT, false, false, SegsDevice>), grid, block, 0, st, p, sd);
-        else if (flavour == 1)
-            hipLaunchKernelGGL((k_place_c<DT, FMT, true, false, SegsDevice>), grid, block, 0, st, p, sd);
-        else
-            hipLaunchKernelGGL((k_place_c<DT, FMT, true, true, SegsDevice>), grid, block, 0, st, p, sd);
-    } else {
-        SegsInline si;
+    const bool few = FMT != KDN_FMT_RAW_BF16 && passes <= kFewPasses;
+    const dim3 block(block_threads(passes * 64, FMT == KDN_FMT_RAW_BF16 || few ? 4 : 8));
+    SegsDevice sd{segs_dev};
+    SegsInline si;
+    if (!segs_dev) {
         std::memset(&si, 0, sizeof si);
         std::memcpy(si.s, segs, (size_t)n * sizeof(Seg));
-        if (flavour == 0)
-            hipLaunchKernelGGL((k_place_c<DT, FMT, false, false, SegsInline>), grid, block, 0, st, p, si);
-        else if (flavour == 1)
-            hipLaunchKernelGGL((k_place_c<DT, FMT, true, false, SegsInline>), grid, block, 0, st, p, si);
-        else
-            hipLaunchKernelGGL((k_place_c<DT, FMT, true, true, SegsInline>), grid, block, 0, st, p, si);
     }
+#define KDN_PLACE_C(DENSE, REUSE, UQ)                                                                           \
+    do {                                                                                                        \
+        if (segs_dev)                                                                                           \
+            hipLaunchKernelGGL((k_place_c<DT, FMT, DENSE, REUSE, UQ, SegsDevice>), grid, block, 0, st, p, sd);  \
+        else                                                                                                    \
+            hipLaunchKernelGGL((k_place_c<DT, FMT, DENSE, REUSE, UQ, SegsInline>), grid, block, 0, st, p, si);  \
+    } while (0)
+    if (few) {
+        if (flavour == 0)
+            KDN_PLACE_C(false, false, 4);
+        else if (flavour == 1)
+            KDN_PLACE_C(true, false, 4);
+        else
+            KDN_PLACE_C(true, true, 4);
+    } else {
+        if (flavour == 0)
+            KDN_PLACE_C(false, false, 8);
+        else if (flavour == 1)
+            KDN_PLACE_C(true, false, 8);
+        else
+            KDN_PLACE_C(true, true, 8);
+    }
+#undef KDN_PLACE_C
 }
 
 // Which place kernel serves a head_dim, by measurement on pools that span the device memory

@@ -1143,10 +1143,15 @@ def main() -> int:
             "fp8": "fp8 e4m3 codes + fp32 row scales", "raw": "raw bf16"}[f]
 
     global ARENA
+    arena_error = None
     if args.chunk_memory == "arena" and args.workload not in ("stream_probe", "toy", "host_stream_int8",
                                                               "host_stream_raw"):
         torch.zeros(1, device=dev)
-        ARENA = kdn.kdn_arena_create(int(args.arena_gib * (1 << 30)))
+        try:
+            ARENA = kdn.kdn_arena_create(int(args.arena_gib * (1 << 30)))
+        except kdn.KdnError as e:            # too little free memory, say: the chunks then lie in plain allocations
+            print("bench.py: no arena (%s); stored chunks in plain device memory" % e, file=sys.stderr)
+            arena_error = str(e)
 
     res = runners[args.workload](args, dev)
 
@@ -1182,6 +1187,8 @@ def main() -> int:
         out["arena"] = dict(ARENA, what="stored chunks lie in kdn_arena memory: granule i is free granule (i * stride) "
                                         "mod free_granules of the device memory in the driver's order; striped_gbs / "
                                         "packed_gbs: scattered tile writes over 1 GiB of it / of memory in that order")
+    elif arena_error is not None:
+        out["arena"] = {"error": arena_error, "what": "kdn_arena_create failed: stored chunks lie in plain device memory"}
     if out["roofline"]["traffic"] is not None:
         out["roofline"]["traffic_from"] = COUNTER_TRAFFIC[args.workload]["profile"]
     del res

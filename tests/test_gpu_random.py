@@ -146,3 +146,58 @@ def test_random_host_paths(seed):
     kdn.kdn_compose(views_p, offsets, d2, dev_table(dst_bt), 10000.0, dest_token_start=dest)
     assert_cache_equal(d1, hd)
     assert_cache_equal(d2, hd)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_batches_with_repeated_views(seed):
+    """Batched composes in which views recur: the same slice of the same chunk in several
+    requests (and twice in one), at destinations that sometimes share the tile grid and
+    sometimes do not, with their own offsets.  Whatever the planner chains, every request's
+    table must hold what a compose of its own gives; the static entry point must agree too."""
+    rng, L, H, D, bs, fmts, n_tab, nb0 = _case(9000 + seed)
+    n_req = int(rng.integers(2, 7))
+    probe = torch.zeros((L, 2, bs, H, D), dtype=torch.bfloat16)
+    G = kdn.kdn_tile_tokens(kdn.PagedCache(probe, torch.zeros_like(probe)))
+    cap = n_tab * bs
+    req_blocks = -(-(3 * cap + 2 * G) // bs)
+    nb = 2 * n_tab + n_req * req_blocks + 3
+    print("[case] repeats seed=%d L=%d H=%d D=%d bs=%d cap=%d tile=%d requests=%d" % (seed, L, H, D, bs, cap, G, n_req),
+          flush=True)
+    src = host_cache(9100 + seed, L, nb, bs, H, D)
+    tabs = synth.disjoint_block_tables(seed, nb, [n_tab, n_tab] + [req_blocks] * n_req)
+    fmt = int(rng.choice(fmts))                                     # one stored form: one launch, chains possible
+    hch = [O.store(src, tabs[i], 0, cap, fmt) for i in range(2)]
+    dch = [chunk_to_dev(h) for h in hch]
+    seen = []                                                       # (chunk, start, length) of earlier views
+    hd = host_cache(9200 + seed, L, nb, bs, H, D)
+    dd = dev_cache(hd)
+    reqs = []
+    for r in range(n_req):
+        views, offs = [], []
+        dest = int(rng.choice([0, G, 2 * G, int(rng.integers(0, bs + 1))]))
+        room = req_blocks * bs - dest
+        for _ in range(int(rng.integers(1, 4))):
+            if seen and rng.random() < 0.6:
+                i, ts, Tv = seen[int(rng.integers(0, len(seen)))]
+            else:
+                i = int(rng.integers(0, 2))
+                ts = int(rng.integers(0, cap))
+                Tv = int(rng.integers(1, cap - ts + 1))
+            if Tv > room:
+                break
+            room -= Tv
+            seen.append((i, ts, Tv))
+            views.append((i, ts, Tv))
+            offs.append(int(rng.integers(-3000, 3000)) if rng.random() < 0.8 else 0)
+        if not views:
+            views, offs = [(0, 0, 1)], [5]
+        O.compose([hch[i].slice(ts, Tv) for i, ts, Tv in views], offs, hd, tabs[2 + r], 10000.0, dest=dest)
+        reqs.append(([dch[i].slice(ts, Tv) for i, ts, Tv in views], offs, dev_table(tabs[2 + r]), dest))
+    plan = kdn.kdn_compose_plan(reqs, dd)
+    print("[case] repeats seed=%d: %d views, %d of them chained behind another" %
+          (seed, len(plan), sum(p["follows"] >= 0 for p in plan)), flush=True)
+    kdn.kdn_compose_batch(reqs, dd, 10000.0)
+    assert_cache_equal(dd, hd)
+    d2 = dev_cache(host_cache(9200 + seed, L, nb, bs, H, D))
+    kdn.kdn_compose_batch_static(reqs, d2, 10000.0)
+    assert_cache_equal(d2, hd)

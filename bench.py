@@ -263,6 +263,14 @@ def workload_stream_probe(args, dev):
                       "store_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 1, 0, reps),
                       "write_only_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 2, 0, reps),
                       "read_only_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 3, 0, reps)})
+    # tile sizes again, now with the tiles scattered over all 200 GiB (the regime an engine-sized pool is in)
+    wide_rows = []
+    for tile_kib in (8, 16, 32, 64, 256, 1024):
+        n_t = (1 << 30) // (tile_kib << 10)
+        wide_ids = torch.from_numpy(rng.permutation((200 << 30) // (tile_kib << 10))[:n_t].astype(np.int32)).to(dev)
+        wide_rows.append({"tile_KiB": tile_kib,
+                          "place_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, n_t, wide_ids, tile_kib, 0, 0, reps),
+                          "store_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, n_t, wide_ids, tile_kib, 1, 0, reps)})
     one_way = {"read_in_order_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, None, 32, 3, 0, reps),
                "write_in_order_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, None, 32, 2, 0, reps)}
     del huge
@@ -278,7 +286,8 @@ def workload_stream_probe(args, dev):
         "extra": {"by_tile_size": rows, "by_launch_width_at_32KiB_tiles": caps,
                   "by_scatter_window_at_32KiB_tiles": windows,
                   "by_span_of_device_memory_at_32KiB_tiles": spans,
-                  "one_direction_in_order_at_32KiB_tiles": one_way},
+                  "one_direction_in_order_at_32KiB_tiles": one_way,
+                  "by_tile_size_scattered_over_200GiB": wide_rows},
         "traffic": None,
     }
 

@@ -148,3 +148,49 @@ def test_argument_checks():
     with pytest.raises(kdn.KdnError) as e:
         kdn.kdn_compose_plan([([a], [0], _table(7), -1)], cache)
     assert e.value.status == kdn.EINVAL
+
+
+def test_plan_equals_a_plain_model_on_random_batches():
+    """The whole bookkeeping against a model written out in Python: prefix sums, one launch per
+    stored form, the order of views that share a buffer, and the chaining rule."""
+    cache = _cache()
+    G = kdn.kdn_tile_tokens(cache)
+    rng = np.random.default_rng(77)
+    pool = [_chunk(cache, 80, f) for f in (INT8, INT8, RAW, INT4)]
+    slices = [(0, 80), (0, 32), (16, 48), (16, 47), (40, 40)]
+    for case in range(60):
+        n_req = int(rng.integers(1, 7))
+        reqs, model = [], []
+        for r in range(n_req):
+            dest = int(rng.choice([0, G, 3 * G, int(rng.integers(0, 40))]))
+            views, offs, S = [], [], dest
+            for c in range(int(rng.integers(1, 5))):
+                i = int(rng.integers(0, len(pool)))
+                ts, n = slices[int(rng.integers(0, len(slices)))]
+                views.append(pool[i].slice(ts, n))
+                offs.append(int(rng.integers(-50, 50)))
+                model.append({"request": r, "chunk": c, "fmt": pool[i].fmt, "dest_token": S, "num_tokens": n,
+                              "offset": offs[-1], "key": (pool[i].data.data_ptr(), ts, n, S % G),
+                              "buf": pool[i].data.data_ptr(), "tok0": ts})
+                S += n
+            reqs.append((views, offs, _table(NB), dest))
+        want = []
+        for launch, fmt in enumerate(sorted({m["fmt"] for m in model})):
+            v = [m for m in model if m["fmt"] == fmt]
+            if n_req > 1:                                           # views of one buffer next to each other
+                v.sort(key=lambda m: (m["buf"], m["tok0"]))         # (stable: ties keep the order of the requests)
+            heads, tails, first = [], [], {}
+            for m in v:
+                (tails if m["key"] in first else heads).append(m)
+                first.setdefault(m["key"], m)
+            last = {}
+            for k, m in enumerate(heads + tails):
+                m["launch"], m["index"] = launch, len(want) + k
+                m["follows"] = last[m["key"]]["index"] if m["key"] in last else -1
+                last[m["key"]] = m
+            want += heads + tails
+        got = kdn.kdn_compose_plan(reqs, cache)
+        assert len(got) == len(want), case
+        for g, w in zip(got, want):
+            for f in ("request", "chunk", "fmt", "launch", "dest_token", "num_tokens", "offset", "follows"):
+                assert g[f] == w[f], (case, f, g, w)

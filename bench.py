@@ -52,10 +52,10 @@ FMT_IDS = {"raw": 0, "int8": 1, "int4": 2, "fp8": 3}
 # under profiles/ (the file named here), per workload; valid only for the library sources
 # they were taken with, whose fingerprint the library itself carries.
 COUNTER_TRAFFIC = {
-    "source_fingerprint": "c96e93b387acbf4c",
-    "70b_long": {"k_place_bytes_per_launch": 16274089718, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
-    "8b": {"k_place_bytes_per_launch": 813896528, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
-    "batched_reuse": {"k_place_bytes_per_launch": 41759102909, "profile": "profiles/k_place_batched_reuse_64req.md"},
+    "source_fingerprint": "f3ff674b7bb35c42",
+    "70b_long": {"k_place_bytes_per_launch": 16274061430, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
+    "8b": {"k_place_bytes_per_launch": 813897802, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
+    "batched_reuse": {"k_place_bytes_per_launch": 41348016375, "profile": "profiles/k_place_batched_reuse_64req.md"},
 }
 
 

@@ -12,7 +12,8 @@ SOURCES = [os.path.join(_PKG, "csrc", "kdn.hip"), os.path.join(_PKG, "csrc", "kd
            os.path.join(_PKG, "csrc", "kdn_pool.cpp")]
 HEADERS = [os.path.join(_ROOT, "include", "kdn.h"), os.path.join(_ROOT, "include", "kdn_pool.h"),
            os.path.join(_ROOT, "include", "kdn_arena.h"),
-           os.path.join(_PKG, "csrc", "kdn_kernels.h"), os.path.join(_PKG, "csrc", "kdn_planner.h")]
+           os.path.join(_PKG, "csrc", "kdn_kernels.h"), os.path.join(_PKG, "csrc", "kdn_planner.h"),
+           os.path.join(_PKG, "csrc", "kdn_blocklist.h")]
 LIB_PATH = os.path.join(_PKG, "libkdn.so")
 
 HIPCC_FLAGS = [

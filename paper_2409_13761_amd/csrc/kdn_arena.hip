@@ -2,6 +2,7 @@
 // only device work is the library's own bandwidth yardstick (kdn_probe_stream), used to
 // report what the striping gained.
 #include "kdn_arena.h"
+#include "kdn_blocklist.h"
 
 #include <hip/hip_runtime.h>
 
@@ -32,8 +33,7 @@ struct Arena {
     size_t bytes = 0, granule = 0;
     void *va = nullptr;
     std::vector<Handle> handles;          // one per granule, in address order
-    std::map<size_t, size_t> free_at;     // offset -> length, disjoint, never adjacent
-    std::map<size_t, size_t> used_at;     // offset -> length
+    kdn_impl::BlockList blocks;           // what is handed out
     kdn_arena_info info{};
 };
 
@@ -113,21 +113,11 @@ void release_all(std::vector<Handle> &h, const std::vector<char> *keep = nullptr
             (void)hipMemRelease(h[i]);
 }
 
-size_t largest_free(const Arena &a)
-{
-    size_t m = 0;
-    for (const auto &kv : a.free_at)
-        m = std::max(m, kv.second);
-    return m;
-}
-
 void fill_info(const Arena &a, kdn_arena_info *out)
 {
     *out = a.info;
-    out->in_use = 0;
-    for (const auto &kv : a.used_at)
-        out->in_use += kv.second;
-    out->largest_free = largest_free(a);
+    out->in_use = a.blocks.in_use();
+    out->largest_free = a.blocks.largest_free();
 }
 
 } // namespace
@@ -276,7 +266,7 @@ kdn_status kdn_arena_create(uint64_t bytes, int32_t granule_mib, kdn_arena_info 
     p.teardown();
     release_all(h, &taken);
 
-    a.free_at[0] = a.bytes;
+    a.blocks = kdn_impl::BlockList(a.bytes, kAlign);
     a.info.seconds = (float)(now() - t_start);
     if (info_out)
         fill_info(a, info_out);
@@ -298,21 +288,11 @@ kdn_status kdn_arena_alloc(uint64_t bytes, void **ptr_out)
     if (it == g_arena.end())
         return KDN_ENOTFOUND;
     Arena &a = it->second;
-    if (bytes > a.bytes)
+    size_t off = 0;
+    if (!a.blocks.take((size_t)bytes, &off))
         return KDN_ESIZE;
-    const size_t want = ((size_t)bytes + kAlign - 1) / kAlign * kAlign;
-    for (auto f = a.free_at.begin(); f != a.free_at.end(); ++f) {
-        if (f->second < want)
-            continue;
-        const size_t off = f->first, len = f->second;
-        a.free_at.erase(f);
-        if (len > want)
-            a.free_at[off + want] = len - want;
-        a.used_at[off] = want;
-        *ptr_out = static_cast<char *>(a.va) + off;
-        return KDN_OK;
-    }
-    return KDN_ESIZE;
+    *ptr_out = static_cast<char *>(a.va) + off;
+    return KDN_OK;
 }
 
 kdn_status kdn_arena_free(void *ptr_dev)
@@ -332,26 +312,7 @@ kdn_status kdn_arena_free(void *ptr_dev)
     const char *p = static_cast<const char *>(ptr_dev), *base = static_cast<const char *>(a.va);
     if (p < base || p >= base + a.bytes)
         return KDN_EINVAL;
-    auto u = a.used_at.find((size_t)(p - base));
-    if (u == a.used_at.end())
-        return KDN_EINVAL;
-    size_t off = u->first, len = u->second;
-    a.used_at.erase(u);
-    auto after = a.free_at.lower_bound(off);
-    if (after != a.free_at.end() && after->first == off + len) { // joins the free stretch behind it
-        len += after->second;
-        after = a.free_at.erase(after);
-    }
-    if (after != a.free_at.begin()) {
-        auto before = std::prev(after);
-        if (before->first + before->second == off) { // and the one in front
-            off = before->first;
-            len += before->second;
-            a.free_at.erase(before);
-        }
-    }
-    a.free_at[off] = len;
-    return KDN_OK;
+    return a.blocks.give((size_t)(p - base)) ? KDN_OK : KDN_EINVAL;
 }
 
 kdn_status kdn_arena_query(kdn_arena_info *info_out)

@@ -29,7 +29,7 @@ def test_a_library_built_from_other_sources_is_recognised(lib, tmp_path):
         c.write_bytes(open(f, "rb").read())
         copies.append(str(c))
     assert build.source_fingerprint(copies) == want and not build.is_stale(files=copies)
-    with open(copies[-2], "a") as fh:                      # csrc/kdn_kernels.h
+    with open(copies[-2], "a") as fh:                      # one of the headers under csrc/
         fh.write("// a comment\n")
     assert build.source_fingerprint(copies) != want
     assert build.is_stale(files=copies)

@@ -33,3 +33,13 @@ def test_oracle_under_sanitizers(tmp_path):
          [os.path.join(ROOT, "tests", "native", "oracle_check.c"),
           os.path.join(ROOT, "oracle", "kdn_oracle.c"), "-lm", "-o", exe])
     assert "oracle_check ok" in _run([exe], env=dict(os.environ, ASAN_OPTIONS="detect_leaks=1"))
+
+
+@pytest.mark.skipif(shutil.which("g++") is None, reason="needs g++")
+def test_arena_block_list_under_sanitizers(tmp_path):
+    """The striped arena's bookkeeping (first fit, joining of freed neighbours, refusal of
+    addresses that are no live block) needs no GPU: 60 000 random steps against a page map."""
+    exe = str(tmp_path / "blocklist_fuzz")
+    _run(["g++", "-std=c++17"] + SAN + ["-I", os.path.join(ROOT, "paper_2409_13761_amd", "csrc"),
+          os.path.join(ROOT, "tests", "native", "blocklist_fuzz.cpp"), "-o", exe])
+    assert "blocklist_fuzz ok" in _run([exe], env=dict(os.environ, ASAN_OPTIONS="detect_leaks=1"))

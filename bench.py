@@ -52,10 +52,10 @@ FMT_IDS = {"raw": 0, "int8": 1, "int4": 2, "fp8": 3}
 # under profiles/ (the file named here), per workload; valid only for the library sources
 # they were taken with, whose fingerprint the library itself carries.
 COUNTER_TRAFFIC = {
-    "source_fingerprint": "f3ff674b7bb35c42",
-    "70b_long": {"k_place_bytes_per_launch": 16274061430, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
-    "8b": {"k_place_bytes_per_launch": 813897802, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
-    "batched_reuse": {"k_place_bytes_per_launch": 41348016375, "profile": "profiles/k_place_batched_reuse_64req.md"},
+    "source_fingerprint": "dc77886253ccca53",
+    "70b_long": {"k_place_bytes_per_launch": 16274064457, "profile": "profiles/k_store_k_place_llama70b_32768tok.md"},
+    "8b": {"k_place_bytes_per_launch": 813883832, "profile": "profiles/k_place_k_store_llama8b_4096tok.md"},
+    "batched_reuse": {"k_place_bytes_per_launch": 41283790417, "profile": "profiles/k_place_batched_reuse_64req.md"},
 }
 
 
@@ -265,7 +265,7 @@ def workload_stream_probe(args, dev):
                       "read_only_scattered_GBps": _probe_rate(kdn, torch, small, [huge] * sets, tiles, span_ids, 32, 3, 0, reps)})
     # tile sizes again, now with the tiles scattered over all 200 GiB (the regime an engine-sized pool is in)
     wide_rows = []
-    for tile_kib in (8, 16, 32, 64, 256, 1024):
+    for tile_kib in (4, 8, 16, 32, 64, 256, 1024):
         n_t = (1 << 30) // (tile_kib << 10)
         wide_ids = torch.from_numpy(rng.permutation((200 << 30) // (tile_kib << 10))[:n_t].astype(np.int32)).to(dev)
         wide_rows.append({"tile_KiB": tile_kib,

@@ -436,8 +436,8 @@ kdn_status kdn_validate_block_table(const int32_t *block_table_dev, int32_t tabl
 
 /* A measuring aid, not a step of the path: moves bytes in the patterns of this library with no
  * arithmetic and no table walk, as the yardstick its kernels are held against.  A tile is
- * tile_kib KiB of big_dev and tile_kib/2 KiB of small_dev (tile_kib a multiple of 8, at most
- * 4096; 32 is the tile of the Llama shapes at block size 16).  direction 0, the pattern of load
+ * tile_kib KiB of big_dev and tile_kib/2 KiB of small_dev (tile_kib 4 or a multiple of 8, at
+ * most 4096; 32 is the tile of the Llama shapes at block size 16, 4 that of one KV head of 128).  direction 0, the pattern of load
  * and compose: a workgroup reads tile i of small_dev and writes tile i of big_dev, or, with
  * tile_ids_dev [device, `tiles` distinct int32], tile tile_ids_dev[i] (destination tiles
  * scattered like the blocks of a random block table).  direction 1, the pattern of store: reads

@@ -829,15 +829,15 @@ kdn_status kdn_probe_stream(void *small_dev, void *big_dev, const int32_t *tile_
 {
     if (!small_dev || !big_dev || tiles == 0 || max_workgroups < 0 || direction < 0 || direction > 3)
         return KDN_EINVAL;
-    if (tile_kib < 8 || tile_kib > 4096 || tile_kib % 8 != 0)
+    if (tile_kib != 4 && (tile_kib < 8 || tile_kib > 4096 || tile_kib % 8 != 0))
         return KDN_EINVAL;
     if (!aligned16(small_dev) || !aligned16(big_dev))
         return KDN_EALIGN;
-    const uint32_t chunks = (uint32_t)tile_kib / 8;
+    const uint32_t chunks = tile_kib == 4 ? 1u : (uint32_t)tile_kib / 8; // the 4 KiB tile: one run of half the width
     const uint32_t grid = max_workgroups > 0 ? std::min<uint32_t>(tiles, (uint32_t)max_workgroups) : tiles;
     hipStream_t hs = static_cast<hipStream_t>(stream);
     u32x4 *sm = static_cast<u32x4 *>(small_dev), *bg = static_cast<u32x4 *>(big_dev);
-    const dim3 g(grid), b(kThreads);
+    const dim3 g(grid), b(tile_kib == 4 ? kThreads / 2 : kThreads);
     const bool fixed = chunks == 4; // the 32 KiB tile has a kernel of its own with nothing predicated
 #define KDN_PROBE(DIR)                                                                                      \
     case DIR:                                                                                               \

@@ -889,7 +889,8 @@ __global__ void k_f32_to_bf16(const float *__restrict__ in, uint16_t *__restrict
 }
 
 // Bandwidth yardstick with the byte patterns of this library and none of its work.  A tile is
-// `chunks` * 8 KiB of the big buffer and half that of the small one.  DIR 0 (the pattern of load
+// `chunks` * 8 KiB of the big buffer and half that of the small one (launched with 128 threads
+// and chunks = 1: 4 KiB and 2 KiB, the tile of one KV head of 128).  DIR 0 (the pattern of load
 // and compose): a workgroup reads tile t of `small` (contiguous, in order) and writes tile
 // ids[t] of `big` (tile t when ids is null): with ids, destination tiles scattered like the
 // blocks of a random block table.  DIR 1 (the pattern of store): reads tile ids[t] of `big`,
@@ -906,21 +907,22 @@ __global__ __launch_bounds__(kThreads) void k_probe_stream(u32x4 *__restrict__ s
 {
     constexpr bool FULL = CH > 0; // nothing is predicated
     const uint32_t chunks = CH ? CH : chunks_arg;
+    const uint32_t NT = CH ? kThreads : blockDim.x; // lanes of a run: 256, or 128 for the 4 KiB tile (2 KiB runs)
     u32x4 seen = {0u, 0u, 0u, 0u};
     for (uint32_t t = blockIdx.x; t < tiles; t += gridDim.x) {
-        u32x4 *s = small + (size_t)t * chunks * kThreads;
+        u32x4 *s = small + (size_t)t * chunks * NT;
         const uint32_t tile = ids ? (uint32_t)ids[t] : t;
-        u32x4 *b = big + (size_t)tile * chunks * (2 * kThreads);
+        u32x4 *b = big + (size_t)tile * chunks * (2 * NT);
         for (uint32_t c0 = 0; c0 < chunks; c0 += 4) {
             u32x4 v[4], w[4];
 #pragma unroll
             for (uint32_t u = 0; u < 4; ++u) {
                 if (FULL || c0 + u < chunks) {
                     if (DIR == 0) {
-                        v[u] = __builtin_nontemporal_load(s + (c0 + u) * kThreads + threadIdx.x);
+                        v[u] = __builtin_nontemporal_load(s + (c0 + u) * NT + threadIdx.x);
                     } else if (DIR == 1 || DIR == 3) {
-                        v[u] = __builtin_nontemporal_load(b + (2 * (c0 + u)) * kThreads + threadIdx.x);
-                        w[u] = __builtin_nontemporal_load(b + (2 * (c0 + u) + 1) * kThreads + threadIdx.x);
+                        v[u] = __builtin_nontemporal_load(b + (2 * (c0 + u)) * NT + threadIdx.x);
+                        w[u] = __builtin_nontemporal_load(b + (2 * (c0 + u) + 1) * NT + threadIdx.x);
                     }
                 }
             }
@@ -930,16 +932,16 @@ __global__ __launch_bounds__(kThreads) void k_probe_stream(u32x4 *__restrict__ s
                     if (DIR == 0) {
                         u32x4 x = v[u];
                         x.x ^= 0x80008000u; // the second vector differs from the first, as an upper half row would
-                        __builtin_nontemporal_store(v[u], b + (2 * (c0 + u)) * kThreads + threadIdx.x);
-                        __builtin_nontemporal_store(x, b + (2 * (c0 + u) + 1) * kThreads + threadIdx.x);
+                        __builtin_nontemporal_store(v[u], b + (2 * (c0 + u)) * NT + threadIdx.x);
+                        __builtin_nontemporal_store(x, b + (2 * (c0 + u) + 1) * NT + threadIdx.x);
                     } else if (DIR == 1) {
-                        __builtin_nontemporal_store(v[u] ^ w[u], s + (c0 + u) * kThreads + threadIdx.x);
+                        __builtin_nontemporal_store(v[u] ^ w[u], s + (c0 + u) * NT + threadIdx.x);
                     } else if (DIR == 2) {
                         const u32x4 x = {tile, 2 * (c0 + u), threadIdx.x, kProbeMark};
                         u32x4 y = x;
                         y.y += 1;
-                        __builtin_nontemporal_store(x, b + (2 * (c0 + u)) * kThreads + threadIdx.x);
-                        __builtin_nontemporal_store(y, b + (2 * (c0 + u) + 1) * kThreads + threadIdx.x);
+                        __builtin_nontemporal_store(x, b + (2 * (c0 + u)) * NT + threadIdx.x);
+                        __builtin_nontemporal_store(y, b + (2 * (c0 + u) + 1) * NT + threadIdx.x);
                     } else {
                         seen ^= v[u] ^ w[u];
                     }
@@ -950,7 +952,7 @@ __global__ __launch_bounds__(kThreads) void k_probe_stream(u32x4 *__restrict__ s
     // keeps the loads of DIR 3 alive; the small buffer is written only if what was read folds
     // to one particular 128-bit value
     if (DIR == 3 && seen.x == kProbeMark && seen.y == ~kProbeMark && seen.z == 0x5eed5eedu && seen.w == 0xfeedf00du)
-        small[(size_t)blockIdx.x * kThreads + threadIdx.x] = seen;
+        small[(size_t)blockIdx.x * NT + threadIdx.x] = seen;
 }
 
 // Writes up to kScratchWords 32-bit words that travel in the kernel arguments to

@@ -1023,14 +1023,16 @@ def lib_store_to_host_with_device_chunk(dc, a, fmt, staging, layers_per_stage):
 
 
 # ------------------------------------------------------------------ the streaming yardstick
-@pytest.mark.parametrize("tile_kib,cap", [(8, 0), (32, 0), (32, 5), (72, 3), (256, 0)])
+@pytest.mark.parametrize("tile_kib,cap", [(4, 0), (4, 7), (8, 0), (32, 0), (32, 5), (72, 3), (256, 0)])
 def test_probe_stream_moves_the_bytes_it_is_timed_for(tile_kib, cap):
     """The yardstick kernel is only worth timing if it moves what it says: every tile of the
-    small buffer lands in the tile of the big one that the id names (each 4 KiB run twice, the
-    second copy with one bit pattern flipped per 16 bytes), nothing else is written, the
-    reverse direction folds the two copies back, the write-only direction fills exactly the
-    named tiles and the read-only one changes nothing."""
+    small buffer lands in the tile of the big one that the id names (each run of 4 KiB, 2 KiB
+    for the 4 KiB tile, twice, the second copy with one bit pattern flipped per 16 bytes),
+    nothing else is written, the reverse direction folds the two copies back, the write-only
+    direction fills exactly the named tiles and the read-only one changes nothing."""
     tiles = 37
+    run = 2048 if tile_kib == 4 else 4096                          # bytes of one run of the small buffer
+    runs = tile_kib * 512 // run                                   # runs per small tile
     rng = np.random.default_rng(500 + tile_kib)
     ids_h = rng.permutation(64)[:tiles].astype(np.int32)
     small_h = rng.integers(0, 256, size=tiles * tile_kib * 512, dtype=np.uint8)
@@ -1039,11 +1041,11 @@ def test_probe_stream_moves_the_bytes_it_is_timed_for(tile_kib, cap):
     ids = torch.from_numpy(ids_h).cuda()
     kdn.kdn_probe_stream(small, big, tiles, ids, tile_kib, 0, cap)
     torch.cuda.synchronize()
-    got = big.cpu().numpy().reshape(64, tile_kib // 8, 2, 4096)
-    src = small_h.reshape(tiles, tile_kib // 8, 4096)
-    flipped = src.copy().view(np.uint32).reshape(tiles, tile_kib // 8, 256, 4)
+    got = big.cpu().numpy().reshape(64, runs, 2, run)
+    src = small_h.reshape(tiles, runs, run)
+    flipped = src.copy().view(np.uint32).reshape(tiles, runs, run // 16, 4)
     flipped[..., 0] ^= np.uint32(0x80008000)
-    flipped = flipped.view(np.uint8).reshape(tiles, tile_kib // 8, 4096)
+    flipped = flipped.view(np.uint8).reshape(tiles, runs, run)
     assert np.array_equal(got[ids_h, :, 0], src) and np.array_equal(got[ids_h, :, 1], flipped)
     untouched = np.setdiff1d(np.arange(64), ids_h)
     assert np.all(got[untouched] == 0xA5)
@@ -1055,17 +1057,17 @@ def test_probe_stream_moves_the_bytes_it_is_timed_for(tile_kib, cap):
     big.fill_(0)
     kdn.kdn_probe_stream(small, big, tiles, None, tile_kib, 0, cap)
     torch.cuda.synchronize()
-    assert np.array_equal(big.cpu().numpy().reshape(64, tile_kib // 8, 2, 4096)[:tiles, :, 0], src)
-    # write only: every named tile holds (tile, 4 KiB run, lane, mark) per 16 bytes, the others are untouched
+    assert np.array_equal(big.cpu().numpy().reshape(64, runs, 2, run)[:tiles, :, 0], src)
+    # write only: every named tile holds (tile, run, lane, mark) per 16 bytes, the others are untouched
     big.fill_(0xA5)
     keep = small.clone()
     kdn.kdn_probe_stream(small, big, tiles, ids, tile_kib, 2, cap)
     torch.cuda.synchronize()
-    got = big.cpu().numpy().reshape(64, tile_kib // 4, 256, 16)
-    want = np.empty((tiles, tile_kib // 4, 256, 4), dtype=np.uint32)
+    got = big.cpu().numpy().reshape(64, 2 * runs, run // 16, 16)
+    want = np.empty((tiles, 2 * runs, run // 16, 4), dtype=np.uint32)
     want[..., 0] = ids_h[:, None, None]
-    want[..., 1] = np.arange(tile_kib // 4)[None, :, None]
-    want[..., 2] = np.arange(256)[None, None, :]
+    want[..., 1] = np.arange(2 * runs)[None, :, None]
+    want[..., 2] = np.arange(run // 16)[None, None, :]
     want[..., 3] = 0x4B444E21
     assert np.array_equal(got[ids_h].view(np.uint32).reshape(want.shape), want)
     assert np.all(got[untouched] == 0xA5) and torch.equal(small, keep)
@@ -1074,7 +1076,7 @@ def test_probe_stream_moves_the_bytes_it_is_timed_for(tile_kib, cap):
     kdn.kdn_probe_stream(small, big, tiles, ids, tile_kib, 3, cap)
     torch.cuda.synchronize()
     assert torch.equal(big, before) and torch.equal(small, keep)
-    for bad_tile, bad_dir in ((4, 0), (tile_kib, 4), (tile_kib, -1)):   # below the smallest tile; no such direction
+    for bad_tile, bad_dir in ((2, 0), (tile_kib, 4), (tile_kib, -1)):   # below the smallest tile; no such direction
         with pytest.raises(kdn.KdnError) as e:
             kdn.kdn_probe_stream(small, big, tiles, ids, bad_tile, bad_dir, 0)
         assert e.value.status == kdn.EINVAL
